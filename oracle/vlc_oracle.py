@@ -1,0 +1,336 @@
+"""CPU oracle for VLCache's selective-recompute prefill (arxiv 2512.12977).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference the HIP path is
+checked against.  It may be imported by tests/, by __graft_entry__.smoke() and by
+the cpu_baseline leg of bench.py, and by nothing else; it shares no code with the
+HIP library and never calls it.
+
+What it computes (Sec. 4.1 "Basic Algorithm", Sec. 4.2, Fig. 4): a request reuses the
+cached K/V of its image tokens at a new position.  In every decoder layer only the
+text tokens and the first floor(r * T) tokens of each T-token image are run through
+the layer; their fresh K/V overwrite the reused entries, reused keys are rotated to
+the new position, and causal attention is evaluated for those query rows only, over
+the whole blended key range.  Rates are non-increasing with depth (Sec. 4.1, last
+paragraph), so the rows a layer needs are always among the rows the layer above
+produced.  Per-layer rates come from a greedy allocation over a sensitivity table
+(Sec. 4.1 "Dynamic Recomputation", Eq. 6-9).
+
+The method is an approximation of full prefill by design, so there is no closed
+form for its output; the functions below follow the algorithm's steps in the
+paper's order.  All arithmetic is float64.  `store` is the rounding applied where
+the GPU path keeps a tensor in its storage type (identity for the fp32 config,
+bf16 round-to-nearest-even for the bf16 configs).
+
+Readings of points the paper leaves open are marked "reading:" where they apply.
+
+Pins (tests/test_oracle_*.py): rate 1.0 equals full prefill; exact-prefix reuse at
+rate 0 equals full prefill; the same with every position shifted by a constant;
+rope_shift(d) o rope_shift(-d) = id and composition with direct RoPE; brute-force
+dense attention on tiny inputs; planner closed forms and exhaustive optimum.
+Parity unpinned: agreement with the authors' own rate lists / prototype numerics
+(their code and tables are not available).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+GRID = 500          # rates live on the grid k/500, k integer (step 0.002; Sec. 4.1 Eq. 9)
+PLANNER_G = 150     # largest grid step the allocator may assign (rate 0.300; Eq. 9)
+
+
+# ----------------------------------------------------------------------------------------------
+# storage rounding
+# ----------------------------------------------------------------------------------------------
+def store_exact(x):
+    """Storage rounding of the fp32 configuration: none (the oracle stays in float64)."""
+    return np.asarray(x, dtype=np.float64)
+
+
+def store_bf16(x):
+    """Round float64 to the nearest bfloat16 value (ties to even); result kept as float64.
+
+    bfloat16 has 8 significant bits.  Only the normal range is handled (all tensors on this
+    path are O(1)); zeros pass through.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)                      # x = m * 2**e, 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0), e - 8)
+
+
+STORE = {"f32": store_exact, "bf16": store_bf16}
+
+
+# ----------------------------------------------------------------------------------------------
+# layer-rate allocation (Sec. 4.1, Eq. 6-9)
+# ----------------------------------------------------------------------------------------------
+def plan_layer_rates(sens, budget_steps, G=None):
+    """Greedy allocation of per-layer grid steps k_i (rate r_i = k_i / 500).
+
+    sens[i][c] is the sensitivity score of layer i at rate c/500 (column 0 = pure reuse).
+    Minimises sum_i sens[i][k_i] approximately, subject to sum_i k_i <= budget_steps,
+    k_0 >= k_1 >= ... >= k_{L-1} >= 0 and k_i <= G.
+
+    reading: the paper only says "a simple greedy algorithm".  Taken as: start from all
+    zeros; repeatedly raise by one step the layer whose next step lowers its score the
+    most, among layers that stay within G and within the monotone constraint; the drop
+    must be positive; equal drops go to the shallowest layer; stop when the budget is
+    used or no layer qualifies.
+    reading: Eq. 6 prints sum over l of S_i(r); taken as sum over i of S_i(r_i).
+    reading: the grid is printed from 0.002 but Eq. 8 allows r_L >= 0 and Sec. 3.2 says some
+    layers should recompute nothing, so step 0 is allowed.
+    """
+    sens = np.asarray(sens, dtype=np.float64)
+    L = sens.shape[0]
+    if G is None:
+        G = sens.shape[1] - 1
+    k = [0] * L
+    used = 0
+    while used < budget_steps:
+        best, best_gain = -1, 0.0
+        for i in range(L):
+            if k[i] >= G:
+                continue
+            if i > 0 and k[i] + 1 > k[i - 1]:
+                continue
+            gain = sens[i][k[i]] - sens[i][k[i] + 1]
+            if gain > best_gain:
+                best, best_gain = i, gain
+        if best < 0:
+            break
+        k[best] += 1
+        used += 1
+    return np.asarray(k, dtype=np.int32)
+
+
+def budget_steps_from_mean_rate(mean_rate_bp, L):
+    """reading: Eq. 7 bounds the *sum* of rates while the tables quote a *mean* rate; the budget
+    is given as a mean rate in basis points and converted to a total number of grid steps:
+    bp/10000 * L * 500 = bp * L / 20, rounded down."""
+    return (int(mean_rate_bp) * int(L)) // 20
+
+
+# ----------------------------------------------------------------------------------------------
+# token selection (Sec. 4.2: first floor(r*T) tokens of each image; Sec. 4.1: query tokens and
+# selected tokens are concatenated)
+# ----------------------------------------------------------------------------------------------
+def leading_count(k, T):
+    """floor(r * T) with r = k/500, in integer arithmetic."""
+    return (int(k) * int(T)) // GRID
+
+
+def select_slots(segments, counts):
+    """Slots (relative to the request start, ascending) recomputed in one layer.
+
+    counts[j] = number of leading tokens of the j-th *image* segment to recompute.
+    reading: every non-image slot is recomputed in every layer, wherever it sits.
+    """
+    out, j = [], 0
+    for seg in segments:
+        if seg.is_image:
+            out.extend(range(seg.start, seg.start + counts[j]))
+            j += 1
+        else:
+            out.extend(range(seg.start, seg.start + seg.length))
+    return np.asarray(out, dtype=np.int64)
+
+
+def image_counts(segments, k=None, explicit=None):
+    """Per-image leading-token counts for one layer from a grid step k or an explicit count."""
+    res = []
+    for seg in segments:
+        if seg.is_image:
+            res.append(min(seg.length, explicit) if explicit is not None else leading_count(k, seg.length))
+    return res
+
+
+def reused_slots(segments, counts):
+    """(slot, cache_row, delta) of every image token that is NOT recomputed in this layer, where
+    delta = new position - position the cached key was rotated at.  Positions are slot indices
+    (plus the request's pos_start, which cancels in delta only if the cache used the same origin;
+    the caller adds pos_start to `slot` when forming delta)."""
+    slot, row, old = [], [], []
+    j = 0
+    for seg in segments:
+        if not seg.is_image:
+            continue
+        for t in range(counts[j], seg.length):
+            slot.append(seg.start + t)
+            row.append(seg.cache_row + t)
+            old.append(seg.old_pos + t)
+        j += 1
+    return (np.asarray(slot, dtype=np.int64), np.asarray(row, dtype=np.int64),
+            np.asarray(old, dtype=np.int64))
+
+
+# ----------------------------------------------------------------------------------------------
+# rotary position embedding
+# ----------------------------------------------------------------------------------------------
+def rope_angles(pos, D, base):
+    """angle[t, i] = pos[t] * base**(-2 i / D), i in [0, D/2)."""
+    i = np.arange(D // 2, dtype=np.float64)
+    inv_freq = np.power(np.float64(base), -2.0 * i / D)
+    return np.asarray(pos, dtype=np.float64)[:, None] * inv_freq[None, :]
+
+
+def rope_rotate(x, pos, base):
+    """Rotate x[t, head, :] by the angles of position pos[t] (may be negative).
+
+    reading: the paper does not give the pairing; the Qwen-family convention is used: element i
+    pairs with element i + D/2;  lo' = lo cos - hi sin,  hi' = hi cos + lo sin.
+    Because rotations compose, calling this on keys that were already rotated at position q with
+    pos = p - q leaves them rotated at p (Sec. 4.2 stores keys un-rotated, i.e. q = 0).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    D = x.shape[-1]
+    half = D // 2
+    ang = rope_angles(pos, D, base)
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+
+# ----------------------------------------------------------------------------------------------
+# decoder layer pieces
+# ----------------------------------------------------------------------------------------------
+def rmsnorm(x, w, eps):
+    x = np.asarray(x, dtype=np.float64)
+    return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps) * np.asarray(w, dtype=np.float64)
+
+
+def silu(x):
+    return x / (1.0 + np.exp(-x))
+
+
+def attention_rows(q, K, V, kv_len, scale):
+    """o[i, h] = softmax(scale * q[i, h] . K[0:kv_len[i], h // g]) @ V[0:kv_len[i], h // g].
+
+    q [n, Hq, D]; K, V [S, Hkv, D]; kv_len[i] = number of leading slots row i may see
+    (its own slot + 1: causal in slot order).  Rows with kv_len 0 give zeros.
+    Fig. 4: only the rows of recomputed tokens are evaluated, each over its whole key range.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    n, Hq, D = q.shape
+    S, Hkv, _ = K.shape
+    g = Hq // Hkv
+    kv_len = np.asarray(kv_len, dtype=np.int64)
+    visible = np.arange(S)[None, :] < kv_len[:, None]           # [n, S]
+    out = np.zeros((n, Hq, D), dtype=np.float64)
+    for h in range(Hq):
+        s = (q[:, h, :] @ K[:, h // g, :].T) * scale             # [n, S]
+        s = np.where(visible, s, -np.inf)
+        m = np.max(s, axis=1, keepdims=True)
+        m = np.where(np.isfinite(m), m, 0.0)
+        p = np.exp(s - m)
+        den = np.sum(p, axis=1, keepdims=True)
+        p = np.where(den > 0, p / np.where(den > 0, den, 1.0), 0.0)
+        out[:, h, :] = p @ V[:, h // g, :]
+    return out
+
+
+def linear(x, w, b=None):
+    y = np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
+    if b is not None:
+        y = y + np.asarray(b, dtype=np.float64)
+    return y
+
+
+def layer_forward(shape, W, x, slots, pos, K, V, store):
+    """One decoder layer for the query rows `slots` of one request.
+
+    x      [n, H]  hidden states of those rows (already gathered, storage-rounded)
+    slots  [n]     their slot indices (ascending)
+    pos    [n]     their position ids
+    K, V   [S, Hkv, D]  the request's keys/values for this layer with every slot that is NOT in
+           `slots` already filled (reused image tokens, rotated to their new position); rows at
+           `slots` are overwritten here with the fresh k, v  (the blend of Sec. 4.2).
+    Returns (h_out [n, H], K, V) with K, V updated in place.
+
+    reading (decoder details, which the paper leaves to the Qwen family): pre-norm RMSNorm,
+    fused q|k|v projection with optional bias, rotate-half RoPE on q and k, grouped-query
+    attention scaled by 1/sqrt(D), output projection + residual, SwiGLU MLP + residual.
+    reading (storage rounding of the bf16 path): normed activations, q/k/v after bias, q/k after
+    RoPE, attention output, both residual sums and the SwiGLU product are rounded to the storage
+    type; gate and up projections are not rounded before the product.
+    """
+    Hq, Hkv, D = shape.Hq, shape.Hkv, shape.D
+    n = x.shape[0]
+    x = np.asarray(x, dtype=np.float64)
+    xn = store(rmsnorm(x, W["w_ln1"], shape.eps))
+    qkv = store(linear(xn, W["w_qkv"], W.get("b_qkv")))
+    q = qkv[:, :Hq * D].reshape(n, Hq, D)
+    k = qkv[:, Hq * D:(Hq + Hkv) * D].reshape(n, Hkv, D)
+    v = qkv[:, (Hq + Hkv) * D:].reshape(n, Hkv, D)
+    q = store(rope_rotate(q, pos, shape.rope_base))
+    k = store(rope_rotate(k, pos, shape.rope_base))
+    K[slots] = k
+    V[slots] = v
+    o = store(attention_rows(q, K, V, np.asarray(slots) + 1, 1.0 / np.sqrt(D)))
+    h1 = store(x + linear(o.reshape(n, Hq * D), W["w_o"]))
+    n2 = store(rmsnorm(h1, W["w_ln2"], shape.eps))
+    gu = linear(n2, W["w_gate_up"])
+    act = store(silu(gu[:, :shape.I]) * gu[:, shape.I:])
+    h2 = store(h1 + linear(act, W["w_down"]))
+    return h2, K, V
+
+
+def blended_kv_before_scatter(shape, request, counts, Kc, Vc, store):
+    """K, V [S, Hkv, D] of one layer with the reused image tokens filled in: keys rotated by
+    (new position - cached position), values copied; all other slots zero (they are overwritten
+    by fresh k, v in layer_forward).  Sec. 4.2: reused tokens take their K/V from the cache and
+    RoPE is applied for the new position."""
+    S = request.S
+    K = np.zeros((S, shape.Hkv, shape.D), dtype=np.float64)
+    V = np.zeros((S, shape.Hkv, shape.D), dtype=np.float64)
+    slot, row, old = reused_slots(request.segments, counts)
+    if slot.size:
+        delta = (request.pos_start + slot) - old
+        K[slot] = store(rope_rotate(np.asarray(Kc, dtype=np.float64)[row], delta, shape.rope_base))
+        V[slot] = np.asarray(Vc, dtype=np.float64)[row]
+    return K, V
+
+
+def selective_prefill(shape, weights, emb, request, counts_per_layer, cache, store):
+    """Selective-recompute prefill of one request through all layers.
+
+    weights[l]           dict of layer l (torch-Linear layout [out, in])
+    emb [S, H]           input hidden rows of every slot of the request
+    counts_per_layer[l]  per-image leading-token counts of layer l (non-increasing in l)
+    cache[l] = (Kc, Vc)  cached image K/V pools of layer l
+    Returns a list over layers of dicts {slots, h, K, V}: recomputed slots, their output hidden
+    rows, and the blended K/V of that layer.
+    """
+    emb = store(emb)
+    out = []
+    prev_slots = np.arange(request.S, dtype=np.int64)
+    prev_h = emb
+    for l, W in enumerate(weights):
+        counts = counts_per_layer[l]
+        slots = select_slots(request.segments, counts)
+        # rows of this layer are a subset of the rows the previous layer produced (Sec. 4.1)
+        where = np.searchsorted(prev_slots, slots)
+        if where.size and (where.max() >= prev_slots.size or np.any(prev_slots[where] != slots)):
+            raise ValueError("layer %d recomputes a token the previous layer dropped" % l)
+        x = prev_h[where]
+        Kc, Vc = cache[l]
+        K, V = blended_kv_before_scatter(shape, request, counts, store(Kc), store(Vc), store)
+        h, K, V = layer_forward(shape, W, x, slots, request.pos_start + slots, K, V, store)
+        out.append({"slots": slots, "h": h, "K": K, "V": V})
+        prev_slots, prev_h = slots, h
+    return out
+
+
+def full_prefill(shape, weights, emb, request, store):
+    """Ordinary causal prefill of every slot (the cache-miss path of Sec. 4.1, and the
+    'r = 1.0 (full-recompute)' column of the accuracy tables)."""
+    S = request.S
+    slots = np.arange(S, dtype=np.int64)
+    h = store(emb)
+    out = []
+    for W in weights:
+        K = np.zeros((S, shape.Hkv, shape.D), dtype=np.float64)
+        V = np.zeros((S, shape.Hkv, shape.D), dtype=np.float64)
+        h, K, V = layer_forward(shape, W, h, slots, request.pos_start + slots, K, V, store)
+        out.append({"slots": slots, "h": h, "K": K, "V": V})
+    return out

@@ -1,0 +1,15 @@
+"""Seeded synthetic inputs for the selective-recompute prefill path.
+
+This module only *describes* workloads (shapes, segment layouts) and draws
+random numbers.  It holds none of the method's arithmetic: no RoPE, no index
+selection, no attention, no rounding to storage types.  Both the CPU oracle's
+tests and the HIP path's tests/benchmark take their inputs from here, so the
+two sides see identical data without sharing any computation.
+"""
+from .workloads import (Shape, Segment, Request, Workload, SHAPES, make_workload,
+                        layer_weights, embedding_rows, cached_kv, sensitivity_table,
+                        normal_f32, WEIGHT_NAMES)
+
+__all__ = ["Shape", "Segment", "Request", "Workload", "SHAPES", "make_workload",
+           "layer_weights", "embedding_rows", "cached_kv", "sensitivity_table",
+           "normal_f32", "WEIGHT_NAMES"]
