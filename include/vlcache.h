@@ -1,0 +1,251 @@
+/*
+ * vlcache.h - C ABI of the selective-recompute prefill library for MI355X (gfx950).
+ *
+ * The library implements the per-layer hot path of VLCache (arxiv 2512.12977): a cached
+ * image's vision-token K/V is reused at a new, non-prefix position and only the text tokens
+ * plus a leading fraction of each image's tokens are recomputed in every decoder layer
+ * (Sec. 4.1 "Basic Algorithm", Sec. 4.2, Fig. 4).
+ *
+ * Conventions
+ *   - Every function returns VLC_OK (0) or a VLC_ERR_* code; vlc_last_error() gives the text of
+ *     the calling thread's last failure.  Nothing throws across this boundary.
+ *   - The caller owns all memory.  The library never allocates or frees device memory; scratch
+ *     space is a caller-provided workspace sized by vlc_layer_workspace_bytes().
+ *   - "host" pointers are read/written by the CPU inside the call.  "device" pointers are only
+ *     handed to kernels.  Device functions enqueue work on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and return without synchronising.
+ *   - Tensors are dense, row-major.  dtype is VLC_F32 or VLC_BF16 and applies to every tensor
+ *     of a call (weights included).  Index arrays are int32.
+ *   - K/V storage is token-major: [rows, Hkv, D] per layer.  Linear weights use the
+ *     [out_features, in_features] layout.
+ *   - A call with zero rows is a no-op that returns VLC_OK.
+ *   - Contents of device index arrays are the caller's contract (in range; scatter targets
+ *     unique); the host-side builders below produce arrays that satisfy it.
+ */
+#ifndef VLCACHE_H_
+#define VLCACHE_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  VLC_OK = 0,
+  VLC_ERR_NULL = 1,       /* a required pointer is NULL */
+  VLC_ERR_SHAPE = 2,      /* a size is negative, zero where it must not be, or unsupported */
+  VLC_ERR_DTYPE = 3,      /* dtype is not VLC_F32 / VLC_BF16 */
+  VLC_ERR_INDEX = 4,      /* a host-side index / segment description is inconsistent */
+  VLC_ERR_WORKSPACE = 5,  /* workspace too small or misaligned */
+  VLC_ERR_HIP = 6,        /* a HIP runtime call failed (text in vlc_last_error) */
+  VLC_ERR_INFEASIBLE = 7  /* the requested plan violates the method's constraints */
+};
+
+enum { VLC_F32 = 0, VLC_BF16 = 1 };
+
+/* Rates live on the grid k/500 (step 0.002, Sec. 4.1 Eq. 9). */
+#define VLC_RATE_GRID 500
+/* Largest grid step the allocator assigns (rate 0.300, Sec. 4.1 Eq. 9). */
+#define VLC_PLANNER_MAX_STEP 150
+
+const char* vlc_last_error(void);
+int vlc_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Host-side planning
+ * ---------------------------------------------------------------------------------------- */
+
+/*
+ * Layer-aware budget allocation (Sec. 4.1 "Dynamic Recomputation", Eq. 6-9): choose grid
+ * steps k[0..L) (rate k/500) that approximately minimise sum_i sens[i][k_i] subject to
+ * sum_i k_i <= budget_steps, k_0 >= k_1 >= ... >= k_{L-1} >= 0 and k_i <= G.
+ * Greedy: from all zeros, repeatedly add one step to the layer whose score drops the most,
+ * among layers that stay <= G and keep the sequence non-increasing; the drop must be > 0;
+ * equal drops go to the lowest layer index; stops when the budget is spent or no layer
+ * qualifies.  The result is unique.
+ *   sens   host, [L][G+1] doubles, column c = score of that layer at rate c/500
+ *   k_out  host, [L] int32, written
+ * Errors: NULL pointers, L <= 0, G <= 0 or G > VLC_RATE_GRID, budget_steps < 0.
+ */
+int vlc_plan_layer_rates(int L, int G, const double* sens, int64_t budget_steps, int32_t* k_out);
+
+/*
+ * One run of consecutive slots of a request inside the packed K/V of a batch.
+ *   start      first packed slot of the run
+ *   length     number of tokens
+ *   is_image   non-zero: vision tokens whose K/V are available in the cache pool
+ *   pos        position id of the run's first token in the new request
+ *   old_pos    position id the cached key of the run's first token was rotated at (0 for keys
+ *              stored before RoPE, Sec. 4.2)
+ *   cache_row  row of the run's first token in the cache pool
+ *   kv_start   first packed slot of the request this run belongs to
+ * Runs must be given in ascending slot order, must not overlap, and the runs of one request
+ * must be adjacent.
+ */
+typedef struct {
+  int32_t start, length, is_image, pos, old_pos, cache_row, kv_start;
+} vlc_segment;
+
+/*
+ * Token selection for every layer (Sec. 4.2: the first floor(r*T) tokens of each T-token
+ * image are recomputed; Sec. 4.1: they are concatenated with the text tokens; rates must not
+ * increase with depth so that each layer's rows exist in the layer above).
+ *   k          host [L], grid step of each layer, 0..500; count = (k*T) / 500 (integer floor)
+ *   count_override host [L] or NULL: if given, layer l recomputes min(T, count_override[l])
+ *              leading tokens of every image instead (k is then ignored and may be NULL)
+ *   cap        row capacity of each per-layer output array
+ * Outputs (host, int32, [L][cap] unless noted; only the first n_rows[l] entries are written):
+ *   n_rows [L] number of recomputed rows
+ *   slot       packed slot of each recomputed row, ascending
+ *   map        index of that row in the previous layer's row list (layer 0: the packed slot
+ *              itself, i.e. the row of the input embedding matrix)
+ *   pos        position id of the row
+ *   kv_start   first packed slot of the row's request
+ *   kv_len     number of leading slots of its request the row attends to (slot-kv_start+1)
+ * Any output pointer except n_rows may be NULL to skip it.
+ * Errors: VLC_ERR_INDEX for malformed segments, VLC_ERR_INFEASIBLE if a layer would recompute
+ * more tokens of some image than the layer above, VLC_ERR_SHAPE if cap is too small.
+ */
+int vlc_plan_token_indices(int n_seg, const vlc_segment* seg, int L, const int32_t* k,
+                           const int32_t* count_override, int64_t cap, int32_t* n_rows,
+                           int32_t* slot, int32_t* map, int32_t* pos, int32_t* kv_start,
+                           int32_t* kv_len);
+
+/*
+ * The complementary list: image tokens that are reused (not recomputed) in each layer, with the
+ * cache-pool row they come from, the packed slot they go to, and the position delta
+ * (new position - old_pos) their cached key must be rotated by (Sec. 4.2).
+ * Outputs host int32 [L][cap], first n_reuse[l] entries written; same k / count_override rules.
+ */
+int vlc_plan_reuse_rows(int n_seg, const vlc_segment* seg, int L, const int32_t* k,
+                        const int32_t* count_override, int64_t cap, int32_t* n_reuse,
+                        int32_t* src_row, int32_t* dst_slot, int32_t* delta);
+
+/* ------------------------------------------------------------------------------------------
+ * Device kernels of the hot path (all pointers below are DEVICE pointers unless noted)
+ * ---------------------------------------------------------------------------------------- */
+
+/*
+ * Row gather: dst[i, :] = src[idx[i], :], i in [0, n)  (Sec. 4.2: the computation mask indexes
+ * the input hidden states and only the selected rows go on).
+ *   src [src_rows, row_elems], dst [n, row_elems]; row_elems * elem size must be a multiple of 16.
+ */
+int vlc_gather_rows(const void* src, int64_t src_rows, int64_t row_elems, const int32_t* idx,
+                    int64_t n, void* dst, int dtype, void* stream);
+
+/*
+ * Re-rotate reused keys to their new position and place reused K/V into the request's K/V
+ * (Sec. 4.2: K/V are stored position-free and RoPE is applied for the new position; with keys
+ * stored already rotated at old_pos the same rotation by delta = new - old applies, because
+ * rotations compose).
+ *   k_dst[dst_row[t]] = R(delta[t]) * k_src[src_row[t]]     t in [0, n_tok)
+ *   v_dst[dst_row[t]] = v_src[src_row[t]]                   (skipped if v_src or v_dst is NULL)
+ * R(d) rotates the pair (x[i], x[i + D/2]) of every head by the angle d * rope_base^(-2i/D):
+ *   lo' = lo cos - hi sin, hi' = hi cos + lo sin.  delta may be negative.
+ * k_src/v_src [src_rows, Hkv, D], k_dst/v_dst [dst_rows, Hkv, D].  In-place use
+ * (k_dst == k_src with dst_row[t] == src_row[t]) is allowed; any other overlap is not.
+ * Angles are formed in double precision and reduced before the float sine/cosine.
+ * D must be 64 or 128.
+ */
+int vlc_rope_shift_kv(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
+                      const int32_t* src_row, const int32_t* dst_row, const int32_t* delta,
+                      int64_t n_tok, int Hkv, int D, double rope_base, int dtype, void* stream);
+
+/*
+ * KV blend (Sec. 4.2 "fine-grained KV cache reuse"): fresh K/V rows of the recomputed tokens
+ * overwrite their slots.  k_cache[dst_row[i]] = k_new[i], v_cache[dst_row[i]] = v_new[i].
+ *   k_new, v_new [n, Hkv, D]; k_cache, v_cache [cache_rows, Hkv, D]; dst_row entries unique.
+ */
+int vlc_scatter_kv(const void* k_new, const void* v_new, const int32_t* dst_row, int64_t n,
+                   void* k_cache, void* v_cache, int64_t cache_rows, int Hkv, int D, int dtype,
+                   void* stream);
+
+/*
+ * Attention for the recomputed query rows only, against the whole blended K/V (Fig. 4):
+ *   out[i, h] = softmax_j( scale * q[i, h] . K[s_i + j, h / g] ) @ V[s_i + j, h / g],
+ *   j in [0, row_kv_len[i]),  s_i = row_kv_start[i],  g = Hq / Hkv.
+ * Rows with row_kv_len 0 produce zeros.  Rows of one request (equal row_kv_start) must be
+ * adjacent; lengths need not be sorted.
+ *   q, out [n, Hq, D]; k_cache, v_cache [*, Hkv, D].  D must be 64 or 128 (bf16: 128 only).
+ * bf16: scores and softmax in float, probabilities rounded to bf16 before the PV product.
+ */
+int vlc_sparse_q_attention(const void* q, const void* k_cache, const void* v_cache,
+                           const int32_t* row_kv_start, const int32_t* row_kv_len, int64_t n,
+                           int Hq, int Hkv, int D, float scale, void* out, int dtype,
+                           void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * One decoder layer of the selective-recompute prefill
+ * ---------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t H, Hq, Hkv, D, I;   /* hidden, query heads, kv heads, head dim, MLP width */
+  int32_t dtype;              /* VLC_F32 | VLC_BF16 */
+  float eps;                  /* RMSNorm epsilon */
+  double rope_base;
+} vlc_layer_shape;
+
+typedef struct {              /* device pointers; b_qkv may be NULL (no bias) */
+  const void* w_ln1;          /* [H] */
+  const void* w_qkv;          /* [(Hq+2Hkv)*D, H], rows: q heads, k heads, v heads */
+  const void* b_qkv;          /* [(Hq+2Hkv)*D] or NULL */
+  const void* w_o;            /* [H, Hq*D] */
+  const void* w_ln2;          /* [H] */
+  const void* w_gate_up;      /* [2I, H], rows: gate then up */
+  const void* w_down;         /* [H, I] */
+} vlc_layer_weights;
+
+typedef struct {
+  int64_t n_in;                 /* rows of h_in (the previous layer's output rows) */
+  int64_t n;                    /* rows recomputed by this layer */
+  const int32_t* map;           /* device [n]: row of h_in each recomputed row comes from */
+  const int32_t* slot;          /* device [n]: packed K/V slot of each row (scatter target) */
+  const int32_t* pos;           /* device [n]: position id of each row */
+  const int32_t* row_kv_start;  /* device [n] */
+  const int32_t* row_kv_len;    /* device [n] */
+  int64_t kv_rows;              /* rows of k_cache / v_cache */
+  int64_t n_reuse;              /* reused image tokens to place before attention (may be 0) */
+  const int32_t* reuse_src;     /* device [n_reuse]: row in k_pool / v_pool */
+  const int32_t* reuse_dst;     /* device [n_reuse]: packed slot in k_cache / v_cache */
+  const int32_t* reuse_delta;   /* device [n_reuse]: new position - cached position */
+  const void* k_pool;           /* device [pool_rows, Hkv, D] cached image keys of this layer */
+  const void* v_pool;           /* device [pool_rows, Hkv, D] */
+  int64_t pool_rows;
+} vlc_layer_plan;
+
+/* Bytes of workspace vlc_layer_forward needs for up to n_rows_max recomputed rows (0 on error). */
+int64_t vlc_layer_workspace_bytes(const vlc_layer_shape* shape, int64_t n_rows_max);
+
+/*
+ * Where the intermediate results of the last vlc_layer_forward call with n_rows recomputed rows
+ * live inside its workspace (byte offsets; for tests and profilers, which check each stage of the
+ * layer in place).  offsets (host, [VLC_WS_FIELDS]): input-normed rows [n,H]; q|k|v projection
+ * before RoPE as float [n,(Hq+2Hkv)D]; rotated queries [n,Hq,D]; attention output [n,Hq,D];
+ * hidden after the attention residual [n,H]; post-attention-normed rows [n,H]; SwiGLU product
+ * [n,I].  All but the second have the layer's storage type.
+ */
+#define VLC_WS_FIELDS 7
+int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t n_rows, int64_t* offsets);
+
+/*
+ * One layer (Sec. 4.1 "Basic Algorithm" / Sec. 4.2; decoder details follow the Qwen family the
+ * paper evaluates): for the n recomputed rows
+ *   x  = h_in[map]                       gather of the retained rows
+ *   q,k,v = RMSNorm(x) Wqkv^T + b ;  RoPE(q), RoPE(k) at pos
+ *   K/V: reused image tokens placed (keys rotated by reuse_delta), then K[slot]=k, V[slot]=v
+ *   a  = attention of the n rows over K/V[row_kv_start : row_kv_start + row_kv_len)
+ *   h1 = x + a Wo^T ;  h_out = h1 + (silu(n2 Wg^T) * (n2 Wu^T)) Wd^T,  n2 = RMSNorm(h1)
+ * h_in [n_in, H], h_out [n, H] (must not alias h_in), k_cache/v_cache [kv_rows, Hkv, D] updated
+ * in place.  Storage rounding for VLC_BF16: normed activations, v after bias, q and k after
+ * RoPE (rounded once: the projection is rotated as float), attention output, both residual sums
+ * and the SwiGLU product are bf16; accumulation, softmax, RoPE and norms are computed in float.  workspace must be 256-byte aligned.
+ * Supported: D in {64,128} for VLC_F32, D == 128 for VLC_BF16; H, I, Hq*D multiples of 64.
+ */
+int vlc_layer_forward(const vlc_layer_shape* shape, const vlc_layer_weights* weights,
+                      const vlc_layer_plan* plan, const void* h_in, void* h_out, void* k_cache,
+                      void* v_cache, void* workspace, int64_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VLCACHE_H_ */

@@ -236,8 +236,11 @@ def linear(x, w, b=None):
     return y
 
 
-def layer_forward(shape, W, x, slots, pos, K, V, store):
-    """One decoder layer for the query rows `slots` of one request.
+STAGES = ("xn", "qkv", "q", "K", "V", "o", "h1", "n2", "act", "h2")
+
+
+def layer_stages(shape, W, x, slots, pos, K, V, store, forced=None):
+    """One decoder layer for the query rows `slots` of one request; returns every stage's result.
 
     x      [n, H]  hidden states of those rows (already gathered, storage-rounded)
     slots  [n]     their slot indices (ascending)
@@ -245,34 +248,51 @@ def layer_forward(shape, W, x, slots, pos, K, V, store):
     K, V   [S, Hkv, D]  the request's keys/values for this layer with every slot that is NOT in
            `slots` already filled (reused image tokens, rotated to their new position); rows at
            `slots` are overwritten here with the fresh k, v  (the blend of Sec. 4.2).
-    Returns (h_out [n, H], K, V) with K, V updated in place.
+    forced optional dict stage-name -> array: where present, the NEXT stage is fed this value
+           instead of the one computed here (used by tests to check each stage of another
+           implementation against this one on identical inputs).
+    Returns a dict with the stages named in STAGES; K and V are the blended caches (updated in place).
 
     reading (decoder details, which the paper leaves to the Qwen family): pre-norm RMSNorm,
     fused q|k|v projection with optional bias, rotate-half RoPE on q and k, grouped-query
     attention scaled by 1/sqrt(D), output projection + residual, SwiGLU MLP + residual.
-    reading (storage rounding of the bf16 path): normed activations, q/k/v after bias, q/k after
-    RoPE, attention output, both residual sums and the SwiGLU product are rounded to the storage
-    type; gate and up projections are not rounded before the product.
+    reading (storage rounding of the bf16 path): the weights themselves (they are tensors of the
+    storage type), normed activations, v after bias, q and k after
+    RoPE (once: the projection result is rotated unrounded), attention output, both residual sums
+    and the SwiGLU product are rounded to the storage type; gate and up projections are not
+    rounded before the product.
     """
     Hq, Hkv, D = shape.Hq, shape.Hkv, shape.D
     n = x.shape[0]
+    forced = forced or {}
+    fed = lambda name, value: np.asarray(forced[name], dtype=np.float64) if name in forced else value
+    r = {}
     x = np.asarray(x, dtype=np.float64)
-    xn = store(rmsnorm(x, W["w_ln1"], shape.eps))
-    qkv = store(linear(xn, W["w_qkv"], W.get("b_qkv")))
-    q = qkv[:, :Hq * D].reshape(n, Hq, D)
-    k = qkv[:, Hq * D:(Hq + Hkv) * D].reshape(n, Hkv, D)
-    v = qkv[:, (Hq + Hkv) * D:].reshape(n, Hkv, D)
-    q = store(rope_rotate(q, pos, shape.rope_base))
-    k = store(rope_rotate(k, pos, shape.rope_base))
+    W = {name: (None if w is None else store(w)) for name, w in W.items()}
+    r["xn"] = store(rmsnorm(x, W["w_ln1"], shape.eps))
+    r["qkv"] = linear(fed("xn", r["xn"]), W["w_qkv"], W.get("b_qkv"))
+    qkv = fed("qkv", r["qkv"])
+    r["q"] = store(rope_rotate(qkv[:, :Hq * D].reshape(n, Hq, D), pos, shape.rope_base))
+    k = store(rope_rotate(qkv[:, Hq * D:(Hq + Hkv) * D].reshape(n, Hkv, D), pos, shape.rope_base))
+    v = store(qkv[:, (Hq + Hkv) * D:].reshape(n, Hkv, D))
     K[slots] = k
     V[slots] = v
-    o = store(attention_rows(q, K, V, np.asarray(slots) + 1, 1.0 / np.sqrt(D)))
-    h1 = store(x + linear(o.reshape(n, Hq * D), W["w_o"]))
-    n2 = store(rmsnorm(h1, W["w_ln2"], shape.eps))
-    gu = linear(n2, W["w_gate_up"])
-    act = store(silu(gu[:, :shape.I]) * gu[:, shape.I:])
-    h2 = store(h1 + linear(act, W["w_down"]))
-    return h2, K, V
+    r["K"], r["V"] = K, V
+    r["o"] = store(attention_rows(fed("q", r["q"]), fed("K", K), fed("V", V), np.asarray(slots) + 1,
+                                  1.0 / np.sqrt(D)))
+    r["h1"] = store(x + linear(fed("o", r["o"]).reshape(n, Hq * D), W["w_o"]))
+    h1 = fed("h1", r["h1"])
+    r["n2"] = store(rmsnorm(h1, W["w_ln2"], shape.eps))
+    gu = linear(fed("n2", r["n2"]), W["w_gate_up"])
+    r["act"] = store(silu(gu[:, :shape.I]) * gu[:, shape.I:])
+    r["h2"] = store(h1 + linear(fed("act", r["act"]), W["w_down"]))
+    return r
+
+
+def layer_forward(shape, W, x, slots, pos, K, V, store):
+    """layer_stages without the intermediate results: (h_out [n, H], K, V)."""
+    r = layer_stages(shape, W, x, slots, pos, K, V, store)
+    return r["h2"], r["K"], r["V"]
 
 
 def blended_kv_before_scatter(shape, request, counts, Kc, Vc, store):

@@ -1,0 +1,376 @@
+// Attention for the recomputed query rows only, over the whole blended K/V of their request
+// (Fig. 4 of the paper: row blocks of the recomputed tokens, each spanning its full causal key range).
+//   bf16: MFMA flash-style kernel, one workgroup per (block of query rows, kv head); the g = Hq/Hkv
+//         query heads that share a kv head are stacked into the same tile so K/V are streamed once
+//         for all of them.
+//   f32 : one wavefront per (row, head), online softmax (the small fp32 configuration).
+#include <hip/hip_runtime.h>
+
+#include "vlc_internal.h"
+
+namespace vlc {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {   // round to nearest, ties to even
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32_to_bf16(a) | (f32_to_bf16(b) << 16); }
+
+// ---------------------------------------------------------------------------------------------
+// bf16 MFMA kernel, D = 128
+// ---------------------------------------------------------------------------------------------
+// Tile: VR = 128 "virtual rows" = (query row, head of the kv group) pairs, head fastest; 4 wavefronts
+// of 32 virtual rows each.  Keys are consumed in blocks of 64.
+//
+// Both products are computed transposed so that every lane owns exactly one virtual row:
+//   S^T[key, vr] = K[key, :] . Q[vr, :]      MFMA A = K fragment (LDS), B = Q fragment (registers)
+//   O^T[d,  vr] += V^T[d, key] P^T[key, vr]  MFMA A = V^T fragment (LDS), B = P^T (from S^T registers)
+// In the 32x32 accumulator layout lane l holds column vr = l % 32 and rows 8*(j/4) + 4*(l/32) + j%4,
+// so a row's running max / sum / rescale factor are per-lane scalars and the only cross-lane step is
+// one exchange between lanes l and l^32.  The S^T accumulators feed the second MFMA directly: its
+// contraction index is just a relabeling of keys, as long as the V^T fragment uses the same
+// relabeling, which is how V^T is laid out in LDS (see v_pos below).
+constexpr int ATT_D = 128;
+constexpr int KB = 64;        // keys per block
+constexpr int VR = 128;       // virtual rows per workgroup
+
+// K tile in LDS: [64 keys][16 chunks of 8 d], chunk XOR-swizzled by the key.
+__device__ __forceinline__ int k_off(int key, int chunk) { return key * 16 + (chunk ^ (key & 15)); }
+// V^T tile in LDS: [128 d][8 chunks of 8 key positions], chunk swizzled by d.
+__device__ __forceinline__ int vt_chunk(int d, int chunk) { return chunk ^ ((d & 7) ^ ((d >> 3) & 7)); }
+
+__global__ __launch_bounds__(256) void attention_bf16_kernel(
+    const uint16_t* __restrict__ q, int64_t q_stride, const uint16_t* __restrict__ kc,
+    const uint16_t* __restrict__ vc, const int32_t* __restrict__ row_kv_start,
+    const int32_t* __restrict__ row_kv_len, int n, int Hq, int Hkv, int g, int rows_per_tile,
+    float scale_log2, uint16_t* __restrict__ out) {
+  __shared__ u32x4 ldsK[KB * 16];            // 16 KB
+  __shared__ u32x4 ldsV[ATT_D * 8];          // 16 KB, transposed
+  __shared__ int s_start[VR];
+  __shared__ int s_len[VR];
+  __shared__ int s_red[4];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, x = lane >> 5;
+  const int kvh = blockIdx.y;
+  const int row0 = blockIdx.x * rows_per_tile;
+  const int rows_here = min(rows_per_tile, n - row0);
+
+  if (tid < rows_per_tile) {
+    const bool ok = tid < rows_here;
+    s_start[tid] = ok ? row_kv_start[row0 + tid] : -1;
+    s_len[tid] = ok ? row_kv_len[row0 + tid] : 0;
+  }
+  __syncthreads();
+
+  // this lane's virtual row
+  const int vr = wave * 32 + l32;
+  const int r_local = vr / g;
+  const int head = kvh * g + (vr - r_local * g);
+  const bool vr_ok = r_local < rows_here;
+  const int my_len = vr_ok ? s_len[r_local] : 0;
+
+  // Q fragments: Q[vr][16*ks + 8*x .. +8)
+  bf16x8 qf[ATT_D / 16];
+  {
+    const u32x4* qp = reinterpret_cast<const u32x4*>(q + (int64_t)(row0 + (vr_ok ? r_local : 0)) * q_stride +
+                                                     (int64_t)head * ATT_D);
+#pragma unroll
+    for (int ks = 0; ks < ATT_D / 16; ++ks) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (vr_ok) v = qp[2 * ks + x];
+      qf[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  f32x16 o_acc[ATT_D / 32];
+#pragma unroll
+  for (int i = 0; i < ATT_D / 32; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o_acc[i][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const int64_t kv_row_elems = (int64_t)Hkv * ATT_D;
+
+  // Rows of different requests (different row_kv_start) may share a tile: handle one run of equal
+  // start at a time; lanes outside the run see every key masked.
+  int seg_begin = 0;
+  while (seg_begin < rows_here) {
+    const int seg_start = s_start[seg_begin];
+    int seg_end = seg_begin + 1;
+    while (seg_end < rows_here && s_start[seg_end] == seg_start) ++seg_end;
+    int seg_max = 0;
+    for (int r = seg_begin; r < seg_end; ++r) seg_max = max(seg_max, s_len[r]);
+
+    const bool in_seg = vr_ok && r_local >= seg_begin && r_local < seg_end;
+    const int len = in_seg ? my_len : 0;
+    // longest / shortest visible range among this wavefront's lanes (uniform per wavefront)
+    int w_max = len, w_min = len;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      w_max = max(w_max, __shfl_xor(w_max, o));
+      w_min = min(w_min, __shfl_xor(w_min, o));
+    }
+
+    const uint16_t* kbase = kc + (int64_t)seg_start * kv_row_elems + (int64_t)kvh * ATT_D;
+    const uint16_t* vbase = vc + (int64_t)seg_start * kv_row_elems + (int64_t)kvh * ATT_D;
+    const int n_blocks = (seg_max + KB - 1) / KB;
+
+    for (int kb = 0; kb < n_blocks; ++kb) {
+      const int key0 = kb * KB;
+      __syncthreads();     // previous block's fragments are no longer needed
+      // ---- K tile: thread handles chunk tid%16 of keys tid/16 + 16*i -------------------------
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = (tid >> 4) + 16 * i;
+        const int gk = min(key0 + key, seg_max - 1);          // stay inside the request's range
+        const u32x4 v = *(reinterpret_cast<const u32x4*>(kbase + (int64_t)gk * kv_row_elems) + (tid & 15));
+        ldsK[k_off(key, tid & 15)] = v;
+      }
+      // ---- V tile, transposed: thread handles 4 keys (group kg) x 8 d (chunk dc) -------------
+      {
+        const int dc = tid & 15, kg = tid >> 4;
+        u32x4 rowv[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int gk = min(key0 + 4 * kg + b, seg_max - 1);
+          rowv[b] = *(reinterpret_cast<const u32x4*>(vbase + (int64_t)gk * kv_row_elems) + dc);
+        }
+        // key = 16*t + 8*a + 4*xx + b  ->  position 16*t + 8*xx + 4*a + b  (chunk 2t+xx, half a)
+        const int t = kg >> 2, a = (kg >> 1) & 1, xx = kg & 1;
+        const int chunk = 2 * t + xx;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int d = 8 * dc + i;
+          uint32_t e[4];
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const uint32_t w = rowv[b][i >> 1];
+            e[b] = (i & 1) ? (w >> 16) : (w & 0xffffu);
+          }
+          u32x2 pr;
+          pr[0] = e[0] | (e[1] << 16);
+          pr[1] = e[2] | (e[3] << 16);
+          u32x2* dst = reinterpret_cast<u32x2*>(&ldsV[d * 8 + vt_chunk(d, chunk)]) + a;
+          *dst = pr;
+        }
+      }
+      __syncthreads();
+
+      if (key0 >= w_max) continue;     // nothing visible for this wavefront in this block
+
+      // ---- S^T = K Q^T -------------------------------------------------------------------------
+      f32x16 st[2];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) st[mt][e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < ATT_D / 16; ++ks) {
+          const u32x4 kv = ldsK[k_off(32 * mt + l32, 2 * ks + x)];
+          st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[ks], st[mt], 0, 0, 0);
+        }
+      }
+      // ---- online softmax (base 2) --------------------------------------------------------------
+      const bool need_mask = key0 + KB > w_min;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          float s = st[mt][j] * scale_log2;
+          if (need_mask) {
+            const int key = key0 + 32 * mt + 8 * (j >> 2) + 4 * x + (j & 3);
+            s = key < len ? s : -INFINITY;
+          }
+          st[mt][j] = s;
+          mx = fmaxf(mx, s);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);          // m_run = -inf -> 0
+      m_run = m_new;
+      float psum = 0.f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const float p = __builtin_amdgcn_exp2f(st[mt][j] - m_use);
+          st[mt][j] = p;
+          psum += p;
+        }
+      l_run = l_run * alpha + psum;
+#pragma unroll
+      for (int i = 0; i < ATT_D / 32; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+      // ---- O^T += V^T P^T -----------------------------------------------------------------------
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        u32x4 pw;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          pw[e] = pack_bf16x2(st[t >> 1][8 * (t & 1) + 2 * e], st[t >> 1][8 * (t & 1) + 2 * e + 1]);
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+        for (int md = 0; md < ATT_D / 32; ++md) {
+          const int d = 32 * md + l32;
+          const u32x4 vv = ldsV[d * 8 + vt_chunk(d, 2 * t + x)];
+          o_acc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, o_acc[md], 0, 0, 0);
+        }
+      }
+    }
+    seg_begin = seg_end;
+  }
+
+  // ---- normalise and store: lane holds d = 32*md + 8*(j/4) + 4*x + j%4 of its virtual row ------
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (vr_ok) {
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    uint16_t* op = out + ((int64_t)(row0 + r_local) * Hq + head) * ATT_D;
+#pragma unroll
+    for (int md = 0; md < ATT_D / 32; ++md)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        u32x2 w;
+        w[0] = pack_bf16x2(o_acc[md][4 * qd] * inv, o_acc[md][4 * qd + 1] * inv);
+        w[1] = pack_bf16x2(o_acc[md][4 * qd + 2] * inv, o_acc[md][4 * qd + 3] * inv);
+        *reinterpret_cast<u32x2*>(op + 32 * md + 8 * qd + 4 * x) = w;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// f32 kernel: one wavefront per (row, head); lanes stride over keys with a private online softmax,
+// merged across lanes at the end.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void attention_f32_kernel(const float* __restrict__ q, int64_t q_stride,
+                                                           const float* __restrict__ kc,
+                                                           const float* __restrict__ vc,
+                                                           const int32_t* __restrict__ row_kv_start,
+                                                           const int32_t* __restrict__ row_kv_len, int Hq,
+                                                           int Hkv, int g, float scale,
+                                                           float* __restrict__ out) {
+  __shared__ float sq[D];
+  const int row = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+  const int kvh = head / g;
+  const float* qp = q + (int64_t)row * q_stride + (int64_t)head * D;
+  for (int d = lane; d < D; d += 64) sq[d] = qp[d] * scale;
+  __syncthreads();
+  const int len = row_kv_len[row];
+  const int64_t start = row_kv_start[row];
+  const int64_t kv_row = (int64_t)Hkv * D;
+  float m = -INFINITY, l = 0.f;
+  float acc[D];
+#pragma unroll
+  for (int d = 0; d < D; ++d) acc[d] = 0.f;
+  for (int j = lane; j < len; j += 64) {
+    const float4* kp = reinterpret_cast<const float4*>(kc + (start + j) * kv_row + (int64_t)kvh * D);
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < D / 4; ++c) {
+      const float4 kv = kp[c];
+      s = fmaf(kv.x, sq[4 * c], s);
+      s = fmaf(kv.y, sq[4 * c + 1], s);
+      s = fmaf(kv.z, sq[4 * c + 2], s);
+      s = fmaf(kv.w, sq[4 * c + 3], s);
+    }
+    const float m_new = fmaxf(m, s);
+    const float alpha = expf(m - m_new);      // m = -inf on the first key -> 0
+    const float p = expf(s - m_new);
+    l = l * alpha + p;
+    const float4* vp = reinterpret_cast<const float4*>(vc + (start + j) * kv_row + (int64_t)kvh * D);
+#pragma unroll
+    for (int c = 0; c < D / 4; ++c) {
+      const float4 vv = vp[c];
+      acc[4 * c] = acc[4 * c] * alpha + p * vv.x;
+      acc[4 * c + 1] = acc[4 * c + 1] * alpha + p * vv.y;
+      acc[4 * c + 2] = acc[4 * c + 2] * alpha + p * vv.z;
+      acc[4 * c + 3] = acc[4 * c + 3] * alpha + p * vv.w;
+    }
+    m = m_new;
+  }
+  // merge the 64 partial softmaxes
+  float m_all = m;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m_all = fmaxf(m_all, __shfl_xor(m_all, o));
+  const float w = (m == -INFINITY) ? 0.f : expf(m - m_all);
+  float l_all = l * w;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) l_all += __shfl_xor(l_all, o);
+  const float inv = l_all > 0.f ? 1.0f / l_all : 0.f;
+  float* op = out + ((int64_t)row * Hq + head) * D;
+#pragma unroll
+  for (int d = 0; d < D; ++d) {
+    float v = acc[d] * w;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if (lane == (d & 63)) op[d] = v * inv;
+  }
+}
+
+}  // namespace
+
+int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const void* v_cache,
+                     const int32_t* row_kv_start, const int32_t* row_kv_len, int64_t n, int Hq, int Hkv,
+                     int D, float scale, void* out, int dtype, hipStream_t st) {
+  if (n <= 0) return VLC_OK;
+  const int g = Hq / Hkv;
+  if (dtype == VLC_BF16) {
+    if (D != ATT_D) return fail(VLC_ERR_SHAPE, "attention(bf16): D=%d unsupported (128 only)", D);
+    if (g > VR) return fail(VLC_ERR_SHAPE, "attention(bf16): Hq/Hkv=%d exceeds %d", g, VR);
+    if (q_stride % 8) return fail(VLC_ERR_SHAPE, "attention(bf16): q row stride must be a multiple of 8");
+    const int rows_per_tile = VR / g;
+    const dim3 grid((unsigned)((n + rows_per_tile - 1) / rows_per_tile), (unsigned)Hkv);
+    hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
+                       (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
+                       Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out);
+    VLC_CHECK_LAUNCH("attention_bf16");
+    return VLC_OK;
+  }
+  if (dtype == VLC_F32) {
+    if (n > 0x7fffffff || Hq > 65535) return fail(VLC_ERR_SHAPE, "attention(f32): grid too large");
+    const dim3 grid((unsigned)n, (unsigned)Hq);
+    if (D == 64)
+      hipLaunchKernelGGL(attention_f32_kernel<64>, grid, dim3(64), 0, st, (const float*)q, q_stride,
+                         (const float*)k_cache, (const float*)v_cache, row_kv_start, row_kv_len, Hq, Hkv, g,
+                         scale, (float*)out);
+    else if (D == 128)
+      hipLaunchKernelGGL(attention_f32_kernel<128>, grid, dim3(64), 0, st, (const float*)q, q_stride,
+                         (const float*)k_cache, (const float*)v_cache, row_kv_start, row_kv_len, Hq, Hkv, g,
+                         scale, (float*)out);
+    else
+      return fail(VLC_ERR_SHAPE, "attention(f32): D=%d unsupported", D);
+    VLC_CHECK_LAUNCH("attention_f32");
+    return VLC_OK;
+  }
+  return fail(VLC_ERR_DTYPE, "attention: dtype=%d", dtype);
+}
+
+}  // namespace vlc
+
+extern "C" int vlc_sparse_q_attention(const void* q, const void* k_cache, const void* v_cache,
+                                      const int32_t* row_kv_start, const int32_t* row_kv_len, int64_t n,
+                                      int Hq, int Hkv, int D, float scale, void* out, int dtype,
+                                      void* stream) {
+  using vlc::fail;
+  if (dtype != VLC_F32 && dtype != VLC_BF16) return fail(VLC_ERR_DTYPE, "vlc_sparse_q_attention: dtype=%d", dtype);
+  if (n < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (D != 64 && D != 128))
+    return fail(VLC_ERR_SHAPE, "vlc_sparse_q_attention: n=%lld Hq=%d Hkv=%d D=%d", (long long)n, Hq, Hkv, D);
+  if (n == 0) return VLC_OK;
+  if (!q || !k_cache || !v_cache || !row_kv_start || !row_kv_len || !out)
+    return fail(VLC_ERR_NULL, "vlc_sparse_q_attention: NULL pointer");
+  if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15)
+    return fail(VLC_ERR_SHAPE, "vlc_sparse_q_attention: pointers must be 16-byte aligned");
+  return vlc::launch_attention(q, (int64_t)Hq * D, k_cache, v_cache, row_kv_start, row_kv_len, n, Hq, Hkv, D,
+                               scale, out, dtype, (hipStream_t)stream);
+}

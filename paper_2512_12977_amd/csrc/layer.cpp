@@ -1,0 +1,137 @@
+// vlc_layer_forward: one decoder layer of the selective-recompute prefill, composed from the
+// library's kernels on one stream (Sec. 4.1 "Basic Algorithm", Sec. 4.2).
+#include <cmath>
+
+#include "vlc_internal.h"
+
+using vlc::fail;
+
+namespace {
+
+inline int64_t align256(int64_t b) { return (b + 255) & ~(int64_t)255; }
+
+struct Workspace {
+  int64_t xn, qkv32, q, attn, h1, n2, act, total;   // byte offsets
+};
+
+Workspace layout(const vlc_layer_shape& s, int64_t n) {
+  const int64_t es = vlc::elem_size(s.dtype);
+  const int64_t nqkv = (int64_t)(s.Hq + 2 * s.Hkv) * s.D;
+  Workspace w;
+  int64_t at = 0;
+  w.xn = at;   at += align256(n * s.H * es);          // input-normed activations
+  w.qkv32 = at; at += align256(n * nqkv * 4);         // fused q|k|v rows, unrounded float
+  w.q = at;    at += align256(n * (int64_t)s.Hq * s.D * es);   // rotated queries
+  w.attn = at; at += align256(n * (int64_t)s.Hq * s.D * es);
+  w.h1 = at;   at += align256(n * s.H * es);          // hidden after the attention residual
+  w.n2 = at;   at += align256(n * s.H * es);          // post-attention-normed activations
+  w.act = at;  at += align256(n * (int64_t)s.I * es); // SwiGLU product
+  w.total = at;
+  return w;
+}
+
+int check_shape(const vlc_layer_shape* s, const char* who) {
+  if (!s) return fail(VLC_ERR_NULL, "%s: shape is NULL", who);
+  if (s->dtype != VLC_F32 && s->dtype != VLC_BF16) return fail(VLC_ERR_DTYPE, "%s: dtype=%d", who, s->dtype);
+  if (s->H <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->I <= 0 || s->Hq % s->Hkv)
+    return fail(VLC_ERR_SHAPE, "%s: H=%d Hq=%d Hkv=%d I=%d", who, s->H, s->Hq, s->Hkv, s->I);
+  if (s->D != 64 && s->D != 128) return fail(VLC_ERR_SHAPE, "%s: D=%d (64 or 128)", who, s->D);
+  if (s->dtype == VLC_BF16 && s->D != 128) return fail(VLC_ERR_SHAPE, "%s: bf16 needs D=128", who);
+  if (s->H % 64 || s->I % 64 || (s->Hq * s->D) % 64)
+    return fail(VLC_ERR_SHAPE, "%s: H, I and Hq*D must be multiples of 64", who);
+  if (!(s->rope_base > 0.0) || !(s->eps >= 0.f)) return fail(VLC_ERR_SHAPE, "%s: rope_base/eps", who);
+  return VLC_OK;
+}
+
+}  // namespace
+
+extern "C" int64_t vlc_layer_workspace_bytes(const vlc_layer_shape* shape, int64_t n_rows_max) {
+  if (check_shape(shape, "vlc_layer_workspace_bytes")) return 0;
+  if (n_rows_max < 0) {
+    fail(VLC_ERR_SHAPE, "vlc_layer_workspace_bytes: n_rows_max=%lld", (long long)n_rows_max);
+    return 0;
+  }
+  return layout(*shape, n_rows_max).total;
+}
+
+extern "C" int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t n_rows, int64_t* offsets) {
+  int rc = check_shape(shape, "vlc_layer_workspace_layout");
+  if (rc) return rc;
+  if (!offsets) return fail(VLC_ERR_NULL, "vlc_layer_workspace_layout: offsets is NULL");
+  if (n_rows < 0) return fail(VLC_ERR_SHAPE, "vlc_layer_workspace_layout: n_rows=%lld", (long long)n_rows);
+  const Workspace w = layout(*shape, n_rows);
+  const int64_t o[VLC_WS_FIELDS] = {w.xn, w.qkv32, w.q, w.attn, w.h1, w.n2, w.act};
+  for (int i = 0; i < VLC_WS_FIELDS; ++i) offsets[i] = o[i];
+  return VLC_OK;
+}
+
+extern "C" int vlc_layer_forward(const vlc_layer_shape* shape, const vlc_layer_weights* w,
+                                 const vlc_layer_plan* p, const void* h_in, void* h_out, void* k_cache,
+                                 void* v_cache, void* workspace, int64_t workspace_bytes, void* stream) {
+  const char* who = "vlc_layer_forward";
+  int rc = check_shape(shape, who);
+  if (rc) return rc;
+  if (!w || !p) return fail(VLC_ERR_NULL, "%s: weights or plan is NULL", who);
+  if (p->n < 0 || p->n_in < 0 || p->n_reuse < 0 || p->kv_rows < 0)
+    return fail(VLC_ERR_SHAPE, "%s: negative count in plan", who);
+  if (p->n > p->n_in) return fail(VLC_ERR_INFEASIBLE, "%s: layer recomputes %lld rows but only %lld were kept above",
+                                  who, (long long)p->n, (long long)p->n_in);
+  if (!k_cache || !v_cache) return fail(VLC_ERR_NULL, "%s: k_cache/v_cache is NULL", who);
+  if (p->n_reuse > 0 && (!p->reuse_src || !p->reuse_dst || !p->reuse_delta || !p->k_pool || !p->v_pool))
+    return fail(VLC_ERR_NULL, "%s: reuse list or pool is NULL", who);
+  const vlc_layer_shape& s = *shape;
+  hipStream_t st = (hipStream_t)stream;
+  const vlc::RopeFreq freq = vlc::make_rope_freq(s.rope_base, s.D);
+
+  // Reused image tokens: keys rotated by the position delta, values copied (independent of the rows).
+  if (p->n_reuse > 0) {
+    rc = vlc::launch_rope_shift(p->k_pool, p->v_pool, k_cache, v_cache, p->reuse_src, p->reuse_dst,
+                                p->reuse_delta, p->n_reuse, s.Hkv, s.D, freq, s.dtype, st);
+    if (rc) return rc;
+  }
+  const int64_t n = p->n;
+  if (n == 0) return VLC_OK;
+  if (!w->w_ln1 || !w->w_qkv || !w->w_o || !w->w_ln2 || !w->w_gate_up || !w->w_down)
+    return fail(VLC_ERR_NULL, "%s: a weight pointer is NULL", who);
+  if (!p->map || !p->slot || !p->pos || !p->row_kv_start || !p->row_kv_len || !h_in || !h_out)
+    return fail(VLC_ERR_NULL, "%s: NULL pointer in plan / hidden states", who);
+  if (h_in == h_out) return fail(VLC_ERR_SHAPE, "%s: h_out must not alias h_in", who);
+  const Workspace ws = layout(s, n);
+  if (!workspace || workspace_bytes < ws.total)
+    return fail(VLC_ERR_WORKSPACE, "%s: workspace of %lld bytes, %lld needed", who, (long long)workspace_bytes,
+                (long long)ws.total);
+  if ((uintptr_t)workspace & 255) return fail(VLC_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned", who);
+  char* base = static_cast<char*>(workspace);
+  void* xn = base + ws.xn;
+  float* qkv32 = reinterpret_cast<float*>(base + ws.qkv32);
+  void* qrot = base + ws.q;
+  void* attn = base + ws.attn;
+  void* h1 = base + ws.h1;
+  void* n2 = base + ws.n2;
+  void* act = base + ws.act;
+  const int64_t H = s.H, nqkv = (int64_t)(s.Hq + 2 * s.Hkv) * s.D, hqd = (int64_t)s.Hq * s.D, I = s.I;
+
+  // x = h_in[map] is never materialised: the norm reads through the map, and so does the residual.
+  rc = vlc::launch_rmsnorm(h_in, p->map, w->w_ln1, xn, n, s.H, s.eps, s.dtype, st);
+  if (rc) return rc;
+  rc = vlc::launch_gemm(xn, H, w->w_qkv, qkv32, nqkv, n, nqkv, H, vlc::EPI_BIAS_F32, w->b_qkv, nullptr, 0,
+                        nullptr, s.dtype, st);
+  if (rc) return rc;
+  // RoPE at the new positions; fresh k, v overwrite their slots (after the reused tokens were placed).
+  rc = vlc::launch_rope_qk_scatter(qkv32, p->pos, p->slot, n, s.Hq, s.Hkv, s.D, freq, qrot, k_cache, v_cache,
+                                   s.dtype, st);
+  if (rc) return rc;
+  rc = vlc::launch_attention(qrot, hqd, k_cache, v_cache, p->row_kv_start, p->row_kv_len, n, s.Hq, s.Hkv, s.D,
+                             1.0f / sqrtf((float)s.D), attn, s.dtype, st);
+  if (rc) return rc;
+  rc = vlc::launch_gemm(attn, hqd, w->w_o, h1, H, n, H, hqd, vlc::EPI_RESIDUAL, nullptr, h_in, H, p->map,
+                        s.dtype, st);
+  if (rc) return rc;
+  rc = vlc::launch_rmsnorm(h1, nullptr, w->w_ln2, n2, n, s.H, s.eps, s.dtype, st);
+  if (rc) return rc;
+  rc = vlc::launch_gemm(n2, H, w->w_gate_up, act, I, n, I, H, vlc::EPI_SWIGLU, nullptr, nullptr, 0, nullptr,
+                        s.dtype, st);
+  if (rc) return rc;
+  return vlc::launch_gemm(act, I, w->w_down, h_out, H, n, H, I, vlc::EPI_RESIDUAL, nullptr, h1, H, nullptr,
+                          s.dtype, st);
+}

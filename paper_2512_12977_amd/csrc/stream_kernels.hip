@@ -1,0 +1,427 @@
+// HBM-bound kernels of the selective-recompute path: row gather, KV scatter, key re-rotation
+// (RoPE shift), RoPE + scatter of fresh q/k/v rows, RMSNorm.  All move 16-byte chunks per lane
+// so that a wavefront touches whole 128-byte lines of each row.
+#include <hip/hip_runtime.h>
+
+#include "vlc_internal.h"
+
+namespace vlc {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {   // round to nearest, ties to even
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// A 16-byte chunk viewed as VEC elements of T, converted to/from float.
+template <typename T> struct Chunk;
+template <> struct Chunk<float> {
+  static constexpr int VEC = 4;
+  __device__ static void unpack(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+  __device__ static uint4 pack(const float* f) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]),
+                      __float_as_uint(f[3]));
+  }
+};
+template <> struct Chunk<uint16_t> {   // bf16
+  static constexpr int VEC = 8;
+  __device__ static void unpack(const uint4& r, float* f) {
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  __device__ static uint4 pack(const float* f) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      w[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+// sin/cos of delta * inv_freq.  The angle is formed and reduced to [-pi, pi] in double (positions
+// reach tens of thousands of radians, beyond what a float angle resolves), then evaluated in float.
+__device__ __forceinline__ void rope_sincos(double inv_freq, int delta, float* s, float* c) {
+  double rev = (double)delta * inv_freq * 0.15915494309189535;   // angle / 2pi
+  rev -= rint(rev);
+  const float r = (float)(rev * 6.283185307179586);
+  *s = sinf(r);
+  *c = cosf(r);
+}
+
+// ---------------------------------------------------------------------------------------------
+// gather / scatter of whole rows in 16-byte chunks
+// ---------------------------------------------------------------------------------------------
+// dst chunk (i, c) = src chunk (src_idx ? src_idx[i] : i, c) written at row (dst_idx ? dst_idx[i] : i).
+// Row strides are given in chunks.  Each thread moves UNROLL chunks, all loads issued first.
+template <int UNROLL>
+__global__ __launch_bounds__(kThreads) void copy_rows_kernel(
+    const uint4* __restrict__ src, int64_t src_stride, const int32_t* __restrict__ src_idx,
+    uint4* __restrict__ dst, int64_t dst_stride, const int32_t* __restrict__ dst_idx, uint32_t total,
+    uint32_t chunks_per_row) {
+  const uint32_t base = blockIdx.x * (uint32_t)(kThreads * UNROLL) + threadIdx.x;
+  uint4 v[UNROLL];
+  int64_t off[UNROLL];
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    const uint32_t id = base + u * kThreads;
+    off[u] = -1;
+    if (id < total) {
+      const uint32_t row = id / chunks_per_row;
+      const uint32_t c = id - row * chunks_per_row;
+      const int64_t srow = src_idx ? (int64_t)src_idx[row] : (int64_t)row;
+      const int64_t drow = dst_idx ? (int64_t)dst_idx[row] : (int64_t)row;
+      v[u] = src[srow * src_stride + c];
+      off[u] = drow * dst_stride + c;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u)
+    if (off[u] >= 0) dst[off[u]] = v[u];
+}
+
+int copy_rows(const void* src, int64_t src_stride_bytes, const int32_t* src_idx, void* dst,
+              int64_t dst_stride_bytes, const int32_t* dst_idx, int64_t n, int64_t row_bytes,
+              hipStream_t st, const char* name) {
+  constexpr int UNROLL = 4;
+  const int64_t cpr = row_bytes / 16;
+  if (n <= 0 || cpr <= 0) return VLC_OK;
+  // keep flat chunk ids within 31 bits: slice the row range if needed
+  const int64_t rows_per_launch = ((int64_t)1 << 30) / cpr > 0 ? ((int64_t)1 << 30) / cpr : 1;
+  for (int64_t r0 = 0; r0 < n; r0 += rows_per_launch) {
+    const int64_t rows = (n - r0 < rows_per_launch) ? n - r0 : rows_per_launch;
+    const uint32_t total = (uint32_t)(rows * cpr);
+    const uint32_t blocks = (total + kThreads * UNROLL - 1) / (kThreads * UNROLL);
+    const uint4* s = reinterpret_cast<const uint4*>(
+        static_cast<const char*>(src) + (src_idx ? 0 : r0 * src_stride_bytes));
+    uint4* d = reinterpret_cast<uint4*>(static_cast<char*>(dst) + (dst_idx ? 0 : r0 * dst_stride_bytes));
+    hipLaunchKernelGGL(copy_rows_kernel<UNROLL>, dim3(blocks), dim3(kThreads), 0, st, s,
+                       src_stride_bytes / 16, src_idx ? src_idx + r0 : nullptr, d, dst_stride_bytes / 16,
+                       dst_idx ? dst_idx + r0 : nullptr, total, (uint32_t)cpr);
+    VLC_CHECK_LAUNCH(name);
+  }
+  return VLC_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// RoPE shift of reused keys + copy of reused values (Sec. 4.2)
+// ---------------------------------------------------------------------------------------------
+// One thread owns, for one token, VEC rotation pairs (a 16-byte chunk of the low half and the
+// matching chunk of the high half) and walks over the Hkv heads, so each sine/cosine is computed
+// once per token and reused for every head.  Consecutive lanes cover consecutive chunks of a row.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void rope_shift_kernel(
+    const uint4* k_src, const uint4* v_src, uint4* k_dst, uint4* v_dst,   // may alias (in-place use)
+    const int32_t* __restrict__ src_row, const int32_t* __restrict__ dst_row,
+    const int32_t* __restrict__ delta, int64_t n_tok, int Hkv, RopeFreq freq) {
+  constexpr int VEC = Chunk<T>::VEC;
+  constexpr int CH = (D / 2) / VEC;                  // chunks per half head
+  constexpr int HEAD_CHUNKS = 2 * CH;                // chunks per head
+  const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t tok = gid / CH;
+  const int c = (int)(gid - tok * CH);
+  if (tok >= n_tok) return;
+  const int64_t srow = src_row[tok], drow = dst_row[tok];
+  const int d = delta[tok];
+  float sn[VEC], cs[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) rope_sincos(freq.inv_freq[c * VEC + i], d, &sn[i], &cs[i]);
+  const int64_t row_chunks = (int64_t)Hkv * HEAD_CHUNKS;
+  const uint4* ks = k_src + srow * row_chunks + c;
+  uint4* kd = k_dst + drow * row_chunks + c;
+  const bool do_v = v_src != nullptr && v_dst != nullptr;
+  const uint4* vs = do_v ? v_src + srow * row_chunks + c : nullptr;
+  uint4* vd = do_v ? v_dst + drow * row_chunks + c : nullptr;
+#pragma unroll 4
+  for (int h = 0; h < Hkv; ++h) {
+    const uint4 lo_r = ks[h * HEAD_CHUNKS];
+    const uint4 hi_r = ks[h * HEAD_CHUNKS + CH];
+    uint4 v_lo, v_hi;
+    if (do_v) {
+      v_lo = vs[h * HEAD_CHUNKS];
+      v_hi = vs[h * HEAD_CHUNKS + CH];
+    }
+    float lo[VEC], hi[VEC], olo[VEC], ohi[VEC];
+    Chunk<T>::unpack(lo_r, lo);
+    Chunk<T>::unpack(hi_r, hi);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      olo[i] = lo[i] * cs[i] - hi[i] * sn[i];
+      ohi[i] = hi[i] * cs[i] + lo[i] * sn[i];
+    }
+    kd[h * HEAD_CHUNKS] = Chunk<T>::pack(olo);
+    kd[h * HEAD_CHUNKS + CH] = Chunk<T>::pack(ohi);
+    if (do_v) {
+      vd[h * HEAD_CHUNKS] = v_lo;
+      vd[h * HEAD_CHUNKS + CH] = v_hi;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// RoPE of fresh q/k rows + scatter of fresh k/v into the cache
+// ---------------------------------------------------------------------------------------------
+// One thread owns VEC rotation pairs of up to HB consecutive heads of one row of the fused q|k|v
+// matrix (unrounded float).  Head index < Hq: query, rotated, written to q_out.  < Hq+Hkv: key,
+// rotated and written to its cache slot (the blend).  Otherwise: value, written to its cache slot.
+// Outputs are rounded to the storage type once, after the rotation.
+template <typename T, int D, int HB>
+__global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
+    const float* __restrict__ qkv, const int32_t* __restrict__ pos, const int32_t* __restrict__ slot,
+    int64_t n, int Hq, int Hkv, int head_blocks, RopeFreq freq, uint4* __restrict__ q_out,
+    uint4* __restrict__ k_cache, uint4* __restrict__ v_cache) {
+  constexpr int VEC = Chunk<T>::VEC;
+  constexpr int CH = (D / 2) / VEC;
+  constexpr int HEAD_CHUNKS = 2 * CH;
+  const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int c = (int)(gid % CH);
+  const int64_t t = gid / CH;
+  const int hb = (int)(t % head_blocks);
+  const int64_t row = t / head_blocks;
+  if (row >= n) return;
+  const int heads = Hq + 2 * Hkv;
+  const int p = pos[row];
+  float sn[VEC], cs[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) rope_sincos(freq.inv_freq[c * VEC + i], p, &sn[i], &cs[i]);
+  const float* r = qkv + row * ((int64_t)heads * D) + c * VEC;
+  uint4* qo = q_out + row * ((int64_t)Hq * HEAD_CHUNKS) + c;
+  const int64_t dst = (int64_t)slot[row] * ((int64_t)Hkv * HEAD_CHUNKS) + c;
+#pragma unroll
+  for (int j = 0; j < HB; ++j) {
+    const int h = hb * HB + j;
+    if (h >= heads) break;
+    float lo[VEC], hi[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; i += 4) {
+      const float4 a = *reinterpret_cast<const float4*>(r + (int64_t)h * D + i);
+      const float4 b = *reinterpret_cast<const float4*>(r + (int64_t)h * D + D / 2 + i);
+      lo[i] = a.x; lo[i + 1] = a.y; lo[i + 2] = a.z; lo[i + 3] = a.w;
+      hi[i] = b.x; hi[i + 1] = b.y; hi[i + 2] = b.z; hi[i + 3] = b.w;
+    }
+    if (h >= Hq + Hkv) {
+      v_cache[dst + (h - Hq - Hkv) * HEAD_CHUNKS] = Chunk<T>::pack(lo);
+      v_cache[dst + (h - Hq - Hkv) * HEAD_CHUNKS + CH] = Chunk<T>::pack(hi);
+      continue;
+    }
+    float olo[VEC], ohi[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      olo[i] = lo[i] * cs[i] - hi[i] * sn[i];
+      ohi[i] = hi[i] * cs[i] + lo[i] * sn[i];
+    }
+    const uint4 plo = Chunk<T>::pack(olo), phi = Chunk<T>::pack(ohi);
+    if (h < Hq) {
+      qo[h * HEAD_CHUNKS] = plo;
+      qo[h * HEAD_CHUNKS + CH] = phi;
+    } else {
+      k_cache[dst + (h - Hq) * HEAD_CHUNKS] = plo;
+      k_cache[dst + (h - Hq) * HEAD_CHUNKS + CH] = phi;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// RMSNorm with optional row gather: y[i] = x[map[i]] * rsqrt(mean(x^2) + eps) * w
+// ---------------------------------------------------------------------------------------------
+template <typename T, int MAXC>
+__global__ __launch_bounds__(kThreads) void rmsnorm_kernel(const uint4* __restrict__ x,
+                                                           const int32_t* __restrict__ map,
+                                                           const uint4* __restrict__ w,
+                                                           uint4* __restrict__ y, int chunks, float inv_h,
+                                                           float eps) {
+  constexpr int VEC = Chunk<T>::VEC;
+  const int64_t row = blockIdx.x;
+  const int64_t srow = map ? (int64_t)map[row] : row;
+  const uint4* xr = x + srow * chunks;
+  float v[MAXC][VEC];
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = threadIdx.x + j * kThreads;
+    if (c < chunks) {
+      Chunk<T>::unpack(xr[c], v[j]);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) ss += v[j][i] * v[j][i];
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  __shared__ float part[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int i = 0; i < kThreads / 64; ++i) tot += part[i];
+  const float r = 1.0f / sqrtf(tot * inv_h + eps);
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = threadIdx.x + j * kThreads;
+    if (c < chunks) {
+      float wv[VEC], o[VEC];
+      Chunk<T>::unpack(w[c], wv);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) o[i] = v[j][i] * r * wv[i];
+      y[row * chunks + c] = Chunk<T>::pack(o);
+    }
+  }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------------
+int launch_gather_rows(const void* src, int64_t row_bytes, const int32_t* idx, int64_t n, void* dst,
+                       hipStream_t st) {
+  return copy_rows(src, row_bytes, idx, dst, row_bytes, nullptr, n, row_bytes, st, "gather_rows");
+}
+
+int launch_scatter_kv(const void* k_new, const void* v_new, int64_t src_stride_elems,
+                      const int32_t* dst_row, int64_t n, void* k_cache, void* v_cache, int Hkv, int D,
+                      int dtype, hipStream_t st) {
+  const int64_t es = elem_size(dtype);
+  const int64_t row_bytes = (int64_t)Hkv * D * es;
+  int rc = copy_rows(k_new, src_stride_elems * es, nullptr, k_cache, row_bytes, dst_row, n, row_bytes, st,
+                     "scatter_kv(K)");
+  if (rc) return rc;
+  return copy_rows(v_new, src_stride_elems * es, nullptr, v_cache, row_bytes, dst_row, n, row_bytes, st,
+                   "scatter_kv(V)");
+}
+
+int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
+                      const int32_t* src_row, const int32_t* dst_row, const int32_t* delta,
+                      int64_t n_tok, int Hkv, int D, const RopeFreq& f, int dtype, hipStream_t st) {
+  if (n_tok <= 0) return VLC_OK;
+  const int vec = dtype == VLC_BF16 ? 8 : 4;
+  const int64_t threads = n_tok * ((D / 2) / vec);
+  const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads));
+#define VLC_LAUNCH_SHIFT(T, DD)                                                                       \
+  hipLaunchKernelGGL((rope_shift_kernel<T, DD>), grid, dim3(kThreads), 0, st, (const uint4*)k_src,    \
+                     (const uint4*)v_src, (uint4*)k_dst, (uint4*)v_dst, src_row, dst_row, delta,      \
+                     n_tok, Hkv, f)
+  if (dtype == VLC_BF16 && D == 128) VLC_LAUNCH_SHIFT(uint16_t, 128);
+  else if (dtype == VLC_BF16 && D == 64) VLC_LAUNCH_SHIFT(uint16_t, 64);
+  else if (dtype == VLC_F32 && D == 128) VLC_LAUNCH_SHIFT(float, 128);
+  else if (dtype == VLC_F32 && D == 64) VLC_LAUNCH_SHIFT(float, 64);
+  else return fail(VLC_ERR_SHAPE, "rope shift: unsupported D=%d", D);
+#undef VLC_LAUNCH_SHIFT
+  VLC_CHECK_LAUNCH("rope_shift_kv");
+  return VLC_OK;
+}
+
+int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t* slot, int64_t n, int Hq,
+                           int Hkv, int D, const RopeFreq& f, void* q_out, void* k_cache, void* v_cache,
+                           int dtype, hipStream_t st) {
+  if (n <= 0) return VLC_OK;
+  constexpr int HB = 4;
+  const int vec = dtype == VLC_BF16 ? 8 : 4;
+  const int head_blocks = (Hq + 2 * Hkv + HB - 1) / HB;
+  const int64_t threads = n * head_blocks * ((D / 2) / vec);
+  const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads));
+#define VLC_LAUNCH_RQS(T, DD)                                                                         \
+  hipLaunchKernelGGL((rope_qk_scatter_kernel<T, DD, HB>), grid, dim3(kThreads), 0, st, qkv32, pos,    \
+                     slot, n, Hq, Hkv, head_blocks, f, (uint4*)q_out, (uint4*)k_cache, (uint4*)v_cache)
+  if (dtype == VLC_BF16 && D == 128) VLC_LAUNCH_RQS(uint16_t, 128);
+  else if (dtype == VLC_BF16 && D == 64) VLC_LAUNCH_RQS(uint16_t, 64);
+  else if (dtype == VLC_F32 && D == 128) VLC_LAUNCH_RQS(float, 128);
+  else if (dtype == VLC_F32 && D == 64) VLC_LAUNCH_RQS(float, 64);
+  else return fail(VLC_ERR_SHAPE, "rope+scatter: unsupported D=%d", D);
+#undef VLC_LAUNCH_RQS
+  VLC_CHECK_LAUNCH("rope_qk_scatter");
+  return VLC_OK;
+}
+
+int launch_rmsnorm(const void* x, const int32_t* map, const void* w, void* y, int64_t n, int H,
+                   float eps, int dtype, hipStream_t st) {
+  if (n <= 0) return VLC_OK;
+  const int vec = dtype == VLC_BF16 ? 8 : 4;
+  if (H % vec) return fail(VLC_ERR_SHAPE, "rmsnorm: H=%d not a multiple of %d", H, vec);
+  const int chunks = H / vec;
+  const dim3 grid((unsigned)n);
+  const float inv_h = 1.0f / (float)H;
+#define VLC_LAUNCH_RMS(T, MAXC)                                                                       \
+  hipLaunchKernelGGL((rmsnorm_kernel<T, MAXC>), grid, dim3(kThreads), 0, st, (const uint4*)x, map,    \
+                     (const uint4*)w, (uint4*)y, chunks, inv_h, eps)
+  if (chunks <= kThreads * 2) {
+    if (dtype == VLC_BF16) VLC_LAUNCH_RMS(uint16_t, 2); else VLC_LAUNCH_RMS(float, 2);
+  } else if (chunks <= kThreads * 4) {
+    if (dtype == VLC_BF16) VLC_LAUNCH_RMS(uint16_t, 4); else VLC_LAUNCH_RMS(float, 4);
+  } else if (chunks <= kThreads * 8) {
+    if (dtype == VLC_BF16) VLC_LAUNCH_RMS(uint16_t, 8); else VLC_LAUNCH_RMS(float, 8);
+  } else {
+    return fail(VLC_ERR_SHAPE, "rmsnorm: H=%d too large", H);
+  }
+#undef VLC_LAUNCH_RMS
+  VLC_CHECK_LAUNCH("rmsnorm");
+  return VLC_OK;
+}
+
+}  // namespace vlc
+
+// ---------------------------------------------------------------------------------------------
+// C ABI entry points of the streaming kernels
+// ---------------------------------------------------------------------------------------------
+using vlc::fail;
+
+extern "C" int vlc_gather_rows(const void* src, int64_t src_rows, int64_t row_elems, const int32_t* idx,
+                               int64_t n, void* dst, int dtype, void* stream) {
+  if (dtype != VLC_F32 && dtype != VLC_BF16) return fail(VLC_ERR_DTYPE, "vlc_gather_rows: dtype=%d", dtype);
+  if (n < 0 || src_rows < 0 || row_elems <= 0)
+    return fail(VLC_ERR_SHAPE, "vlc_gather_rows: n=%lld src_rows=%lld row_elems=%lld", (long long)n,
+                (long long)src_rows, (long long)row_elems);
+  if (n == 0) return VLC_OK;
+  if (!src || !idx || !dst) return fail(VLC_ERR_NULL, "vlc_gather_rows: NULL pointer");
+  const int64_t row_bytes = row_elems * vlc::elem_size(dtype);
+  if (row_bytes % 16) return fail(VLC_ERR_SHAPE, "vlc_gather_rows: row of %lld bytes is not a multiple of 16",
+                                  (long long)row_bytes);
+  if (((uintptr_t)src | (uintptr_t)dst) & 15) return fail(VLC_ERR_SHAPE, "vlc_gather_rows: pointers must be 16-byte aligned");
+  return vlc::launch_gather_rows(src, row_bytes, idx, n, dst, (hipStream_t)stream);
+}
+
+static int check_kv(const char* who, int Hkv, int D, int dtype) {
+  if (dtype != VLC_F32 && dtype != VLC_BF16) return fail(VLC_ERR_DTYPE, "%s: dtype=%d", who, dtype);
+  if (Hkv <= 0 || (D != 64 && D != 128)) return fail(VLC_ERR_SHAPE, "%s: Hkv=%d D=%d unsupported", who, Hkv, D);
+  return VLC_OK;
+}
+
+extern "C" int vlc_rope_shift_kv(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
+                                 const int32_t* src_row, const int32_t* dst_row, const int32_t* delta,
+                                 int64_t n_tok, int Hkv, int D, double rope_base, int dtype, void* stream) {
+  int rc = check_kv("vlc_rope_shift_kv", Hkv, D, dtype);
+  if (rc) return rc;
+  if (n_tok < 0) return fail(VLC_ERR_SHAPE, "vlc_rope_shift_kv: n_tok=%lld", (long long)n_tok);
+  if (!(rope_base > 0.0)) return fail(VLC_ERR_SHAPE, "vlc_rope_shift_kv: rope_base must be positive");
+  if (n_tok == 0) return VLC_OK;
+  if (!k_src || !k_dst || !src_row || !dst_row || !delta)
+    return fail(VLC_ERR_NULL, "vlc_rope_shift_kv: NULL pointer");
+  if (((uintptr_t)k_src | (uintptr_t)k_dst | (uintptr_t)v_src | (uintptr_t)v_dst) & 15)
+    return fail(VLC_ERR_SHAPE, "vlc_rope_shift_kv: pointers must be 16-byte aligned");
+  return vlc::launch_rope_shift(k_src, v_src, k_dst, v_dst, src_row, dst_row, delta, n_tok, Hkv, D,
+                                vlc::make_rope_freq(rope_base, D), dtype, (hipStream_t)stream);
+}
+
+extern "C" int vlc_scatter_kv(const void* k_new, const void* v_new, const int32_t* dst_row, int64_t n,
+                              void* k_cache, void* v_cache, int64_t cache_rows, int Hkv, int D, int dtype,
+                              void* stream) {
+  int rc = check_kv("vlc_scatter_kv", Hkv, D, dtype);
+  if (rc) return rc;
+  if (n < 0 || cache_rows < 0) return fail(VLC_ERR_SHAPE, "vlc_scatter_kv: n=%lld cache_rows=%lld", (long long)n, (long long)cache_rows);
+  if (n == 0) return VLC_OK;
+  if (!k_new || !v_new || !dst_row || !k_cache || !v_cache) return fail(VLC_ERR_NULL, "vlc_scatter_kv: NULL pointer");
+  if (n > cache_rows) return fail(VLC_ERR_INDEX, "vlc_scatter_kv: %lld unique rows cannot fit a cache of %lld rows", (long long)n, (long long)cache_rows);
+  if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)k_cache | (uintptr_t)v_cache) & 15)
+    return fail(VLC_ERR_SHAPE, "vlc_scatter_kv: pointers must be 16-byte aligned");
+  return vlc::launch_scatter_kv(k_new, v_new, (int64_t)Hkv * D, dst_row, n, k_cache, v_cache, Hkv, D, dtype,
+                                (hipStream_t)stream);
+}

@@ -1,0 +1,81 @@
+// Internal helpers shared by the library's translation units (not part of the C ABI).
+#ifndef VLC_INTERNAL_H_
+#define VLC_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "vlcache.h"
+
+namespace vlc {
+
+// Records the message for vlc_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+inline int elem_size(int dtype) { return dtype == VLC_BF16 ? 2 : 4; }
+
+#define VLC_CHECK_HIP(expr)                                                              \
+  do {                                                                                   \
+    hipError_t e_ = (expr);                                                              \
+    if (e_ != hipSuccess)                                                                \
+      return ::vlc::fail(VLC_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));    \
+  } while (0)
+
+#define VLC_CHECK_LAUNCH(name)                                                           \
+  do {                                                                                   \
+    hipError_t e_ = hipGetLastError();                                                   \
+    if (e_ != hipSuccess)                                                                \
+      return ::vlc::fail(VLC_ERR_HIP, "launch of %s failed: %s", name,                   \
+                         hipGetErrorString(e_));                                         \
+  } while (0)
+
+// RoPE inverse frequencies theta_i = base^(-2i/D), i < D/2, in double; passed to kernels by value.
+struct RopeFreq {
+  double inv_freq[64];
+};
+RopeFreq make_rope_freq(double base, int D);
+
+// ---- internal launchers (enqueue only; arguments already validated by the callers) ----------
+
+// dst[i,:] = src[idx[i],:] in 16-byte chunks; row_bytes % 16 == 0.  idx may be NULL (identity).
+int launch_gather_rows(const void* src, int64_t row_bytes, const int32_t* idx, int64_t n, void* dst,
+                       hipStream_t st);
+
+// y[i,:] = rmsnorm(x[map ? map[i] : i, :]) * w
+int launch_rmsnorm(const void* x, const int32_t* map, const void* w, void* y, int64_t n, int H,
+                   float eps, int dtype, hipStream_t st);
+
+int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
+                      const int32_t* src_row, const int32_t* dst_row, const int32_t* delta,
+                      int64_t n_tok, int Hkv, int D, const RopeFreq& f, int dtype, hipStream_t st);
+
+// Strided scatter of K/V rows: cache[dst_row[i]] = src[i * src_stride_elems ...]
+int launch_scatter_kv(const void* k_new, const void* v_new, int64_t src_stride_elems,
+                      const int32_t* dst_row, int64_t n, void* k_cache, void* v_cache, int Hkv, int D,
+                      int dtype, hipStream_t st);
+
+// From the unrounded float rows qkv32 [n, (Hq+2Hkv)*D]: q rotated at pos[i] -> q_out [n, Hq*D];
+// k rotated -> k_cache[slot[i]]; v -> v_cache[slot[i]].  Outputs have the storage type `dtype`
+// and are rounded once, after the rotation.
+int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t* slot, int64_t n, int Hq,
+                           int Hkv, int D, const RopeFreq& f, void* q_out, void* k_cache, void* v_cache,
+                           int dtype, hipStream_t st);
+
+// q rows have a row stride of q_stride elements (dense q: Hq*D).
+int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const void* v_cache,
+                     const int32_t* row_kv_start, const int32_t* row_kv_len, int64_t n, int Hq, int Hkv,
+                     int D, float scale, void* out, int dtype, hipStream_t st);
+
+enum Epilogue {
+  EPI_BIAS = 0,      // C = A W^T + bias[n]               (bias may be NULL)
+  EPI_RESIDUAL = 1,  // C = A W^T + resid[rmap ? rmap[m] : m, n]
+  EPI_SWIGLU = 2,    // W = [gate(I rows); up(I rows)], C[m, j] = silu(A Wg^T)[m,j] * (A Wu^T)[m,j], N = I
+  EPI_BIAS_F32 = 3   // as EPI_BIAS but C is a float matrix whatever the input type (no rounding)
+};
+// C[M,N] = epilogue(A[M,K] (row stride lda) * W[N(or 2N),K]^T); C row stride ldc.
+int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
+                int64_t K, int epilogue, const void* bias, const void* resid, int64_t ldr,
+                const int32_t* rmap, int dtype, hipStream_t st);
+
+}  // namespace vlc
+#endif

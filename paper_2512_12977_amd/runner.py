@@ -1,0 +1,108 @@
+"""Host-side driver around the C ABI: uploads tensors, builds per-layer plans with the library's
+own planner, and calls vlc_layer_forward layer by layer.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def torch_dtype(name: str):
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+
+
+def make_shape(sh) -> B.LayerShape:
+    """sh: any object with H, Hq, Hkv, D, I, dtype ('f32'|'bf16'), eps, rope_base."""
+    return B.LayerShape(sh.H, sh.Hq, sh.Hkv, sh.D, sh.I, B.VLC_BF16 if sh.dtype == "bf16" else B.VLC_F32,
+                        float(sh.eps), float(sh.rope_base))
+
+
+def segments_of(requests: Sequence) -> List[B.Segment]:
+    """Flatten requests (with .segments, .kv_start, .pos_start) into the ABI's segment records."""
+    out = []
+    for r in requests:
+        for s in r.segments:
+            out.append(B.Segment(r.kv_start + s.start, s.length, int(s.is_image), r.pos_start + s.start,
+                                 s.old_pos, s.cache_row, r.kv_start))
+    return out
+
+
+class DeviceWeights:
+    """One layer's weights on the GPU plus the pointer record the ABI takes."""
+
+    def __init__(self, W: Dict[str, Optional[np.ndarray]], dtype, device="cuda"):
+        self.t = {}
+        for name, a in W.items():
+            self.t[name] = None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(device=device, dtype=dtype)
+        self.rec = B.LayerWeights(*[None if self.t[n] is None else self.t[n].data_ptr()
+                                    for n in ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down")])
+
+    @classmethod
+    def random(cls, sh, dtype, seed: int, device="cuda") -> "DeviceWeights":
+        """Random-init weights generated on the device (throughput runs; values do not affect timing)."""
+        g = torch.Generator(device=device)
+        g.manual_seed(seed)
+        self = cls.__new__(cls)
+        nq = (sh.Hq + 2 * sh.Hkv) * sh.D
+        sizes = {"w_ln1": (sh.H,), "w_qkv": (nq, sh.H), "b_qkv": (nq,), "w_o": (sh.H, sh.Hq * sh.D),
+                 "w_ln2": (sh.H,), "w_gate_up": (2 * sh.I, sh.H), "w_down": (sh.H, sh.I)}
+        self.t = {}
+        for name, size in sizes.items():
+            if name == "b_qkv" and not sh.qkv_bias:
+                self.t[name] = None
+                continue
+            w = torch.randn(size, generator=g, device=device, dtype=torch.float32) * 0.02
+            if name in ("w_ln1", "w_ln2"):
+                w += 1.0
+            self.t[name] = w.to(dtype)
+        self.rec = B.LayerWeights(*[None if self.t[n] is None else self.t[n].data_ptr()
+                                    for n in ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down")])
+        return self
+
+
+class DevicePlans:
+    """Per-layer index arrays on the GPU, built by the library's host planner."""
+
+    def __init__(self, requests: Sequence, L: int, k=None, count_override=None, all_rows: bool = False,
+                 device="cuda"):
+        segs = segments_of(requests)
+        if all_rows:   # full recompute: rate 1.0 in every layer, nothing reused
+            k, count_override = np.full(L, 500, dtype=np.int32), None
+        self.host = B.vlc_plan_token_indices(segs, L, k=k, count_override=count_override)
+        self.reuse = B.vlc_plan_reuse_rows(segs, L, k=k, count_override=count_override)
+        self.L = L
+        self.total_slots = sum(s.length for s in segs)
+        self.n_rows = [int(v) for v in self.host["n_rows"]]
+        self.n_reuse = [int(v) for v in self.reuse["n_reuse"]]
+        self.dev = []
+        for l in range(L):
+            n, m = self.n_rows[l], self.n_reuse[l]
+            d = {name: torch.from_numpy(self.host[name][l, :n].copy()).to(device)
+                 for name in ("slot", "map", "pos", "kv_start", "kv_len")}
+            d.update({name: torch.from_numpy(self.reuse[name][l, :m].copy()).to(device)
+                      for name in ("src_row", "dst_slot", "delta")})
+            self.dev.append(d)
+
+    def record(self, l: int, n_in: int, kv_rows: int, k_pool=None, v_pool=None) -> B.LayerPlan:
+        d = self.dev[l]
+        n, m = self.n_rows[l], self.n_reuse[l]
+        p = lambda t: t.data_ptr() if t is not None and t.numel() else None
+        return B.LayerPlan(n_in, n, p(d["map"]), p(d["slot"]), p(d["pos"]), p(d["kv_start"]), p(d["kv_len"]),
+                           kv_rows, m if k_pool is not None else 0, p(d["src_row"]), p(d["dst_slot"]),
+                           p(d["delta"]), p(k_pool), p(v_pool), 0 if k_pool is None else k_pool.shape[0])
+
+
+class Workspace:
+    def __init__(self, shape_rec: B.LayerShape, n_rows_max: int, device="cuda"):
+        nbytes = B.vlc_layer_workspace_bytes(shape_rec, n_rows_max)
+        self.t = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        assert self.t.data_ptr() % 256 == 0
+
+
+def run_layer(shape_rec, weights: DeviceWeights, plan_rec, h_in, h_out, k_cache, v_cache, ws: Workspace,
+              stream=None) -> None:
+    B.vlc_layer_forward(shape_rec, weights.rec, plan_rec, h_in, h_out, k_cache, v_cache, ws.t, stream)

@@ -1,0 +1,193 @@
+"""GPU parity of the individual C-ABI kernels against the CPU oracle (needs an MI355X)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import vlc_oracle as orc
+import paper_2512_12977_amd as vlc
+from helpers import assert_close
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+TD = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def to_dev(a, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV).to(TD[dtype])
+
+
+def i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def back(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def stored(a, dtype):
+    """What the device holds after upload: the oracle's storage rounding of the float32 data."""
+    return orc.STORE[dtype](np.asarray(a, dtype=np.float32).astype(np.float64))
+
+
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,elems,n", [(37, 256, 61), (1600, 3584, 596), (5, 8, 1), (300, 8192, 257)])
+def test_gather_rows_bit_exact(dtype, rows, elems, n):
+    rng = np.random.default_rng(rows + n)
+    src = rng.standard_normal((rows, elems)).astype(np.float32)
+    idx = rng.integers(0, rows, size=n)
+    d_src = to_dev(src, dtype)
+    d_dst = torch.full((n, elems), 7.0, device=DEV, dtype=TD[dtype])
+    vlc.vlc_gather_rows(d_src, i32(idx), d_dst)
+    torch.cuda.synchronize()
+    # the selection itself is exact: compare bit patterns with plain indexing of the uploaded rows
+    assert torch.equal(d_dst, d_src[torch.from_numpy(idx).to(DEV)])
+    np.testing.assert_array_equal(back(d_dst), stored(src, dtype)[idx])
+
+
+def test_gather_rows_empty_and_errors():
+    src = torch.zeros((4, 8), device=DEV)
+    dst = torch.zeros((0, 8), device=DEV)
+    vlc.vlc_gather_rows(src, i32([]), dst)          # n = 0: no-op
+    with pytest.raises(vlc.VlcError) as e:          # 12-byte rows are not a multiple of 16
+        vlc.vlc_gather_rows(torch.zeros((4, 3), device=DEV), i32([0]), torch.zeros((1, 3), device=DEV))
+    assert e.value.code == 2
+
+
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("Hkv,D,base", [(2, 64, 1e4), (4, 128, 1e6), (8, 128, 1e6)])
+def test_rope_shift_kv_vs_oracle(dtype, Hkv, D, base):
+    rng = np.random.default_rng(Hkv * D)
+    pool, S, n = 300, 517, 211
+    ks = rng.standard_normal((pool, Hkv, D)).astype(np.float32)
+    vs = rng.standard_normal((pool, Hkv, D)).astype(np.float32)
+    src = rng.permutation(pool)[:n]
+    dst = rng.permutation(S)[:n]
+    delta = rng.integers(-20000, 20000, size=n)
+    delta[:3] = [0, 1, -1]
+    d_k = torch.zeros((S, Hkv, D), device=DEV, dtype=TD[dtype])
+    d_v = torch.zeros((S, Hkv, D), device=DEV, dtype=TD[dtype])
+    vlc.vlc_rope_shift_kv(to_dev(ks, dtype), to_dev(vs, dtype), d_k, d_v, i32(src), i32(dst), i32(delta), base)
+    torch.cuda.synchronize()
+    want_k = np.zeros((S, Hkv, D))
+    want_v = np.zeros((S, Hkv, D))
+    want_k[dst] = orc.STORE[dtype](orc.rope_rotate(stored(ks, dtype)[src], delta, base))
+    want_v[dst] = stored(vs, dtype)[src]
+    assert_close(back(d_k), want_k, dtype, "shifted K")
+    np.testing.assert_array_equal(back(d_v), want_v)            # values are copied, bit-exact
+    # delta 0 leaves keys bit-identical
+    np.testing.assert_array_equal(back(d_k)[dst[0]], stored(ks, dtype)[src[0]])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rope_shift_in_place_and_inverse(dtype):
+    """In-place use, and shift(d) followed by shift(-d) returns the keys (to storage rounding)."""
+    rng = np.random.default_rng(5)
+    S, Hkv, D, base = 130, 4, 128, 1e6
+    k0 = rng.standard_normal((S, Hkv, D)).astype(np.float32)
+    d_k = to_dev(k0, dtype)
+    rows = np.arange(S)
+    delta = rng.integers(-4000, 4000, size=S)
+    vlc.vlc_rope_shift_kv(d_k, None, d_k, None, i32(rows), i32(rows), i32(delta), base)
+    torch.cuda.synchronize()
+    assert_close(back(d_k), orc.STORE[dtype](orc.rope_rotate(stored(k0, dtype), delta, base)), dtype, "in place")
+    vlc.vlc_rope_shift_kv(d_k, None, d_k, None, i32(rows), i32(rows), i32(-delta), base)
+    torch.cuda.synchronize()
+    assert_close(back(d_k), stored(k0, dtype), dtype, "round trip")
+    if dtype == "f32":
+        assert np.max(np.abs(back(d_k) - k0)) < 5e-6
+
+
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_scatter_kv_bit_exact(dtype):
+    rng = np.random.default_rng(9)
+    S, n, Hkv, D = 1600, 596, 4, 128
+    kn = rng.standard_normal((n, Hkv, D)).astype(np.float32)
+    vn = rng.standard_normal((n, Hkv, D)).astype(np.float32)
+    kc = rng.standard_normal((S, Hkv, D)).astype(np.float32)
+    vc = rng.standard_normal((S, Hkv, D)).astype(np.float32)
+    dst = np.sort(rng.permutation(S)[:n])
+    d_kc, d_vc = to_dev(kc, dtype), to_dev(vc, dtype)
+    vlc.vlc_scatter_kv(to_dev(kn, dtype), to_dev(vn, dtype), i32(dst), d_kc, d_vc)
+    torch.cuda.synchronize()
+    want_k, want_v = stored(kc, dtype), stored(vc, dtype)
+    want_k[dst] = stored(kn, dtype)
+    want_v[dst] = stored(vn, dtype)
+    np.testing.assert_array_equal(back(d_kc), want_k)
+    np.testing.assert_array_equal(back(d_vc), want_v)
+
+
+# ------------------------------------------------------------------------------------------
+def attention_case(dtype, Hq, Hkv, D, requests, seed, lens_sorted=True):
+    """requests: list of (S, [query slots]).  Packed KV, per-row start/len, oracle per request."""
+    rng = np.random.default_rng(seed)
+    total = sum(S for S, _ in requests)
+    K = rng.standard_normal((total, Hkv, D)).astype(np.float32)
+    V = rng.standard_normal((total, Hkv, D)).astype(np.float32)
+    starts, lens, base = [], [], 0
+    for S, slots in requests:
+        for s in slots:
+            starts.append(base)
+            lens.append(s + 1 if s >= 0 else 0)
+        base += S
+    n = len(starts)
+    q = rng.standard_normal((n, Hq, D)).astype(np.float32)
+    d_out = torch.full((n, Hq, D), 3.0, device=DEV, dtype=TD[dtype])
+    scale = 1.0 / math.sqrt(D)
+    vlc.vlc_sparse_q_attention(to_dev(q, dtype), to_dev(K, dtype), to_dev(V, dtype), i32(starts), i32(lens),
+                               scale, d_out)
+    torch.cuda.synchronize()
+    want = np.zeros((n, Hq, D))
+    row, base = 0, 0
+    for S, slots in requests:
+        m = len(slots)
+        want[row:row + m] = orc.attention_rows(stored(q[row:row + m], dtype), stored(K[base:base + S], dtype),
+                                               stored(V[base:base + S], dtype),
+                                               np.asarray(lens[row:row + m]), scale)
+        row += m
+        base += S
+    want = orc.STORE[dtype](want)
+    return assert_close(back(d_out), want, dtype, "attention")
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,D", [("f32", 4, 2, 64), ("f32", 4, 4, 128), ("bf16", 28, 4, 128),
+                                           ("bf16", 64, 8, 128), ("bf16", 4, 2, 128), ("bf16", 3, 3, 128)])
+def test_attention_single_request_ragged(dtype, Hq, Hkv, D):
+    S = 333
+    slots = list(range(0, 40)) + [41, 44, 100, 101, 102, 199, 200] + list(range(310, 333))
+    attention_case(dtype, Hq, Hkv, D, [(S, slots)], seed=Hq * 7 + D)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,D", [("f32", 4, 2, 64), ("bf16", 28, 4, 128), ("bf16", 16, 2, 128)])
+def test_attention_packed_requests_share_tiles(dtype, Hq, Hkv, D):
+    """Three requests whose few rows land in the same row tile; includes a zero-length row and
+    a single-key row."""
+    reqs = [(70, [0, 5, 69]), (130, [-1, 0, 64, 65, 129]), (64, [63]), (200, list(range(150, 200)))]
+    attention_case(dtype, Hq, Hkv, D, reqs, seed=11)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_attention_unsorted_lengths_and_one_row(dtype):
+    D = 64 if dtype == "f32" else 128
+    attention_case(dtype, 4, 2, D, [(257, [256, 3, 128, 0, 77])], seed=3)
+    attention_case(dtype, 4, 2, D, [(65, [64])], seed=4)
+
+
+def test_attention_long_context_bf16():
+    """7B head layout, S = 4500: rows at the start of each 'image' and a trailing text run."""
+    S = 4500
+    slots = list(range(0, 30)) + [s for b in range(30, 4000, 1024) for s in range(b, b + 20)] + \
+        list(range(S - 120, S))
+    attention_case("bf16", 28, 4, 128, [(S, slots)], seed=21)
+
+
+def test_attention_errors():
+    q = torch.zeros((2, 4, 128), device=DEV, dtype=torch.bfloat16)
+    kv = torch.zeros((8, 3, 128), device=DEV, dtype=torch.bfloat16)
+    with pytest.raises(vlc.VlcError) as e:      # 4 query heads over 3 kv heads
+        vlc.vlc_sparse_q_attention(q, kv, kv, i32([0, 0]), i32([1, 2]), 1.0, torch.zeros_like(q))
+    assert e.value.code == 2

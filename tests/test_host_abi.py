@@ -1,0 +1,125 @@
+"""Host side of the C ABI (no GPU): the library loads, exports what the header declares, and its
+planner / index builders agree bit-for-bit with the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import vlc_synth as syn
+from oracle import vlc_oracle as orc
+import paper_2512_12977_amd as vlc
+from paper_2512_12977_amd.runner import segments_of
+from helpers import plan_steps, counts_for
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "vlcache.h")).read()
+    names = set(re.findall(r"\b(vlc_[a-z_]+)\s*\(", hdr))
+    assert {"vlc_plan_layer_rates", "vlc_gather_rows", "vlc_rope_shift_kv", "vlc_scatter_kv",
+            "vlc_sparse_q_attention", "vlc_layer_forward"} <= names
+    L = ctypes.CDLL(vlc.lib_path())
+    for n in sorted(names):
+        assert hasattr(L, n), n
+    assert vlc.lib().vlc_version() >= 100
+
+
+def test_planner_bit_exact_vs_oracle():
+    rng = np.random.default_rng(0)
+    for trial in range(40):
+        L, G = int(rng.integers(1, 40)), int(rng.integers(1, 151))
+        if trial % 3 == 0:
+            sens = rng.random((L, G + 1))
+        elif trial % 3 == 1:
+            sens = syn.sensitivity_table(L, G, trial)
+        else:   # many exact ties
+            sens = np.round(rng.random((L, G + 1)) * 4) / 4
+        B = int(rng.integers(0, L * G + 3))
+        np.testing.assert_array_equal(vlc.vlc_plan_layer_rates(sens, B), orc.plan_layer_rates(sens, B))
+    for L, bp in ((28, 500), (80, 300)):
+        sens = syn.sensitivity_table(L, 150, 1)
+        B = orc.budget_steps_from_mean_rate(bp, L)
+        np.testing.assert_array_equal(vlc.vlc_plan_layer_rates(sens, B), orc.plan_layer_rates(sens, B))
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_token_indices_bit_exact_vs_oracle(name):
+    wl = syn.make_workload(name)
+    L = wl.shape.L
+    k, explicit = plan_steps(wl)
+    segs = segments_of(wl.requests)
+    out = vlc.vlc_plan_token_indices(segs, L, k=k, count_override=explicit)
+    reuse = vlc.vlc_plan_reuse_rows(segs, L, k=k, count_override=explicit)
+    prev = None
+    for l in range(L):
+        slots, pos, start, klen, src, dst, delta = [], [], [], [], [], [], []
+        for req in wl.requests:
+            counts = counts_for(req, k, explicit, l)
+            s = orc.select_slots(req.segments, counts)
+            slots.append(req.kv_start + s)
+            pos.append(req.pos_start + s)
+            start.append(np.full(len(s), req.kv_start))
+            klen.append(s + 1)
+            rs, rr, ro = orc.reused_slots(req.segments, counts)
+            src.append(rr)
+            dst.append(req.kv_start + rs)
+            delta.append(req.pos_start + rs - ro)
+        slots = np.concatenate(slots)
+        n = int(out["n_rows"][l])
+        assert n == len(slots)
+        np.testing.assert_array_equal(out["slot"][l, :n], slots)
+        np.testing.assert_array_equal(out["pos"][l, :n], np.concatenate(pos))
+        np.testing.assert_array_equal(out["kv_start"][l, :n], np.concatenate(start))
+        np.testing.assert_array_equal(out["kv_len"][l, :n], np.concatenate(klen))
+        if l == 0:
+            np.testing.assert_array_equal(out["map"][l, :n], slots)
+        else:
+            np.testing.assert_array_equal(prev[out["map"][l, :n]], slots)
+        m = int(reuse["n_reuse"][l])
+        np.testing.assert_array_equal(reuse["src_row"][l, :m], np.concatenate(src))
+        np.testing.assert_array_equal(reuse["dst_slot"][l, :m], np.concatenate(dst))
+        np.testing.assert_array_equal(reuse["delta"][l, :m], np.concatenate(delta))
+        prev = slots
+
+
+def test_workload_row_counts():
+    """Row counts the benchmark configurations state."""
+    def rows(name):
+        wl = syn.make_workload(name)
+        k, explicit = plan_steps(wl)
+        out = vlc.vlc_plan_token_indices(segments_of(wl.requests), wl.shape.L, k=k, count_override=explicit)
+        return out["n_rows"]
+    assert list(rows("c1")) == [61, 61]
+    assert set(rows("c2")) == {596}
+    assert set(rows("c4")) == {8 * 2368} and set(rows("c4_5")) == {8 * 2864}
+
+
+def test_host_error_paths():
+    sens = np.ones((3, 5))
+    with pytest.raises(vlc.VlcError) as e:
+        vlc.vlc_plan_layer_rates(sens, -1)
+    assert e.value.code == 2
+    segs = [vlc.Segment(0, 10, 0, 0, 0, 0, 0), vlc.Segment(10, 50, 1, 10, 0, 0, 0)]
+    with pytest.raises(vlc.VlcError) as e:      # rate grows with depth
+        vlc.vlc_plan_token_indices(segs, 2, k=[10, 20])
+    assert e.value.code == 7
+    with pytest.raises(vlc.VlcError) as e:      # overlapping runs
+        vlc.vlc_plan_token_indices([segs[0], vlc.Segment(5, 5, 0, 5, 0, 0, 0)], 1, k=[0])
+    assert e.value.code == 4
+    with pytest.raises(vlc.VlcError) as e:      # capacity
+        vlc.vlc_plan_token_indices(segs, 1, k=[500], cap=20)
+    assert e.value.code == 2
+    with pytest.raises(vlc.VlcError) as e:      # k outside the grid
+        vlc.vlc_plan_token_indices(segs, 1, k=[501])
+    assert e.value.code == 2
+    # no rows at all is fine
+    out = vlc.vlc_plan_token_indices([vlc.Segment(0, 50, 1, 0, 0, 0, 0)], 2, k=[0, 0])
+    assert list(out["n_rows"]) == [0, 0]
+    # shape errors of the layer entry points are reported without touching a GPU
+    bad = vlc.LayerShape(256, 4, 3, 64, 512, 0, 1e-6, 1e4)
+    with pytest.raises(vlc.VlcError):
+        vlc.vlc_layer_workspace_bytes(bad, 10)
+    assert "Hq" in vlc.last_error()
