@@ -245,6 +245,22 @@ int vlc_layer_forward(const vlc_layer_shape* shape, const vlc_layer_weights* wei
                       const vlc_layer_plan* plan, const void* h_in, void* h_out, void* k_cache,
                       void* v_cache, void* workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * vlc_layer_forward with per-stage timing marks, for benchmarks: stage_events (host array of
+ * VLC_LAYER_STAGES + 1 hipEvent_t handles created by the caller) - event i is recorded on `stream`
+ * before stage i starts, the last one after the final stage.  Stages, in launch order:
+ *   0 reused K/V placement (RoPE shift)   1 input RMSNorm (reads h_in through map)
+ *   2 q|k|v projection                    3 RoPE of q,k + scatter of fresh k,v
+ *   4 attention of the recomputed rows    5 output projection + residual
+ *   6 post-attention RMSNorm              7 gate|up projection + SwiGLU     8 down projection + residual
+ * Everything else is identical to vlc_layer_forward.
+ */
+#define VLC_LAYER_STAGES 9
+int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_layer_weights* weights,
+                            const vlc_layer_plan* plan, const void* h_in, void* h_out, void* k_cache,
+                            void* v_cache, void* workspace, int64_t workspace_bytes, void* stream,
+                            void* const* stage_events);
+
 #ifdef __cplusplus
 }
 #endif

@@ -67,6 +67,7 @@ def lib():
                                                                 C.c_void_p, C.c_int, C.c_void_p]
         L.vlc_layer_workspace_layout.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
         L.vlc_layer_forward.argtypes = [C.c_void_p] * 8 + [C.c_int64, C.c_void_p]
+        L.vlc_layer_forward_timed.argtypes = [C.c_void_p] * 8 + [C.c_int64, C.c_void_p, C.c_void_p]
         _LIB = L
     return _LIB
 
@@ -216,3 +217,16 @@ def vlc_layer_forward(shape: LayerShape, weights: LayerWeights, plan: LayerPlan,
     _check(lib().vlc_layer_forward(C.addressof(shape), C.addressof(weights), C.addressof(plan), _dev(h_in),
                                    _dev(h_out), _dev(k_cache), _dev(v_cache), _dev(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+LAYER_STAGES = ("rope_shift", "rmsnorm1", "qkv_gemm", "rope_scatter", "attention", "o_gemm", "rmsnorm2",
+                "gate_up_swiglu_gemm", "down_gemm")
+
+
+def vlc_layer_forward_timed(shape: LayerShape, weights: LayerWeights, plan: LayerPlan, h_in, h_out, k_cache,
+                            v_cache, workspace, stage_events, stream=None) -> None:
+    """stage_events: ctypes array of len(LAYER_STAGES)+1 hipEvent_t handles (c_void_p)."""
+    _check(lib().vlc_layer_forward_timed(C.addressof(shape), C.addressof(weights), C.addressof(plan),
+                                         _dev(h_in), _dev(h_out), _dev(k_cache), _dev(v_cache), _dev(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream),
+                                         C.addressof(stage_events)))

@@ -45,86 +45,115 @@ __device__ __forceinline__ void tile_coords(int pid, int total, int tiles_m, int
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA kernel
 // ---------------------------------------------------------------------------------------------
-// Workgroup: 256 threads = 4 wavefronts in a 2 x 2 grid; wavefront tile (BM/2) x (BN/2) made of
-// 32x32 MFMA tiles.  The MFMA "A" operand is the W fragment and the "B" operand the activation
-// fragment, so an accumulator tile is indexed [n][m]: lane l holds, for m = l % 32, the outputs
-// n = 8*(j/4) + 4*(l/32) + j%4 (j = register index): four consecutive n per lane, i.e. 8
-// contiguous bytes of a C row.
+// Workgroup tile BM x BN, WGM x WGN wavefronts, wavefront tile (BM/WGM) x (BN/WGN) made of 32x32
+// MFMA tiles.  The MFMA "A" operand is the W fragment and the "B" operand the activation fragment,
+// so an accumulator tile is indexed [n][m]: lane l holds, for m = l % 32, the outputs
+// n = 8*(j/4) + 4*(l/32) + j%4 (j = register index): four consecutive n per lane, i.e. 8 contiguous
+// bytes of a bf16 C row.
 //
-// LDS holds [rows][64] bf16 tiles (128 B per row = 8 chunks of 16 B); the chunk index is XOR-ed
-// with a function of the row so that the 16-byte fragment reads of consecutive rows fall into
-// different banks.
+// Operands reach LDS straight from global memory (global_load_lds, 16 bytes per lane, no register
+// staging) through a ring of STAGES k-tiles of 64 columns, so the next k-tile is in flight while
+// the current one is consumed.  A wavefront-level load writes 64 consecutive 16-byte chunks of LDS
+// in lane order; the XOR swizzle that keeps the later 16-byte fragment reads of consecutive rows
+// in different banks is therefore applied on the global side (which chunk of its row each lane
+// fetches).  Fragments are double-buffered in registers across the four 16-wide k-steps.
+//
+// SPLIT > 1 (few output tiles): each workgroup reduces one contiguous range of k-tiles and
+// writes float partials; splitk_epilogue_kernel sums them and applies the epilogue.
 constexpr int BK = 64;
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row & 7) ^ ((row >> 3) & 1)); }
+__device__ __forceinline__ int fswz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(
+#define VLC_WAITCNT_VM(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
+
+enum { EPI_PARTIAL = 100 };   // internal: float partial sums of one k-range (split-K)
+
+template <int BM, int BN, int WGM, int WGN, int STAGES, int OCC, int EPI>
+__global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
     const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ W, uint16_t* __restrict__ C,
     int64_t ldc, int M, int N, int K, const uint16_t* __restrict__ bias, const uint16_t* __restrict__ resid,
-    int64_t ldr, const int32_t* __restrict__ rmap, int tiles_m, int tiles_n) {
-  constexpr int WM = BM / 2, WN = BN / 2;        // wavefront tile
-  constexpr int MT = WM / 32, NT = WN / 32;      // MFMA tiles per wavefront
-  constexpr int A_ITERS = BM / 32, W_ITERS = BN / 32;   // 16-byte chunks per thread per k-tile
+    int64_t ldr, const int32_t* __restrict__ rmap, int tiles_m, int tiles_n, int kt_per_split) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;      // wavefront tile
+  constexpr int MT = WM / 32, NT = WN / 32;        // MFMA tiles per wavefront
+  constexpr int STAGE_CHUNKS = (BM + BN) * 8;      // 16-byte chunks per stage
+  constexpr int A_INSTR = BM * 8 / 64 / NW, W_INSTR = BN * 8 / 64 / NW;   // wavefront loads per k-tile
+  constexpr int LOADS = A_INSTR + W_INSTR;
+  constexpr int KS = BK / 16;
   // columns of C covered by this tile: SwiGLU consumes a gate and an up row per output column
   constexpr int CN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  static_assert(STAGES >= 2 && STAGES <= 4, "ring depth");
+  static_assert(EPI != EPI_SWIGLU || NT % 2 == 0, "SwiGLU pairs tiles inside a wavefront");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u32x4* ldsA = reinterpret_cast<u32x4*>(smem);                     // [2][BM][8] chunks
-  u32x4* ldsW = reinterpret_cast<u32x4*>(smem) + 2 * BM * 8;        // [2][BN][8] chunks
+  u32x4* lds = reinterpret_cast<u32x4*>(smem);
 
+  const int tiles = tiles_m * tiles_n;
+  const int split = blockIdx.x / tiles;
   int tm, tn;
-  tile_coords(blockIdx.x, gridDim.x, tiles_m, tiles_n, &tm, &tn);
+  tile_coords(blockIdx.x - split * tiles, tiles, tiles_m, tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * CN;
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
   const int l32 = lane & 31, x = lane >> 5;
 
-  // ---- global -> register staging: thread handles chunk (tid % 8) of rows tid/8 + 32*i ----------
-  const int ld_row = tid >> 3, ld_chunk = tid & 7;
-  const u32x4* a_src[A_ITERS];
-  const u32x4* w_src[W_ITERS];
+  const int kt_begin = split * kt_per_split;
+  const int kt_end = min(K / BK, kt_begin + kt_per_split);
+  const int KT = kt_end - kt_begin;
+
+  // ---- per-lane global source of each of this wavefront's loads (k-tile kt_begin) ---------------
+  const uint16_t* a_src[A_INSTR];
+  const uint16_t* w_src[W_INSTR];
 #pragma unroll
-  for (int i = 0; i < A_ITERS; ++i) {
-    int r = m0 + ld_row + 32 * i;
-    r = r < M ? r : M - 1;                                  // ragged tail: re-read the last row
-    a_src[i] = reinterpret_cast<const u32x4*>(A + (int64_t)r * lda) + ld_chunk;
+  for (int i = 0; i < A_INSTR; ++i) {
+    const int p = (wave * A_INSTR + i) * 64 + lane;        // LDS chunk this lane fills
+    const int r = p >> 3, c = (p & 7) ^ fswz(r);
+    int gr = m0 + r;
+    gr = gr < M ? gr : M - 1;                              // ragged tail: re-read the last row
+    a_src[i] = A + (int64_t)gr * lda + (int64_t)kt_begin * BK + c * 8;
   }
 #pragma unroll
-  for (int i = 0; i < W_ITERS; ++i) {
-    const int lr = ld_row + 32 * i;                          // row inside the LDS W tile
-    int r;
-    if (EPI == EPI_SWIGLU) r = lr < BN / 2 ? n0 + lr : N + n0 + (lr - BN / 2);   // gate rows | up rows
-    else r = n0 + lr;
+  for (int i = 0; i < W_INSTR; ++i) {
+    const int p = (wave * W_INSTR + i) * 64 + lane;
+    const int r = p >> 3, c = (p & 7) ^ fswz(r);
+    int gr;
+    if constexpr (EPI == EPI_SWIGLU) gr = r < BN / 2 ? n0 + r : N + n0 + (r - BN / 2);   // gate | up rows
+    else gr = n0 + r;
     const int limit = (EPI == EPI_SWIGLU) ? 2 * N : N;
-    r = r < limit ? r : limit - 1;
-    w_src[i] = reinterpret_cast<const u32x4*>(W + (int64_t)r * K) + ld_chunk;
+    gr = gr < limit ? gr : limit - 1;
+    w_src[i] = W + (int64_t)gr * K + (int64_t)kt_begin * BK + c * 8;
   }
-  u32x4 a_reg[A_ITERS], w_reg[W_ITERS];
-
-#define VLC_LOAD_GLOBAL(kt_)                                                                 \
-  _Pragma("unroll") for (int i = 0; i < A_ITERS; ++i) a_reg[i] = a_src[i][(kt_) * (BK / 8)]; \
-  _Pragma("unroll") for (int i = 0; i < W_ITERS; ++i) w_reg[i] = w_src[i][(kt_) * (BK / 8)];
-#define VLC_STORE_LDS(buf_)                                                                 \
-  _Pragma("unroll") for (int i = 0; i < A_ITERS; ++i) {                                     \
-    const int r_ = ld_row + 32 * i;                                                         \
-    ldsA[((buf_) * BM + r_) * 8 + swz(r_, ld_chunk)] = a_reg[i];                            \
-  }                                                                                         \
-  _Pragma("unroll") for (int i = 0; i < W_ITERS; ++i) {                                     \
-    const int r_ = ld_row + 32 * i;                                                         \
-    ldsW[((buf_) * BN + r_) * 8 + swz(r_, ld_chunk)] = w_reg[i];                            \
+#define VLC_ISSUE(kt_, stage_)                                                                                   \
+  {                                                                                                              \
+    u32x4* sa_ = lds + (stage_) * STAGE_CHUNKS + wave * A_INSTR * 64;                                            \
+    u32x4* sw_ = lds + (stage_) * STAGE_CHUNKS + BM * 8 + wave * W_INSTR * 64;                                   \
+    _Pragma("unroll") for (int i = 0; i < A_INSTR; ++i)                                                          \
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_src[i] + (kt_) * BK),   \
+                                       (__attribute__((address_space(3))) void*)(sa_ + i * 64), 16, 0, 0);       \
+    _Pragma("unroll") for (int i = 0; i < W_INSTR; ++i)                                                          \
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(w_src[i] + (kt_) * BK),   \
+                                       (__attribute__((address_space(3))) void*)(sw_ + i * 64), 16, 0, 0);       \
   }
 
-  // LDS row of MFMA tile nt of this wavefront inside the W tile
-  int w_row[NT];
+  // fragment positions inside a stage (chunk units) for every 16-wide k-step
+  int w_off[NT][KS], a_off[MT][KS];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
+    int r;
     if constexpr (EPI == EPI_SWIGLU)
-      w_row[nt] = nt < NT / 2 ? wn * (WN / 2) + nt * 32 : BN / 2 + wn * (WN / 2) + (nt - NT / 2) * 32;
+      r = (nt < NT / 2 ? wn * (WN / 2) + nt * 32 : BN / 2 + wn * (WN / 2) + (nt - NT / 2) * 32) + l32;
     else
-      w_row[nt] = wn * WN + nt * 32;
+      r = wn * WN + nt * 32 + l32;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) w_off[nt][ks] = BM * 8 + r * 8 + ((2 * ks + x) ^ fswz(r));
+  }
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int r = wm * WM + mt * 32 + l32;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) a_off[mt][ks] = r * 8 + ((2 * ks + x) ^ fswz(r));
   }
 
   f32x16 acc[NT][MT];
@@ -135,43 +164,48 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int KT = K / BK;
-  VLC_LOAD_GLOBAL(0)
-  VLC_STORE_LDS(0)
-  __syncthreads();
-
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) { VLC_LOAD_GLOBAL(kt + 1) }
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 wf[NT], af[MT];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int r = w_row[nt] + l32;
-        const u32x4 v = ldsW[(buf * BN + r) * 8 + swz(r, 2 * ks + x)];
-        wf[nt] = __builtin_bit_cast(bf16x8, v);
-      }
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int r = wm * WM + mt * 32 + l32;
-        const u32x4 v = ldsA[(buf * BM + r) * 8 + swz(r, 2 * ks + x)];
-        af[mt] = __builtin_bit_cast(bf16x8, v);
-      }
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nt], af[mt], acc[nt][mt], 0, 0, 0);
-    }
-    if (kt + 1 < KT) { VLC_STORE_LDS(buf ^ 1) }
-    __syncthreads();
+#define VLC_COMPUTE_TILE(kt_)                                                                                    \
+  {                                                                                                              \
+    const u32x4* st_ = lds + ((kt_) % STAGES) * STAGE_CHUNKS;                                                    \
+    bf16x8 wf[2][NT], af[2][MT];                                                                                 \
+    _Pragma("unroll") for (int nt = 0; nt < NT; ++nt) wf[0][nt] = __builtin_bit_cast(bf16x8, st_[w_off[nt][0]]); \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) af[0][mt] = __builtin_bit_cast(bf16x8, st_[a_off[mt][0]]); \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                          \
+      if (ks + 1 < KS) {                                                                                         \
+        _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                        \
+          wf[(ks + 1) & 1][nt] = __builtin_bit_cast(bf16x8, st_[w_off[nt][ks + 1]]);                             \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                        \
+          af[(ks + 1) & 1][mt] = __builtin_bit_cast(bf16x8, st_[a_off[mt][ks + 1]]);                             \
+      }                                                                                                          \
+      _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                          \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                        \
+          acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][nt], af[ks & 1][mt], acc[nt][mt], 0, 0, 0); \
+    }                                                                                                            \
   }
-#undef VLC_LOAD_GLOBAL
-#undef VLC_STORE_LDS
+
+  // prologue: fill STAGES-1 stages
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < KT) VLC_ISSUE(s, s)
+  int kt = 0;
+  for (; kt + STAGES - 1 < KT; ++kt) {   // steady state: k-tile kt+STAGES-1 is fetched while kt is consumed
+    VLC_WAITCNT_VM((STAGES - 2) * LOADS);          // this wavefront's part of k-tile kt has landed
+    __syncthreads();                               // everyone's part has; stage (kt-1)%STAGES is free
+    VLC_ISSUE(kt + STAGES - 1, (kt + STAGES - 1) % STAGES)
+    VLC_COMPUTE_TILE(kt)
+  }
+  for (; kt < KT; ++kt) {                // drain
+    const int later = KT - 1 - kt;
+    if (later >= 2) { VLC_WAITCNT_VM(2 * LOADS); } else if (later == 1) { VLC_WAITCNT_VM(LOADS); } else { VLC_WAITCNT_VM(0); }
+    __syncthreads();
+    VLC_COMPUTE_TILE(kt)
+  }
+#undef VLC_ISSUE
+#undef VLC_COMPUTE_TILE
 
   // ---- epilogue ---------------------------------------------------------------------------------
   constexpr int ONT = (EPI == EPI_SWIGLU) ? NT / 2 : NT;   // output tiles along n per wavefront
+  constexpr int OWN = (EPI == EPI_SWIGLU) ? WN / 2 : WN;   // output columns per wavefront
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int m = m0 + wm * WM + mt * 32 + l32;
@@ -180,7 +214,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     if constexpr (EPI == EPI_RESIDUAL) rrow = rmap ? (int64_t)rmap[m] : (int64_t)m;
 #pragma unroll
     for (int nt = 0; nt < ONT; ++nt) {
-      const int nbase = n0 + ((EPI == EPI_SWIGLU) ? wn * (WN / 2) : wn * WN) + nt * 32 + 4 * x;
+      const int nbase = n0 + wn * OWN + nt * 32 + 4 * x;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int n = nbase + 8 * q;
@@ -188,6 +222,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[nt][mt][4 * q + e];
+        if constexpr (EPI == EPI_PARTIAL) {
+          float* P = reinterpret_cast<float*>(C) + ((int64_t)split * M + m) * ldc + n;
+          *reinterpret_cast<float4*>(P) = make_float4(v[0], v[1], v[2], v[3]);
+          continue;
+        }
         if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_F32) {
           if (bias) {
             const uint2 b = *reinterpret_cast<const uint2*>(bias + n);
@@ -198,13 +237,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
           const uint2 b = *reinterpret_cast<const uint2*>(resid + rrow * ldr + n);
           v[0] += __uint_as_float(b.x << 16); v[1] += __uint_as_float(b.x & 0xffff0000u);
           v[2] += __uint_as_float(b.y << 16); v[3] += __uint_as_float(b.y & 0xffff0000u);
-        } else {
+        } else if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = silu_f(v[e]) * acc[nt + NT / 2][mt][4 * q + e];
         }
         if constexpr (EPI == EPI_BIAS_F32) {   // unrounded float output (C is a float matrix)
-          float4 o = make_float4(v[0], v[1], v[2], v[3]);
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + (int64_t)m * ldc + n) = o;
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + (int64_t)m * ldc + n) =
+              make_float4(v[0], v[1], v[2], v[3]);
         } else {
           uint2 o;
           o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
@@ -213,6 +252,45 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
         }
       }
     }
+  }
+}
+
+// Sum of the split-K partials [splits][M][N] (float) + epilogue; one thread per 4 columns.
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float* __restrict__ P, int splits,
+                                                              uint16_t* __restrict__ C, int64_t ldc, int M, int N,
+                                                              const uint16_t* __restrict__ bias,
+                                                              const uint16_t* __restrict__ resid, int64_t ldr,
+                                                              const int32_t* __restrict__ rmap) {
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int nq = N / 4;
+  const int64_t m = id / nq;
+  const int n = (int)(id - m * nq) * 4;
+  if (m >= M) return;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int k = 0; k < splits; ++k) {
+    const float4 p = *reinterpret_cast<const float4*>(P + ((int64_t)k * M + m) * N + n);
+    s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+  }
+  if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_F32) {
+    if (bias) {
+      const uint2 b = *reinterpret_cast<const uint2*>(bias + n);
+      s.x += __uint_as_float(b.x << 16); s.y += __uint_as_float(b.x & 0xffff0000u);
+      s.z += __uint_as_float(b.y << 16); s.w += __uint_as_float(b.y & 0xffff0000u);
+    }
+  } else if constexpr (EPI == EPI_RESIDUAL) {
+    const int64_t rrow = rmap ? (int64_t)rmap[m] : m;
+    const uint2 b = *reinterpret_cast<const uint2*>(resid + rrow * ldr + n);
+    s.x += __uint_as_float(b.x << 16); s.y += __uint_as_float(b.x & 0xffff0000u);
+    s.z += __uint_as_float(b.y << 16); s.w += __uint_as_float(b.y & 0xffff0000u);
+  }
+  if constexpr (EPI == EPI_BIAS_F32) {
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + m * ldc + n) = s;
+  } else {
+    uint2 o;
+    o.x = f32_to_bf16(s.x) | (f32_to_bf16(s.y) << 16);
+    o.y = f32_to_bf16(s.z) | (f32_to_bf16(s.w) << 16);
+    *reinterpret_cast<uint2*>(C + m * ldc + n) = o;
   }
 }
 
@@ -282,34 +360,69 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
   }
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int OCC, int EPI>
 int launch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
-                int64_t K, const void* bias, const void* resid, int64_t ldr, const int32_t* rmap,
-                hipStream_t st) {
+                int64_t K, const void* bias, const void* resid, int64_t ldr, const int32_t* rmap, int splits,
+                int kt_per_split, hipStream_t st) {
   constexpr int CN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + CN - 1) / CN);
-  const size_t lds = (size_t)2 * (BM + BN) * BK * 2;
-  auto kern = gemm_bf16_kernel<BM, BN, EPI>;
+  const size_t lds = (size_t)STAGES * (BM + BN) * BK * 2;
+  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, STAGES, OCC, EPI>;
   static bool attr_set = false;    // raising the dynamic LDS limit is per kernel, once per process
   if (!attr_set) {
     VLC_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), lds, st, (const uint16_t*)A, lda,
-                     (const uint16_t*)W, (uint16_t*)C, ldc, (int)M, (int)N, (int)K, (const uint16_t*)bias,
-                     (const uint16_t*)resid, ldr, rmap, tiles_m, tiles_n);
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(WGM * WGN * 64), lds, st, (const uint16_t*)A,
+                     lda, (const uint16_t*)W, (uint16_t*)C, ldc, (int)M, (int)N, (int)K, (const uint16_t*)bias,
+                     (const uint16_t*)resid, ldr, rmap, tiles_m, tiles_n, kt_per_split);
   VLC_CHECK_LAUNCH("gemm_bf16");
   return VLC_OK;
 }
 
+// Tile choice.  Many rows: 256 x 256 tiles, 8 wavefronts.  Few rows: 128 x 128 tiles, 4 wavefronts, two
+// workgroups per CU; if that still leaves most of the 256 CUs idle, the k range is split as well.
 template <int EPI>
 int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
                   int64_t K, const void* bias, const void* resid, int64_t ldr, const int32_t* rmap,
-                  hipStream_t st) {
-  // Few rows: 128-row tiles waste less of the ragged tail and put more workgroups on the chip.
-  if (M <= 1024) return launch_bf16<128, 256, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, st);
-  return launch_bf16<256, 256, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, st);
+                  void* splitk_ws, int64_t splitk_ws_bytes, hipStream_t st) {
+  const int KT = (int)(K / BK);
+  if (M >= 1536)
+    return launch_bf16<256, 256, 2, 4, 2, 1, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, st);
+  constexpr int CN = (EPI == EPI_SWIGLU) ? 64 : 128;
+  const int64_t tiles = ((M + 127) / 128) * ((N + CN - 1) / CN);
+  int splits = 1;
+  if constexpr (EPI != EPI_SWIGLU) {
+    if (splitk_ws && tiles < 384) {
+      // 512 workgroups are resident at once (two per CU): pick the split count that minimises
+      // (rounds of resident workgroups) x (k-tiles per workgroup), keeping >= 8 k-tiles per split.
+      int64_t best = (int64_t)((tiles + 511) / 512) * KT;
+      for (int sp = 2; sp <= 8; ++sp) {
+        if (KT / sp < 8 || (int64_t)sp * M * N * 4 > splitk_ws_bytes) break;
+        const int64_t cost = ((tiles * sp + 511) / 512) * ((KT + sp - 1) / sp) + 2;   // +2: second launch
+        if (cost < best) {
+          best = cost;
+          splits = sp;
+        }
+      }
+    }
+  }
+  if (splits <= 1)
+    return launch_bf16<128, 128, 2, 2, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, st);
+  if constexpr (EPI != EPI_SWIGLU) {
+    const int per = (KT + splits - 1) / splits;
+    splits = (KT + per - 1) / per;
+    int rc = launch_bf16<128, 128, 2, 2, 2, 2, EPI_PARTIAL>(A, lda, W, splitk_ws, N, M, N, K, nullptr, nullptr, 0,
+                                                            nullptr, splits, per, st);
+    if (rc) return rc;
+    const int64_t threads = M * (N / 4);
+    hipLaunchKernelGGL(splitk_epilogue_kernel<EPI>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                       (const float*)splitk_ws, splits, (uint16_t*)C, ldc, (int)M, (int)N, (const uint16_t*)bias,
+                       (const uint16_t*)resid, ldr, rmap);
+    VLC_CHECK_LAUNCH("splitk_epilogue");
+  }
+  return VLC_OK;
 }
 
 template <int EPI>
@@ -326,9 +439,16 @@ int launch_f32(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, 
 
 }  // namespace
 
+// Split-K only runs when a GEMM has fewer than 384 tiles of 128 x 128, and then uses about
+// 512 / tiles splits: splits * M * N floats stay below 2 * 512 * 128 * 128 * 4 bytes.
+int64_t gemm_splitk_ws_bytes(int64_t n_rows, int64_t max_n) {
+  (void)max_n;
+  return n_rows < 1536 ? (int64_t)64 << 20 : 0;
+}
+
 int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
                 int64_t K, int epilogue, const void* bias, const void* resid, int64_t ldr,
-                const int32_t* rmap, int dtype, hipStream_t st) {
+                const int32_t* rmap, int dtype, void* splitk_ws, int64_t splitk_ws_bytes, hipStream_t st) {
   if (M <= 0 || N <= 0) return VLC_OK;
   if (K <= 0) return fail(VLC_ERR_SHAPE, "gemm: K=%lld", (long long)K);
   if (M > INT32_MAX || N > INT32_MAX / 2 || K > INT32_MAX)
@@ -338,10 +458,10 @@ int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
     if (N % 4 || lda % 8 || ldc % 4 || (epilogue == EPI_RESIDUAL && ldr % 4))
       return fail(VLC_ERR_SHAPE, "gemm(bf16): N, lda, ldc, ldr must keep 8-byte (A: 16-byte) alignment");
     switch (epilogue) {
-      case EPI_BIAS: return dispatch_bf16<EPI_BIAS>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, st);
-      case EPI_BIAS_F32: return dispatch_bf16<EPI_BIAS_F32>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, st);
-      case EPI_RESIDUAL: return dispatch_bf16<EPI_RESIDUAL>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, st);
-      case EPI_SWIGLU: return dispatch_bf16<EPI_SWIGLU>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, st);
+      case EPI_BIAS: return dispatch_bf16<EPI_BIAS>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, st);
+      case EPI_BIAS_F32: return dispatch_bf16<EPI_BIAS_F32>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, st);
+      case EPI_RESIDUAL: return dispatch_bf16<EPI_RESIDUAL>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, st);
+      case EPI_SWIGLU: return dispatch_bf16<EPI_SWIGLU>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, st);
     }
   } else if (dtype == VLC_F32) {
     switch (epilogue) {

@@ -11,7 +11,7 @@ namespace {
 inline int64_t align256(int64_t b) { return (b + 255) & ~(int64_t)255; }
 
 struct Workspace {
-  int64_t xn, qkv32, q, attn, h1, n2, act, total;   // byte offsets
+  int64_t xn, qkv32, q, attn, h1, n2, act, splitk, splitk_bytes, total;   // byte offsets
 };
 
 Workspace layout(const vlc_layer_shape& s, int64_t n) {
@@ -26,6 +26,9 @@ Workspace layout(const vlc_layer_shape& s, int64_t n) {
   w.h1 = at;   at += align256(n * s.H * es);          // hidden after the attention residual
   w.n2 = at;   at += align256(n * s.H * es);          // post-attention-normed activations
   w.act = at;  at += align256(n * (int64_t)s.I * es); // SwiGLU product
+  w.splitk = at;                                      // float partials of split-K GEMMs (few rows only)
+  w.splitk_bytes = s.dtype == VLC_BF16 ? vlc::gemm_splitk_ws_bytes(n, nqkv) : 0;
+  at += align256(w.splitk_bytes);
   w.total = at;
   return w;
 }
@@ -65,10 +68,16 @@ extern "C" int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t 
   return VLC_OK;
 }
 
-extern "C" int vlc_layer_forward(const vlc_layer_shape* shape, const vlc_layer_weights* w,
-                                 const vlc_layer_plan* p, const void* h_in, void* h_out, void* k_cache,
-                                 void* v_cache, void* workspace, int64_t workspace_bytes, void* stream) {
+static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weights* w,
+                              const vlc_layer_plan* p, const void* h_in, void* h_out, void* k_cache,
+                              void* v_cache, void* workspace, int64_t workspace_bytes, void* stream,
+                              void* const* ev) {
   const char* who = "vlc_layer_forward";
+  // optional stage timing: ev[i] is recorded before stage i, ev[VLC_LAYER_STAGES] after the last
+#define VLC_MARK(i)                                                                     \
+  do {                                                                                  \
+    if (ev) VLC_CHECK_HIP(hipEventRecord((hipEvent_t)ev[i], (hipStream_t)stream));      \
+  } while (0)
   int rc = check_shape(shape, who);
   if (rc) return rc;
   if (!w || !p) return fail(VLC_ERR_NULL, "%s: weights or plan is NULL", who);
@@ -83,6 +92,7 @@ extern "C" int vlc_layer_forward(const vlc_layer_shape* shape, const vlc_layer_w
   hipStream_t st = (hipStream_t)stream;
   const vlc::RopeFreq freq = vlc::make_rope_freq(s.rope_base, s.D);
 
+  VLC_MARK(0);
   // Reused image tokens: keys rotated by the position delta, values copied (independent of the rows).
   if (p->n_reuse > 0) {
     rc = vlc::launch_rope_shift(p->k_pool, p->v_pool, k_cache, v_cache, p->reuse_src, p->reuse_dst,
@@ -90,7 +100,10 @@ extern "C" int vlc_layer_forward(const vlc_layer_shape* shape, const vlc_layer_w
     if (rc) return rc;
   }
   const int64_t n = p->n;
-  if (n == 0) return VLC_OK;
+  if (n == 0) {
+    for (int i = 1; i <= VLC_LAYER_STAGES; ++i) VLC_MARK(i);
+    return VLC_OK;
+  }
   if (!w->w_ln1 || !w->w_qkv || !w->w_o || !w->w_ln2 || !w->w_gate_up || !w->w_down)
     return fail(VLC_ERR_NULL, "%s: a weight pointer is NULL", who);
   if (!p->map || !p->slot || !p->pos || !p->row_kv_start || !p->row_kv_len || !h_in || !h_out)
@@ -109,29 +122,60 @@ extern "C" int vlc_layer_forward(const vlc_layer_shape* shape, const vlc_layer_w
   void* h1 = base + ws.h1;
   void* n2 = base + ws.n2;
   void* act = base + ws.act;
+  void* skw = ws.splitk_bytes ? base + ws.splitk : nullptr;
   const int64_t H = s.H, nqkv = (int64_t)(s.Hq + 2 * s.Hkv) * s.D, hqd = (int64_t)s.Hq * s.D, I = s.I;
 
   // x = h_in[map] is never materialised: the norm reads through the map, and so does the residual.
+  VLC_MARK(1);
   rc = vlc::launch_rmsnorm(h_in, p->map, w->w_ln1, xn, n, s.H, s.eps, s.dtype, st);
   if (rc) return rc;
+  VLC_MARK(2);
   rc = vlc::launch_gemm(xn, H, w->w_qkv, qkv32, nqkv, n, nqkv, H, vlc::EPI_BIAS_F32, w->b_qkv, nullptr, 0,
-                        nullptr, s.dtype, st);
+                        nullptr, s.dtype, skw, ws.splitk_bytes, st);
   if (rc) return rc;
   // RoPE at the new positions; fresh k, v overwrite their slots (after the reused tokens were placed).
+  VLC_MARK(3);
   rc = vlc::launch_rope_qk_scatter(qkv32, p->pos, p->slot, n, s.Hq, s.Hkv, s.D, freq, qrot, k_cache, v_cache,
                                    s.dtype, st);
   if (rc) return rc;
+  VLC_MARK(4);
   rc = vlc::launch_attention(qrot, hqd, k_cache, v_cache, p->row_kv_start, p->row_kv_len, n, s.Hq, s.Hkv, s.D,
                              1.0f / sqrtf((float)s.D), attn, s.dtype, st);
   if (rc) return rc;
+  VLC_MARK(5);
   rc = vlc::launch_gemm(attn, hqd, w->w_o, h1, H, n, H, hqd, vlc::EPI_RESIDUAL, nullptr, h_in, H, p->map,
-                        s.dtype, st);
+                        s.dtype, skw, ws.splitk_bytes, st);
   if (rc) return rc;
+  VLC_MARK(6);
   rc = vlc::launch_rmsnorm(h1, nullptr, w->w_ln2, n2, n, s.H, s.eps, s.dtype, st);
   if (rc) return rc;
+  VLC_MARK(7);
   rc = vlc::launch_gemm(n2, H, w->w_gate_up, act, I, n, I, H, vlc::EPI_SWIGLU, nullptr, nullptr, 0, nullptr,
-                        s.dtype, st);
+                        s.dtype, skw, ws.splitk_bytes, st);
   if (rc) return rc;
-  return vlc::launch_gemm(act, I, w->w_down, h_out, H, n, H, I, vlc::EPI_RESIDUAL, nullptr, h1, H, nullptr,
-                          s.dtype, st);
+  VLC_MARK(8);
+  rc = vlc::launch_gemm(act, I, w->w_down, h_out, H, n, H, I, vlc::EPI_RESIDUAL, nullptr, h1, H, nullptr,
+                        s.dtype, skw, ws.splitk_bytes, st);
+  if (rc) return rc;
+  VLC_MARK(9);
+  return VLC_OK;
+#undef VLC_MARK
+}
+
+extern "C" int vlc_layer_forward(const vlc_layer_shape* shape, const vlc_layer_weights* w,
+                                 const vlc_layer_plan* p, const void* h_in, void* h_out, void* k_cache,
+                                 void* v_cache, void* workspace, int64_t workspace_bytes, void* stream) {
+  return layer_forward_impl(shape, w, p, h_in, h_out, k_cache, v_cache, workspace, workspace_bytes, stream,
+                            nullptr);
+}
+
+extern "C" int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_layer_weights* w,
+                                       const vlc_layer_plan* p, const void* h_in, void* h_out, void* k_cache,
+                                       void* v_cache, void* workspace, int64_t workspace_bytes, void* stream,
+                                       void* const* stage_events) {
+  if (!stage_events) return fail(VLC_ERR_NULL, "vlc_layer_forward_timed: stage_events is NULL");
+  for (int i = 0; i <= VLC_LAYER_STAGES; ++i)
+    if (!stage_events[i]) return fail(VLC_ERR_NULL, "vlc_layer_forward_timed: stage_events[%d] is NULL", i);
+  return layer_forward_impl(shape, w, p, h_in, h_out, k_cache, v_cache, workspace, workspace_bytes, stream,
+                            stage_events);
 }

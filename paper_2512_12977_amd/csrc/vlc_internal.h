@@ -73,9 +73,12 @@ enum Epilogue {
   EPI_BIAS_F32 = 3   // as EPI_BIAS but C is a float matrix whatever the input type (no rounding)
 };
 // C[M,N] = epilogue(A[M,K] (row stride lda) * W[N(or 2N),K]^T); C row stride ldc.
+// splitk_ws: optional float scratch for split-K partials (used when the output has few tiles);
+// gemm_splitk_ws_bytes gives a size that lets every GEMM of a layer with n rows split freely.
 int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
                 int64_t K, int epilogue, const void* bias, const void* resid, int64_t ldr,
-                const int32_t* rmap, int dtype, hipStream_t st);
+                const int32_t* rmap, int dtype, void* splitk_ws, int64_t splitk_ws_bytes, hipStream_t st);
+int64_t gemm_splitk_ws_bytes(int64_t n_rows, int64_t max_n);
 
 }  // namespace vlc
 #endif

@@ -106,3 +106,17 @@ class Workspace:
 def run_layer(shape_rec, weights: DeviceWeights, plan_rec, h_in, h_out, k_cache, v_cache, ws: Workspace,
               stream=None) -> None:
     B.vlc_layer_forward(shape_rec, weights.rec, plan_rec, h_in, h_out, k_cache, v_cache, ws.t, stream)
+
+
+def plan_for(wl):
+    """(k per layer | None, explicit leading-token count per layer | None) of a workload description,
+    through the library's planner.  A mean-rate budget of bp basis points over L layers is
+    bp * L / 20 grid steps of 0.002 (integer floor)."""
+    L = wl.shape.L
+    if wl.plan == "static":
+        return np.full(L, wl.static_k, dtype=np.int32), None
+    if wl.plan == "explicit":
+        return None, np.full(L, wl.explicit_counts, dtype=np.int32)
+    import vlc_synth as syn
+    sens = syn.sensitivity_table(L, 150, 1)
+    return B.vlc_plan_layer_rates(sens, (int(wl.budget_bp) * L) // 20), None
