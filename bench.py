@@ -112,6 +112,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full", action="store_true", help="skip the full-recompute comparison")
     ap.add_argument("--cpu-layers", type=int, default=None, help="layers of the oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, run one plain row copy of 1 GiB through vlc_gather_rows "
+                         "(identity index) so a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (requests are independent and "
@@ -264,6 +267,15 @@ def main() -> int:
         torch.cuda.synchronize()
         full_ms = hev.elapsed_ms(e2[0], e2[1]) / fsteps
         hev.destroy(e2)
+
+    if args.calibrate_copy:
+        rows_c, elems_c = 1 << 17, 4096                      # 2^17 rows x 8 KiB = 1 GiB read + 1 GiB written
+        src_c = torch.ones((rows_c, elems_c), device=dev, dtype=torch.bfloat16)
+        dst_c = torch.empty_like(src_c)
+        idx_c = torch.arange(rows_c, device=dev, dtype=torch.int32)
+        vlc.vlc_gather_rows(src_c, idx_c, dst_c)
+        torch.cuda.synchronize()
+        del src_c, dst_c, idx_c
 
     # ---- CPU oracle on a bounded sample --------------------------------------------------------------
     cpu = None

@@ -15,6 +15,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 __device__ __forceinline__ uint32_t f32_to_bf16(float f) {   // round to nearest, ties to even
   uint32_t u = __float_as_uint(f);
@@ -27,7 +29,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32_t
 // bf16 MFMA kernel, D = 128
 // ---------------------------------------------------------------------------------------------
 // Tile: VR = 128 "virtual rows" = (query row, head of the kv group) pairs, head fastest; 4 wavefronts
-// of 32 virtual rows each.  Keys are consumed in blocks of 64.
+// of 32 virtual rows each, two workgroups per CU.  Keys are consumed in blocks of 64.
 //
 // Both products are computed transposed so that every lane owns exactly one virtual row:
 //   S^T[key, vr] = K[key, :] . Q[vr, :]      MFMA A = K fragment (LDS), B = Q fragment (registers)
@@ -36,28 +38,33 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32_t
 // so a row's running max / sum / rescale factor are per-lane scalars and the only cross-lane step is
 // one exchange between lanes l and l^32.  The S^T accumulators feed the second MFMA directly: its
 // contraction index is just a relabeling of keys, as long as the V^T fragment uses the same
-// relabeling, which is how V^T is laid out in LDS (see v_pos below).
+// relabeling, which is how V^T is laid out in LDS.
+//
+// K/V blocks go through a two-stage LDS ring: while block kb is consumed, the K tile of block kb+1
+// is copied global -> LDS directly (the XOR swizzle is applied by permuting which 16-byte chunk each
+// lane fetches) and the V tile of block kb+1 is fetched into registers, then written transposed.
 constexpr int ATT_D = 128;
 constexpr int KB = 64;        // keys per block
 constexpr int VR = 128;       // virtual rows per workgroup
+constexpr int K_TILE_CHUNKS = KB * 16;      // [64 keys][16 chunks of 8 d]
+constexpr int V_TILE_CHUNKS = ATT_D * 8;    // [128 d][8 chunks of 8 key positions]
+constexpr int ATT_STAGE_CHUNKS = K_TILE_CHUNKS + V_TILE_CHUNKS;
 
-// K tile in LDS: [64 keys][16 chunks of 8 d], chunk XOR-swizzled by the key.
-__device__ __forceinline__ int k_off(int key, int chunk) { return key * 16 + (chunk ^ (key & 15)); }
-// V^T tile in LDS: [128 d][8 chunks of 8 key positions], chunk swizzled by d.
+// V^T tile in LDS: chunk swizzled by d.
 __device__ __forceinline__ int vt_chunk(int d, int chunk) { return chunk ^ ((d & 7) ^ ((d >> 3) & 7)); }
 
-__global__ __launch_bounds__(256) void attention_bf16_kernel(
+#define VLC_ATT_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8) | (0 << 14))
+
+__global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
     const uint16_t* __restrict__ q, int64_t q_stride, const uint16_t* __restrict__ kc,
     const uint16_t* __restrict__ vc, const int32_t* __restrict__ row_kv_start,
     const int32_t* __restrict__ row_kv_len, int n, int Hq, int Hkv, int g, int rows_per_tile,
     float scale_log2, uint16_t* __restrict__ out) {
-  __shared__ u32x4 ldsK[KB * 16];            // 16 KB
-  __shared__ u32x4 ldsV[ATT_D * 8];          // 16 KB, transposed
+  __shared__ u32x4 lds[2 * ATT_STAGE_CHUNKS];     // 64 KB
   __shared__ int s_start[VR];
   __shared__ int s_len[VR];
-  __shared__ int s_red[4];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, x = lane >> 5;
   const int kvh = blockIdx.y;
   const int row0 = blockIdx.x * rows_per_tile;
@@ -99,6 +106,19 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 
   const int64_t kv_row_elems = (int64_t)Hkv * ATT_D;
 
+  // K tile: this lane fills LDS chunks (wave*4 + i)*64 + lane, i < 4, i.e. key = chunk / 16 and the
+  // logical 8-element chunk c = (chunk % 16) ^ (key % 16) of that key's 128 d.
+  int k_key[4], k_c[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int p = (wave * 4 + i) * 64 + lane;
+    k_key[i] = p >> 4;
+    k_c[i] = (p & 15) ^ (k_key[i] & 15);
+  }
+  // V tile: this lane owns 4 keys (group kg) x 8 d (chunk dc) and writes them transposed
+  const int v_dc = tid & 15, v_kg = tid >> 4;
+  const int v_chunk = 2 * (v_kg >> 2) + (v_kg & 1), v_half = (v_kg >> 1) & 1;
+
   // Rows of different requests (different row_kv_start) may share a tile: handle one run of equal
   // start at a time; lanes outside the run see every key masked.
   int seg_begin = 0;
@@ -122,112 +142,136 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const uint16_t* kbase = kc + (int64_t)seg_start * kv_row_elems + (int64_t)kvh * ATT_D;
     const uint16_t* vbase = vc + (int64_t)seg_start * kv_row_elems + (int64_t)kvh * ATT_D;
     const int n_blocks = (seg_max + KB - 1) / KB;
+    const int last_key = seg_max - 1;               // loads never leave the run's key range
+
+    u32x4 vreg[4];
+#define VLC_ATT_ISSUE(kb_, stage_)                                                                             \
+  {                                                                                                            \
+    const int key0_ = (kb_) * KB;                                                                              \
+    u32x4* sk_ = lds + (stage_) * ATT_STAGE_CHUNKS + wave * 256;                                               \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                            \
+      const int gk_ = min(key0_ + k_key[i], last_key);                                                         \
+      __builtin_amdgcn_global_load_lds(                                                                        \
+          (const __attribute__((address_space(1))) void*)(kbase + (int64_t)gk_ * kv_row_elems + k_c[i] * 8),   \
+          (__attribute__((address_space(3))) void*)(sk_ + i * 64), 16, 0, 0);                                  \
+    }                                                                                                          \
+    _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                                            \
+      const int gk_ = min(key0_ + 4 * v_kg + b, last_key);                                                     \
+      vreg[b] = *(reinterpret_cast<const u32x4*>(vbase + (int64_t)gk_ * kv_row_elems) + v_dc);                 \
+    }                                                                                                          \
+  }
+    // key = 16*t + 8*a + 4*xx + b  ->  position 16*t + 8*xx + 4*a + b  (chunk 2t+xx, half a)
+#define VLC_ATT_WRITE_V(stage_)                                                                                \
+  {                                                                                                            \
+    u32x4* sv_ = lds + (stage_) * ATT_STAGE_CHUNKS + K_TILE_CHUNKS;                                            \
+    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                            \
+      const int d_ = 8 * v_dc + i;                                                                             \
+      uint32_t e_[4];                                                                                          \
+      _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                                          \
+        const uint32_t w_ = vreg[b][i >> 1];                                                                   \
+        e_[b] = (i & 1) ? (w_ >> 16) : (w_ & 0xffffu);                                                         \
+      }                                                                                                        \
+      u32x2 pr_;                                                                                               \
+      pr_[0] = e_[0] | (e_[1] << 16);                                                                          \
+      pr_[1] = e_[2] | (e_[3] << 16);                                                                          \
+      *(reinterpret_cast<u32x2*>(&sv_[d_ * 8 + vt_chunk(d_, v_chunk)]) + v_half) = pr_;                        \
+    }                                                                                                          \
+  }
+
+    __syncthreads();                 // the ring is free (previous run finished reading it)
+    if (n_blocks > 0) {
+      VLC_ATT_ISSUE(0, 0)
+      VLC_ATT_WRITE_V(0)
+      VLC_ATT_WAIT_VM0();
+    }
+    __syncthreads();
 
     for (int kb = 0; kb < n_blocks; ++kb) {
       const int key0 = kb * KB;
-      __syncthreads();     // previous block's fragments are no longer needed
-      // ---- K tile: thread handles chunk tid%16 of keys tid/16 + 16*i -------------------------
+      const int stage = kb & 1;
+      const bool more = kb + 1 < n_blocks;
+      if (more) VLC_ATT_ISSUE(kb + 1, stage ^ 1)
+
+      if (key0 < w_max) {              // something visible for this wavefront in this block
+        const u32x4* sk = lds + stage * ATT_STAGE_CHUNKS;
+        const u32x4* sv = sk + K_TILE_CHUNKS;
+        // ---- S^T = K Q^T -----------------------------------------------------------------------
+        f32x16 st[2];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = (tid >> 4) + 16 * i;
-        const int gk = min(key0 + key, seg_max - 1);          // stay inside the request's range
-        const u32x4 v = *(reinterpret_cast<const u32x4*>(kbase + (int64_t)gk * kv_row_elems) + (tid & 15));
-        ldsK[k_off(key, tid & 15)] = v;
-      }
-      // ---- V tile, transposed: thread handles 4 keys (group kg) x 8 d (chunk dc) -------------
-      {
-        const int dc = tid & 15, kg = tid >> 4;
-        u32x4 rowv[4];
+        for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const int gk = min(key0 + 4 * kg + b, seg_max - 1);
-          rowv[b] = *(reinterpret_cast<const u32x4*>(vbase + (int64_t)gk * kv_row_elems) + dc);
-        }
-        // key = 16*t + 8*a + 4*xx + b  ->  position 16*t + 8*xx + 4*a + b  (chunk 2t+xx, half a)
-        const int t = kg >> 2, a = (kg >> 1) & 1, xx = kg & 1;
-        const int chunk = 2 * t + xx;
+          for (int e = 0; e < 16; ++e) st[mt][e] = 0.f;
+          const int key = 32 * mt + l32;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int d = 8 * dc + i;
-          uint32_t e[4];
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const uint32_t w = rowv[b][i >> 1];
-            e[b] = (i & 1) ? (w >> 16) : (w & 0xffffu);
+          for (int ks = 0; ks < ATT_D / 16; ++ks) {
+            const u32x4 kv = sk[key * 16 + ((2 * ks + x) ^ (key & 15))];
+            st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[ks], st[mt], 0, 0, 0);
           }
-          u32x2 pr;
-          pr[0] = e[0] | (e[1] << 16);
-          pr[1] = e[2] | (e[3] << 16);
-          u32x2* dst = reinterpret_cast<u32x2*>(&ldsV[d * 8 + vt_chunk(d, chunk)]) + a;
-          *dst = pr;
         }
+        // ---- online softmax (base 2) -------------------------------------------------------------
+        if (key0 + KB > w_min) {       // some lane has keys of this block beyond its range
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const int key = key0 + 32 * mt + 8 * (j >> 2) + 4 * x + (j & 3);
+              st[mt][j] = key < len ? st[mt][j] : -INFINITY;
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) mx = fmaxf(mx, st[mt][j]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;          // scale > 0: max commutes with it
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // m_run = -inf -> 0
+        const bool grew = m_new > m_run;
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(st[mt][j], scale_log2, -m_use));
+            st[mt][j] = p;
+            psum += p;
+          }
+        l_run = l_run * alpha + psum;
+        if (__any(grew)) {             // rescale only when some row's maximum moved
+#pragma unroll
+          for (int i = 0; i < ATT_D / 32; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+        }
+        // ---- O^T += V^T P^T ----------------------------------------------------------------------
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          bf16x8 pf;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            f32x2 pr = {st[t >> 1][8 * (t & 1) + 2 * e], st[t >> 1][8 * (t & 1) + 2 * e + 1]};
+            const bf16x2 pb = __builtin_convertvector(pr, bf16x2);
+            pf[2 * e] = pb[0];
+            pf[2 * e + 1] = pb[1];
+          }
+#pragma unroll
+          for (int md = 0; md < ATT_D / 32; ++md) {
+            const int d = 32 * md + l32;
+            const u32x4 vv = sv[d * 8 + vt_chunk(d, 2 * t + x)];
+            o_acc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, o_acc[md], 0, 0, 0);
+          }
+        }
+      }
+      if (more) {
+        VLC_ATT_WRITE_V(stage ^ 1)     // waits for the V registers of block kb+1
+        VLC_ATT_WAIT_VM0();            // and for this wavefront's share of its K tile
       }
       __syncthreads();
-
-      if (key0 >= w_max) continue;     // nothing visible for this wavefront in this block
-
-      // ---- S^T = K Q^T -------------------------------------------------------------------------
-      f32x16 st[2];
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) st[mt][e] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < ATT_D / 16; ++ks) {
-          const u32x4 kv = ldsK[k_off(32 * mt + l32, 2 * ks + x)];
-          st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[ks], st[mt], 0, 0, 0);
-        }
-      }
-      // ---- online softmax (base 2) --------------------------------------------------------------
-      const bool need_mask = key0 + KB > w_min;
-      float mx = -INFINITY;
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          float s = st[mt][j] * scale_log2;
-          if (need_mask) {
-            const int key = key0 + 32 * mt + 8 * (j >> 2) + 4 * x + (j & 3);
-            s = key < len ? s : -INFINITY;
-          }
-          st[mt][j] = s;
-          mx = fmaxf(mx, s);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);          // m_run = -inf -> 0
-      m_run = m_new;
-      float psum = 0.f;
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const float p = __builtin_amdgcn_exp2f(st[mt][j] - m_use);
-          st[mt][j] = p;
-          psum += p;
-        }
-      l_run = l_run * alpha + psum;
-#pragma unroll
-      for (int i = 0; i < ATT_D / 32; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
-      // ---- O^T += V^T P^T -----------------------------------------------------------------------
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        u32x4 pw;
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          pw[e] = pack_bf16x2(st[t >> 1][8 * (t & 1) + 2 * e], st[t >> 1][8 * (t & 1) + 2 * e + 1]);
-        const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-        for (int md = 0; md < ATT_D / 32; ++md) {
-          const int d = 32 * md + l32;
-          const u32x4 vv = ldsV[d * 8 + vt_chunk(d, 2 * t + x)];
-          o_acc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, o_acc[md], 0, 0, 0);
-        }
-      }
     }
+#undef VLC_ATT_ISSUE
+#undef VLC_ATT_WRITE_V
     seg_begin = seg_end;
   }
 
@@ -240,9 +284,11 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     for (int md = 0; md < ATT_D / 32; ++md)
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
+        f32x2 a0 = {o_acc[md][4 * qd] * inv, o_acc[md][4 * qd + 1] * inv};
+        f32x2 a1 = {o_acc[md][4 * qd + 2] * inv, o_acc[md][4 * qd + 3] * inv};
         u32x2 w;
-        w[0] = pack_bf16x2(o_acc[md][4 * qd] * inv, o_acc[md][4 * qd + 1] * inv);
-        w[1] = pack_bf16x2(o_acc[md][4 * qd + 2] * inv, o_acc[md][4 * qd + 3] * inv);
+        w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a0, bf16x2));
+        w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a1, bf16x2));
         *reinterpret_cast<u32x2*>(op + 32 * md + 8 * qd + 4 * x) = w;
       }
   }

@@ -267,11 +267,15 @@ __global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float* __res
   const int64_t m = id / nq;
   const int n = (int)(id - m * nq) * 4;
   if (m >= M) return;
+  // all loads first (independent), then the sum in split order
+  float4 part[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (k < splits) part[k] = *reinterpret_cast<const float4*>(P + ((int64_t)k * M + m) * N + n);
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int k = 0; k < splits; ++k) {
-    const float4 p = *reinterpret_cast<const float4*>(P + ((int64_t)k * M + m) * N + n);
-    s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
-  }
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (k < splits) { s.x += part[k].x; s.y += part[k].y; s.z += part[k].z; s.w += part[k].w; }
   if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_F32) {
     if (bias) {
       const uint2 b = *reinterpret_cast<const uint2*>(bias + n);

@@ -51,26 +51,44 @@ template <> struct Chunk<uint16_t> {   // bf16
 
 // sin/cos of delta * inv_freq.  The angle is formed and reduced to [-pi, pi] in double (positions
 // reach tens of thousands of radians, beyond what a float angle resolves), then evaluated in float.
+// FAST (bf16 storage, 8 significant bits): the hardware sine/cosine, which take the angle in
+// revolutions; otherwise the library routines on the reduced angle.
+template <bool FAST>
 __device__ __forceinline__ void rope_sincos(double inv_freq, int delta, float* s, float* c) {
   double rev = (double)delta * inv_freq * 0.15915494309189535;   // angle / 2pi
   rev -= rint(rev);
-  const float r = (float)(rev * 6.283185307179586);
-  *s = sinf(r);
-  *c = cosf(r);
+  if (FAST) {
+    *s = __builtin_amdgcn_sinf((float)rev);
+    *c = __builtin_amdgcn_cosf((float)rev);
+  } else {
+    const float r = (float)(rev * 6.283185307179586);
+    *s = sinf(r);
+    *c = cosf(r);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
 // gather / scatter of whole rows in 16-byte chunks
 // ---------------------------------------------------------------------------------------------
 // dst chunk (i, c) = src chunk (src_idx ? src_idx[i] : i, c) written at row (dst_idx ? dst_idx[i] : i).
-// Row strides are given in chunks.  Each thread moves UNROLL chunks, all loads issued first.
+// Row strides are given in chunks.  Each thread moves UNROLL chunks, all loads issued first
+// (plain cached accesses: non-temporal ones measured half the rate here).  blockIdx.y selects one of up to two
+// (src, dst) pairs that share the index arrays (K and V of a scatter go in one launch).
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
 template <int UNROLL>
-__global__ __launch_bounds__(kThreads) void copy_rows_kernel(
-    const uint4* __restrict__ src, int64_t src_stride, const int32_t* __restrict__ src_idx,
-    uint4* __restrict__ dst, int64_t dst_stride, const int32_t* __restrict__ dst_idx, uint32_t total,
-    uint32_t chunks_per_row) {
+__global__ __launch_bounds__(kThreads) void copy_rows_kernel(const u32x4* __restrict__ src0,
+                                                             const u32x4* __restrict__ src1,
+                                                             u32x4* __restrict__ dst0, u32x4* __restrict__ dst1,
+                                                             int64_t src_stride,
+                                                             const int32_t* __restrict__ src_idx,
+                                                             int64_t dst_stride,
+                                                             const int32_t* __restrict__ dst_idx, uint32_t total,
+                                                             uint32_t chunks_per_row) {
+  const u32x4* __restrict__ src = blockIdx.y ? src1 : src0;
+  u32x4* __restrict__ dst = blockIdx.y ? dst1 : dst0;
   const uint32_t base = blockIdx.x * (uint32_t)(kThreads * UNROLL) + threadIdx.x;
-  uint4 v[UNROLL];
+  u32x4 v[UNROLL];
   int64_t off[UNROLL];
 #pragma unroll
   for (int u = 0; u < UNROLL; ++u) {
@@ -90,8 +108,9 @@ __global__ __launch_bounds__(kThreads) void copy_rows_kernel(
     if (off[u] >= 0) dst[off[u]] = v[u];
 }
 
-int copy_rows(const void* src, int64_t src_stride_bytes, const int32_t* src_idx, void* dst,
-              int64_t dst_stride_bytes, const int32_t* dst_idx, int64_t n, int64_t row_bytes,
+// One or two row copies (same row count, strides and index arrays) in a single launch.
+int copy_rows(const void* src0, const void* src1, int64_t src_stride_bytes, const int32_t* src_idx, void* dst0,
+              void* dst1, int64_t dst_stride_bytes, const int32_t* dst_idx, int64_t n, int64_t row_bytes,
               hipStream_t st, const char* name) {
   constexpr int UNROLL = 4;
   const int64_t cpr = row_bytes / 16;
@@ -102,11 +121,13 @@ int copy_rows(const void* src, int64_t src_stride_bytes, const int32_t* src_idx,
     const int64_t rows = (n - r0 < rows_per_launch) ? n - r0 : rows_per_launch;
     const uint32_t total = (uint32_t)(rows * cpr);
     const uint32_t blocks = (total + kThreads * UNROLL - 1) / (kThreads * UNROLL);
-    const uint4* s = reinterpret_cast<const uint4*>(
-        static_cast<const char*>(src) + (src_idx ? 0 : r0 * src_stride_bytes));
-    uint4* d = reinterpret_cast<uint4*>(static_cast<char*>(dst) + (dst_idx ? 0 : r0 * dst_stride_bytes));
-    hipLaunchKernelGGL(copy_rows_kernel<UNROLL>, dim3(blocks), dim3(kThreads), 0, st, s,
-                       src_stride_bytes / 16, src_idx ? src_idx + r0 : nullptr, d, dst_stride_bytes / 16,
+    const int64_t so = src_idx ? 0 : r0 * src_stride_bytes, dof = dst_idx ? 0 : r0 * dst_stride_bytes;
+    const u32x4* s0 = reinterpret_cast<const u32x4*>(static_cast<const char*>(src0) + so);
+    u32x4* d0 = reinterpret_cast<u32x4*>(static_cast<char*>(dst0) + dof);
+    const u32x4* s1 = src1 ? reinterpret_cast<const u32x4*>(static_cast<const char*>(src1) + so) : nullptr;
+    u32x4* d1 = dst1 ? reinterpret_cast<u32x4*>(static_cast<char*>(dst1) + dof) : nullptr;
+    hipLaunchKernelGGL(copy_rows_kernel<UNROLL>, dim3(blocks, src1 ? 2 : 1), dim3(kThreads), 0, st, s0, s1, d0, d1,
+                       src_stride_bytes / 16, src_idx ? src_idx + r0 : nullptr, dst_stride_bytes / 16,
                        dst_idx ? dst_idx + r0 : nullptr, total, (uint32_t)cpr);
     VLC_CHECK_LAUNCH(name);
   }
@@ -135,7 +156,7 @@ __global__ __launch_bounds__(kThreads) void rope_shift_kernel(
   const int d = delta[tok];
   float sn[VEC], cs[VEC];
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) rope_sincos(freq.inv_freq[c * VEC + i], d, &sn[i], &cs[i]);
+  for (int i = 0; i < VEC; ++i) rope_sincos<sizeof(T) == 2>(freq.inv_freq[c * VEC + i], d, &sn[i], &cs[i]);
   const int64_t row_chunks = (int64_t)Hkv * HEAD_CHUNKS;
   const uint4* ks = k_src + srow * row_chunks + c;
   uint4* kd = k_dst + drow * row_chunks + c;
@@ -168,9 +189,6 @@ __global__ __launch_bounds__(kThreads) void rope_shift_kernel(
   }
 }
 
-// ---------------------------------------------------------------------------------------------
-// RoPE of fresh q/k rows + scatter of fresh k/v into the cache
-// ---------------------------------------------------------------------------------------------
 // One thread owns VEC rotation pairs of up to HB consecutive heads of one row of the fused q|k|v
 // matrix (unrounded float).  Head index < Hq: query, rotated, written to q_out.  < Hq+Hkv: key,
 // rotated and written to its cache slot (the blend).  Otherwise: value, written to its cache slot.
@@ -193,7 +211,7 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
   const int p = pos[row];
   float sn[VEC], cs[VEC];
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) rope_sincos(freq.inv_freq[c * VEC + i], p, &sn[i], &cs[i]);
+  for (int i = 0; i < VEC; ++i) rope_sincos<sizeof(T) == 2>(freq.inv_freq[c * VEC + i], p, &sn[i], &cs[i]);
   const float* r = qkv + row * ((int64_t)heads * D) + c * VEC;
   uint4* qo = q_out + row * ((int64_t)Hq * HEAD_CHUNKS) + c;
   const int64_t dst = (int64_t)slot[row] * ((int64_t)Hkv * HEAD_CHUNKS) + c;
@@ -284,7 +302,7 @@ __global__ __launch_bounds__(kThreads) void rmsnorm_kernel(const uint4* __restri
 // ---------------------------------------------------------------------------------------------
 int launch_gather_rows(const void* src, int64_t row_bytes, const int32_t* idx, int64_t n, void* dst,
                        hipStream_t st) {
-  return copy_rows(src, row_bytes, idx, dst, row_bytes, nullptr, n, row_bytes, st, "gather_rows");
+  return copy_rows(src, nullptr, row_bytes, idx, dst, nullptr, row_bytes, nullptr, n, row_bytes, st, "gather_rows");
 }
 
 int launch_scatter_kv(const void* k_new, const void* v_new, int64_t src_stride_elems,
@@ -292,11 +310,8 @@ int launch_scatter_kv(const void* k_new, const void* v_new, int64_t src_stride_e
                       int dtype, hipStream_t st) {
   const int64_t es = elem_size(dtype);
   const int64_t row_bytes = (int64_t)Hkv * D * es;
-  int rc = copy_rows(k_new, src_stride_elems * es, nullptr, k_cache, row_bytes, dst_row, n, row_bytes, st,
-                     "scatter_kv(K)");
-  if (rc) return rc;
-  return copy_rows(v_new, src_stride_elems * es, nullptr, v_cache, row_bytes, dst_row, n, row_bytes, st,
-                   "scatter_kv(V)");
+  return copy_rows(k_new, v_new, src_stride_elems * es, nullptr, k_cache, v_cache, row_bytes, dst_row, n,
+                   row_bytes, st, "scatter_kv");
 }
 
 int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
