@@ -55,11 +55,16 @@ __device__ __forceinline__ int vt_chunk(int d, int chunk) { return chunk ^ ((d &
 
 #define VLC_ATT_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8) | (0 << 14))
 
+// SPLIT: blockIdx.z handles every nsplit-th share of each run's key blocks and leaves an
+// un-normalised partial (O as float, running max, running sum) for attention_merge_kernel; used when
+// there are too few (row tile, kv head) pairs to occupy the chip and the key loop is the critical path.
+template <bool SPLIT>
 __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
     const uint16_t* __restrict__ q, int64_t q_stride, const uint16_t* __restrict__ kc,
     const uint16_t* __restrict__ vc, const int32_t* __restrict__ row_kv_start,
     const int32_t* __restrict__ row_kv_len, int n, int Hq, int Hkv, int g, int rows_per_tile,
-    float scale_log2, uint16_t* __restrict__ out) {
+    float scale_log2, uint16_t* __restrict__ out, int nsplit, float* __restrict__ part_o,
+    float* __restrict__ part_ml) {
   __shared__ u32x4 lds[2 * ATT_STAGE_CHUNKS];     // 64 KB
   __shared__ int s_start[VR];
   __shared__ int s_len[VR];
@@ -141,7 +146,13 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
 
     const uint16_t* kbase = kc + (int64_t)seg_start * kv_row_elems + (int64_t)kvh * ATT_D;
     const uint16_t* vbase = vc + (int64_t)seg_start * kv_row_elems + (int64_t)kvh * ATT_D;
-    const int n_blocks = (seg_max + KB - 1) / KB;
+    const int all_blocks = (seg_max + KB - 1) / KB;
+    int kb_first = 0, n_blocks = all_blocks;        // this workgroup's share of the run's key blocks
+    if (SPLIT) {
+      const int per = (all_blocks + nsplit - 1) / nsplit;
+      kb_first = min(all_blocks, (int)blockIdx.z * per);
+      n_blocks = min(all_blocks, kb_first + per) - kb_first;
+    }
     const int last_key = seg_max - 1;               // loads never leave the run's key range
 
     u32x4 vreg[4];
@@ -180,17 +191,17 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
 
     __syncthreads();                 // the ring is free (previous run finished reading it)
     if (n_blocks > 0) {
-      VLC_ATT_ISSUE(0, 0)
+      VLC_ATT_ISSUE(kb_first, 0)
       VLC_ATT_WRITE_V(0)
       VLC_ATT_WAIT_VM0();
     }
     __syncthreads();
 
     for (int kb = 0; kb < n_blocks; ++kb) {
-      const int key0 = kb * KB;
+      const int key0 = (kb_first + kb) * KB;
       const int stage = kb & 1;
       const bool more = kb + 1 < n_blocks;
-      if (more) VLC_ATT_ISSUE(kb + 1, stage ^ 1)
+      if (more) VLC_ATT_ISSUE(kb_first + kb + 1, stage ^ 1)
 
       if (key0 < w_max) {              // something visible for this wavefront in this block
         const u32x4* sk = lds + stage * ATT_STAGE_CHUNKS;
@@ -277,6 +288,23 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
 
   // ---- normalise and store: lane holds d = 32*md + 8*(j/4) + 4*x + j%4 of its virtual row ------
   const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (SPLIT) {
+    if (vr_ok) {
+      const int64_t rh = ((int64_t)blockIdx.z * n + (row0 + r_local)) * Hq + head;
+      float* po = part_o + rh * ATT_D;
+#pragma unroll
+      for (int md = 0; md < ATT_D / 32; ++md)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd)
+          *reinterpret_cast<float4*>(po + 32 * md + 8 * qd + 4 * x) =
+              make_float4(o_acc[md][4 * qd], o_acc[md][4 * qd + 1], o_acc[md][4 * qd + 2], o_acc[md][4 * qd + 3]);
+      if (x == 0) {
+        part_ml[2 * rh] = m_run;
+        part_ml[2 * rh + 1] = l_tot;
+      }
+    }
+    return;
+  }
   if (vr_ok) {
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     uint16_t* op = out + ((int64_t)(row0 + r_local) * Hq + head) * ATT_D;
@@ -292,6 +320,39 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
         *reinterpret_cast<u32x2*>(op + 32 * md + 8 * qd + 4 * x) = w;
       }
   }
+}
+
+// Merge of the split partials: out = sum_z O_z 2^(m_z - m) / sum_z l_z 2^(m_z - m), m = max_z m_z.
+// One thread per 8 output elements.
+__global__ __launch_bounds__(256) void attention_merge_kernel(const float* __restrict__ part_o,
+                                                              const float* __restrict__ part_ml, int nsplit,
+                                                              int64_t rows_heads, uint16_t* __restrict__ out) {
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t rh = id / (ATT_D / 8);
+  const int c = (int)(id - rh * (ATT_D / 8));
+  if (rh >= rows_heads) return;
+  float m = -INFINITY;
+  for (int z = 0; z < nsplit; ++z) m = fmaxf(m, part_ml[2 * (z * rows_heads + rh)]);
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float l = 0.f;
+  for (int z = 0; z < nsplit; ++z) {
+    const float mz = part_ml[2 * (z * rows_heads + rh)];
+    if (mz == -INFINITY) continue;                     // this share saw no visible key
+    const float w = __builtin_amdgcn_exp2f(mz - m);
+    l += part_ml[2 * (z * rows_heads + rh) + 1] * w;
+    const float4* po = reinterpret_cast<const float4*>(part_o + (z * rows_heads + rh) * ATT_D + 8 * c);
+    const float4 a = po[0], b = po[1];
+    acc[0] += a.x * w; acc[1] += a.y * w; acc[2] += a.z * w; acc[3] += a.w * w;
+    acc[4] += b.x * w; acc[5] += b.y * w; acc[6] += b.z * w; acc[7] += b.w * w;
+  }
+  const float inv = l > 0.f ? 1.0f / l : 0.f;
+  u32x4 w4;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    f32x2 pr = {acc[2 * e] * inv, acc[2 * e + 1] * inv};
+    w4[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+  }
+  *reinterpret_cast<u32x4*>(out + rh * ATT_D + 8 * c) = w4;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -366,9 +427,17 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float* __restri
 
 }  // namespace
 
+int64_t attention_ws_bytes(int64_t n, int Hq, int Hkv, int D, int dtype) {
+  if (dtype != VLC_BF16 || D != ATT_D || Hq % Hkv || Hq / Hkv > VR) return 0;
+  const int64_t wgs = ((n + VR / (Hq / Hkv) - 1) / (VR / (Hq / Hkv))) * Hkv;
+  if (wgs >= 256 || n <= 0) return 0;                  // enough workgroups without splitting
+  const int64_t nsplit = 8;
+  return nsplit * n * Hq * (ATT_D + 2) * 4;
+}
+
 int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const void* v_cache,
                      const int32_t* row_kv_start, const int32_t* row_kv_len, int64_t n, int Hq, int Hkv,
-                     int D, float scale, void* out, int dtype, hipStream_t st) {
+                     int D, float scale, void* out, int dtype, void* ws, int64_t ws_bytes, hipStream_t st) {
   if (n <= 0) return VLC_OK;
   const int g = Hq / Hkv;
   if (dtype == VLC_BF16) {
@@ -376,10 +445,34 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
     if (g > VR) return fail(VLC_ERR_SHAPE, "attention(bf16): Hq/Hkv=%d exceeds %d", g, VR);
     if (q_stride % 8) return fail(VLC_ERR_SHAPE, "attention(bf16): q row stride must be a multiple of 8");
     const int rows_per_tile = VR / g;
-    const dim3 grid((unsigned)((n + rows_per_tile - 1) / rows_per_tile), (unsigned)Hkv);
-    hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
+    const int64_t tiles = (n + rows_per_tile - 1) / rows_per_tile;
+    // Few workgroups: split the key range so that about 512 are resident (two per CU).
+    int nsplit = 1;
+    if (ws && tiles * Hkv < 256) {
+      nsplit = (int)((512 + tiles * Hkv - 1) / (tiles * Hkv));
+      if (nsplit > 8) nsplit = 8;
+      while (nsplit > 1 && (int64_t)nsplit * n * Hq * (ATT_D + 2) * 4 > ws_bytes) --nsplit;
+    }
+    if (nsplit > 1) {
+      float* part_o = static_cast<float*>(ws);
+      float* part_ml = part_o + (int64_t)nsplit * n * Hq * ATT_D;
+      const dim3 grid((unsigned)tiles, (unsigned)Hkv, (unsigned)nsplit);
+      hipLaunchKernelGGL(attention_bf16_kernel<true>, grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
+                         (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
+                         Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, nsplit, part_o,
+                         part_ml);
+      VLC_CHECK_LAUNCH("attention_bf16(split)");
+      const int64_t threads = n * Hq * (ATT_D / 8);
+      hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, part_o,
+                         part_ml, nsplit, n * Hq, (uint16_t*)out);
+      VLC_CHECK_LAUNCH("attention_merge");
+      return VLC_OK;
+    }
+    const dim3 grid((unsigned)tiles, (unsigned)Hkv);
+    hipLaunchKernelGGL(attention_bf16_kernel<false>, grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
                        (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
-                       Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out);
+                       Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, 1, nullptr,
+                       nullptr);
     VLC_CHECK_LAUNCH("attention_bf16");
     return VLC_OK;
   }
@@ -418,5 +511,5 @@ extern "C" int vlc_sparse_q_attention(const void* q, const void* k_cache, const 
   if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15)
     return fail(VLC_ERR_SHAPE, "vlc_sparse_q_attention: pointers must be 16-byte aligned");
   return vlc::launch_attention(q, (int64_t)Hq * D, k_cache, v_cache, row_kv_start, row_kv_len, n, Hq, Hkv, D,
-                               scale, out, dtype, (hipStream_t)stream);
+                               scale, out, dtype, nullptr, 0, (hipStream_t)stream);
 }

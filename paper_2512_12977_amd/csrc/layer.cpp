@@ -11,7 +11,7 @@ namespace {
 inline int64_t align256(int64_t b) { return (b + 255) & ~(int64_t)255; }
 
 struct Workspace {
-  int64_t xn, qkv32, q, attn, h1, n2, act, splitk, splitk_bytes, total;   // byte offsets
+  int64_t xn, qkv32, q, attn, h1, n2, act, splitk, splitk_bytes, att, att_bytes, total;   // byte offsets
 };
 
 Workspace layout(const vlc_layer_shape& s, int64_t n) {
@@ -29,6 +29,9 @@ Workspace layout(const vlc_layer_shape& s, int64_t n) {
   w.splitk = at;                                      // float partials of split-K GEMMs (few rows only)
   w.splitk_bytes = s.dtype == VLC_BF16 ? vlc::gemm_splitk_ws_bytes(n, nqkv) : 0;
   at += align256(w.splitk_bytes);
+  w.att = at;                                         // partials of key-split attention (few rows only)
+  w.att_bytes = vlc::attention_ws_bytes(n, s.Hq, s.Hkv, s.D, s.dtype);
+  at += align256(w.att_bytes);
   w.total = at;
   return w;
 }
@@ -54,7 +57,23 @@ extern "C" int64_t vlc_layer_workspace_bytes(const vlc_layer_shape* shape, int64
     fail(VLC_ERR_SHAPE, "vlc_layer_workspace_bytes: n_rows_max=%lld", (long long)n_rows_max);
     return 0;
   }
-  return layout(*shape, n_rows_max).total;
+  // The row buffers grow with n; the two scratch areas exist only for small n.  A workspace sized
+  // here must serve every call with n <= n_rows_max: take the row buffers at n_rows_max and the
+  // largest scratch any smaller n can ask for.
+  const vlc_layer_shape& s = *shape;
+  const Workspace top = layout(s, n_rows_max);
+  const int64_t rows_only = top.splitk;                               // scratch areas come last
+  int64_t scratch = top.total - rows_only;
+  const int64_t g = s.Hq / s.Hkv;
+  const int64_t rows_per_tile = g <= 128 ? 128 / g : 1;
+  int64_t n_small = ((256 + s.Hkv - 1) / s.Hkv - 1) * rows_per_tile;  // largest n whose attention may split
+  if (n_small > 1535) n_small = 1535;                                 // and split-K never runs from 1536 on
+  if (n_small > n_rows_max) n_small = n_rows_max;
+  for (int64_t n : {n_small, n_rows_max < 1535 ? n_rows_max : (int64_t)1535}) {
+    const Workspace w = layout(s, n);
+    if (w.total - w.splitk > scratch) scratch = w.total - w.splitk;
+  }
+  return rows_only + scratch;
 }
 
 extern "C" int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t n_rows, int64_t* offsets) {
@@ -140,7 +159,8 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
   if (rc) return rc;
   VLC_MARK(4);
   rc = vlc::launch_attention(qrot, hqd, k_cache, v_cache, p->row_kv_start, p->row_kv_len, n, s.Hq, s.Hkv, s.D,
-                             1.0f / sqrtf((float)s.D), attn, s.dtype, st);
+                             1.0f / sqrtf((float)s.D), attn, s.dtype, ws.att_bytes ? base + ws.att : nullptr,
+                             ws.att_bytes, st);
   if (rc) return rc;
   VLC_MARK(5);
   rc = vlc::launch_gemm(attn, hqd, w->w_o, h1, H, n, H, hqd, vlc::EPI_RESIDUAL, nullptr, h_in, H, p->map,

@@ -61,10 +61,12 @@ int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t
                            int Hkv, int D, const RopeFreq& f, void* q_out, void* k_cache, void* v_cache,
                            int dtype, hipStream_t st);
 
-// q rows have a row stride of q_stride elements (dense q: Hq*D).
+// q rows have a row stride of q_stride elements (dense q: Hq*D).  ws: optional float scratch of
+// attention_ws_bytes() that allows splitting the key range when there are few query rows.
 int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const void* v_cache,
                      const int32_t* row_kv_start, const int32_t* row_kv_len, int64_t n, int Hq, int Hkv,
-                     int D, float scale, void* out, int dtype, hipStream_t st);
+                     int D, float scale, void* out, int dtype, void* ws, int64_t ws_bytes, hipStream_t st);
+int64_t attention_ws_bytes(int64_t n, int Hq, int Hkv, int D, int dtype);
 
 enum Epilogue {
   EPI_BIAS = 0,      // C = A W^T + bias[n]               (bias may be NULL)

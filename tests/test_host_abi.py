@@ -123,3 +123,16 @@ def test_host_error_paths():
     with pytest.raises(vlc.VlcError):
         vlc.vlc_layer_workspace_bytes(bad, 10)
     assert "Hq" in vlc.last_error()
+
+
+def test_workspace_size_is_monotone_in_rows():
+    """A workspace sized for n_max rows must serve every call with fewer rows (the scratch areas for
+    split-K GEMMs and key-split attention only exist for small row counts)."""
+    from paper_2512_12977_amd.runner import make_shape
+    for name in ("7b", "72b", "tiny_bf16", "tiny"):
+        rec = make_shape(syn.SHAPES[name])
+        prev = 0
+        for n in list(range(0, 3000, 13)) + [5000, 18944, 147456]:
+            b = vlc.vlc_layer_workspace_bytes(rec, n)
+            assert b >= prev, (name, n, b, prev)
+            prev = b
