@@ -101,6 +101,18 @@ def stage_work(sh, n, n_reuse, pairs):
     }
 
 
+def stage_bytes_of_gemm(sh, name, n):
+    """Bytes a GEMM stage must move once: weights + input rows + output rows."""
+    e = 2 if sh.dtype == "bf16" else 4
+    dims = {"qkv_gemm": (sh.n_qkv, sh.H, 4), "o_gemm": (sh.H, sh.Hq * sh.D, e),
+            "gate_up_swiglu_gemm": (2 * sh.I, sh.H, e), "down_gemm": (sh.H, sh.I, e)}
+    if name not in dims:
+        return None
+    N, K, eo = dims[name]
+    n_out = sh.I if name == "gate_up_swiglu_gemm" else N
+    return float(N * K * e + n * K * e + n * n_out * eo)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -246,12 +258,21 @@ def main() -> int:
         ach = fl / dur / 1e12
         roofline = {"kernel": dom_name, "bound": "mfma" if sh.dtype == "bf16" else "alu", "achieved": round(ach, 2),
                     "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4), "traffic": None,
-                    "avg_launch_us": round(dur * 1e6, 2), "flops_per_launch": fl}
+                    "avg_launch_us": round(dur * 1e6, 2), "flops_per_launch": fl,
+                    "algorithmic_bytes_per_launch": stage_bytes_of_gemm(sh, dom_name, float(np.mean(rows)))}
     else:
         ach = by / dur / 1e9
         roofline = {"kernel": dom_name, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
                     "avg_launch_us": round(dur * 1e6, 2), "bytes_per_launch": by}
+
+    # HBM traffic of the dominant kernel, if a counter run of this workload has been summarised
+    try:
+        tr = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))[wl.name][dom_name]
+        roofline["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
+        roofline["traffic_source"] = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/traffic.json"
+    except Exception:
+        pass
 
     # ---- full recompute through the same kernels ---------------------------------------------------
     full_ms = None
