@@ -40,18 +40,26 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32_t
 // contraction index is just a relabeling of keys, as long as the V^T fragment uses the same
 // relabeling, which is how V^T is laid out in LDS.
 //
-// K/V blocks go through a two-stage LDS ring: while block kb is consumed, the K tile of block kb+1
-// is copied global -> LDS directly (the XOR swizzle is applied by permuting which 16-byte chunk each
-// lane fetches) and the V tile of block kb+1 is fetched into registers, then written transposed.
+// K/V blocks go through a two-stage LDS ring: while block kb is consumed, the K and V tiles of block
+// kb+1 are copied global -> LDS directly, both row-major [key][d] (the XOR swizzles are applied by
+// permuting which 16-byte chunk each lane fetches).  The V^T fragments are read with the transposing
+// LDS load (ds_read_b64_tr_b16): inside a group of 16 lanes, lane i receives element i%4 of the four
+// 8-byte chunks addressed by lanes i/4, i/4+4, i/4+8, i/4+12; with lane s of the group pointing at
+// row key0 + s/4, columns d0 + 4*(s%4), lane i ends up with V[key0 .. key0+3][d0 + i].
 constexpr int ATT_D = 128;
 constexpr int KB = 64;        // keys per block
 constexpr int VR = 128;       // virtual rows per workgroup
 constexpr int K_TILE_CHUNKS = KB * 16;      // [64 keys][16 chunks of 8 d]
-constexpr int V_TILE_CHUNKS = ATT_D * 8;    // [128 d][8 chunks of 8 key positions]
+constexpr int V_TILE_CHUNKS = KB * 16;      // same shape
 constexpr int ATT_STAGE_CHUNKS = K_TILE_CHUNKS + V_TILE_CHUNKS;
 
-// V^T tile in LDS: chunk swizzled by d.
-__device__ __forceinline__ int vt_chunk(int d, int chunk) { return chunk ^ ((d & 7) ^ ((d >> 3) & 7)); }
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+// K tile: chunk XOR key%16 (16-byte fragment reads of consecutive keys hit different banks).
+// V tile: chunk XOR (key%4)*4 (a transposing read touches 4 consecutive keys x 64 bytes).
+__device__ __forceinline__ int k_swz(int key, int c) { return c ^ (key & 15); }
+__device__ __forceinline__ int v_swz(int key, int c) { return c ^ ((key & 3) << 2); }
 
 #define VLC_ATT_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8) | (0 << 14))
 
@@ -111,18 +119,20 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
 
   const int64_t kv_row_elems = (int64_t)Hkv * ATT_D;
 
-  // K tile: this lane fills LDS chunks (wave*4 + i)*64 + lane, i < 4, i.e. key = chunk / 16 and the
-  // logical 8-element chunk c = (chunk % 16) ^ (key % 16) of that key's 128 d.
-  int k_key[4], k_c[4];
+  // K and V tiles: this lane fills LDS chunks (wave*4 + i)*64 + lane, i < 4, of each tile, i.e.
+  // key = chunk / 16 and the logical 8-element chunk that the tile's swizzle places there.
+  int t_key[4], k_c[4], v_c[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int p = (wave * 4 + i) * 64 + lane;
-    k_key[i] = p >> 4;
-    k_c[i] = (p & 15) ^ (k_key[i] & 15);
+    t_key[i] = p >> 4;
+    k_c[i] = k_swz(t_key[i], p & 15);
+    v_c[i] = v_swz(t_key[i], p & 15);
   }
-  // V tile: this lane owns 4 keys (group kg) x 8 d (chunk dc) and writes them transposed
-  const int v_dc = tid & 15, v_kg = tid >> 4;
-  const int v_chunk = 2 * (v_kg >> 2) + (v_kg & 1), v_half = (v_kg >> 1) & 1;
+  // transposing V reads: lane s of a 16-lane group points at key s/4, columns 4*(s%4) of the group's
+  // 16-wide d range; groups 0/1 take the two d halves of a 32-wide tile, groups 0-1 / 2-3 are x = 0 / 1.
+  const int tr_key = 4 * x + ((lane & 15) >> 2);                 // + 16*t + 8*r
+  const int tr_d = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);      // + 32*md
 
   // Rows of different requests (different row_kv_start) may share a tile: handle one run of equal
   // start at a time; lanes outside the run see every key masked.
@@ -155,44 +165,23 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
     }
     const int last_key = seg_max - 1;               // loads never leave the run's key range
 
-    u32x4 vreg[4];
 #define VLC_ATT_ISSUE(kb_, stage_)                                                                             \
   {                                                                                                            \
     const int key0_ = (kb_) * KB;                                                                              \
     u32x4* sk_ = lds + (stage_) * ATT_STAGE_CHUNKS + wave * 256;                                               \
+    u32x4* sv_ = sk_ + K_TILE_CHUNKS;                                                                          \
     _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                            \
-      const int gk_ = min(key0_ + k_key[i], last_key);                                                         \
-      __builtin_amdgcn_global_load_lds(                                                                        \
-          (const __attribute__((address_space(1))) void*)(kbase + (int64_t)gk_ * kv_row_elems + k_c[i] * 8),   \
-          (__attribute__((address_space(3))) void*)(sk_ + i * 64), 16, 0, 0);                                  \
-    }                                                                                                          \
-    _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                                            \
-      const int gk_ = min(key0_ + 4 * v_kg + b, last_key);                                                     \
-      vreg[b] = *(reinterpret_cast<const u32x4*>(vbase + (int64_t)gk_ * kv_row_elems) + v_dc);                 \
-    }                                                                                                          \
-  }
-    // key = 16*t + 8*a + 4*xx + b  ->  position 16*t + 8*xx + 4*a + b  (chunk 2t+xx, half a)
-#define VLC_ATT_WRITE_V(stage_)                                                                                \
-  {                                                                                                            \
-    u32x4* sv_ = lds + (stage_) * ATT_STAGE_CHUNKS + K_TILE_CHUNKS;                                            \
-    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                            \
-      const int d_ = 8 * v_dc + i;                                                                             \
-      uint32_t e_[4];                                                                                          \
-      _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                                          \
-        const uint32_t w_ = vreg[b][i >> 1];                                                                   \
-        e_[b] = (i & 1) ? (w_ >> 16) : (w_ & 0xffffu);                                                         \
-      }                                                                                                        \
-      u32x2 pr_;                                                                                               \
-      pr_[0] = e_[0] | (e_[1] << 16);                                                                          \
-      pr_[1] = e_[2] | (e_[3] << 16);                                                                          \
-      *(reinterpret_cast<u32x2*>(&sv_[d_ * 8 + vt_chunk(d_, v_chunk)]) + v_half) = pr_;                        \
+      const int64_t gk_ = (int64_t)min(key0_ + t_key[i], last_key) * kv_row_elems;                             \
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + gk_ + k_c[i] * 8), \
+                                       (__attribute__((address_space(3))) void*)(sk_ + i * 64), 16, 0, 0);     \
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + gk_ + v_c[i] * 8), \
+                                       (__attribute__((address_space(3))) void*)(sv_ + i * 64), 16, 0, 0);     \
     }                                                                                                          \
   }
 
     __syncthreads();                 // the ring is free (previous run finished reading it)
     if (n_blocks > 0) {
       VLC_ATT_ISSUE(kb_first, 0)
-      VLC_ATT_WRITE_V(0)
       VLC_ATT_WAIT_VM0();
     }
     __syncthreads();
@@ -205,7 +194,7 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
 
       if (key0 < w_max) {              // something visible for this wavefront in this block
         const u32x4* sk = lds + stage * ATT_STAGE_CHUNKS;
-        const u32x4* sv = sk + K_TILE_CHUNKS;
+        const unsigned char* sv = reinterpret_cast<const unsigned char*>(sk + K_TILE_CHUNKS);
         // ---- S^T = K Q^T -----------------------------------------------------------------------
         f32x16 st[2];
 #pragma unroll
@@ -215,7 +204,7 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
           const int key = 32 * mt + l32;
 #pragma unroll
           for (int ks = 0; ks < ATT_D / 16; ++ks) {
-            const u32x4 kv = sk[key * 16 + ((2 * ks + x) ^ (key & 15))];
+            const u32x4 kv = sk[key * 16 + k_swz(key, 2 * ks + x)];
             st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[ks], st[mt], 0, 0, 0);
           }
         }
@@ -269,20 +258,24 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
           }
 #pragma unroll
           for (int md = 0; md < ATT_D / 32; ++md) {
-            const int d = 32 * md + l32;
-            const u32x4 vv = sv[d * 8 + vt_chunk(d, 2 * t + x)];
+            const int d0 = 32 * md + tr_d;
+            s16x4 half[2];
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+              const int key = 16 * t + 8 * r + tr_key;
+              const int byte = (key * 16 + v_swz(key, d0 >> 3)) * 16 + (d0 & 4) * 2;
+              half[r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                  (__attribute__((address_space(3))) s16x4*)(const_cast<unsigned char*>(sv) + byte));
+            }
+            const s16x8 vv = __builtin_shufflevector(half[0], half[1], 0, 1, 2, 3, 4, 5, 6, 7);
             o_acc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, o_acc[md], 0, 0, 0);
           }
         }
       }
-      if (more) {
-        VLC_ATT_WRITE_V(stage ^ 1)     // waits for the V registers of block kb+1
-        VLC_ATT_WAIT_VM0();            // and for this wavefront's share of its K tile
-      }
+      if (more) VLC_ATT_WAIT_VM0();    // this wavefront's share of block kb+1 has landed
       __syncthreads();
     }
 #undef VLC_ATT_ISSUE
-#undef VLC_ATT_WRITE_V
     seg_begin = seg_end;
   }
 
@@ -430,14 +423,15 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float* __restri
 int64_t attention_ws_bytes(int64_t n, int Hq, int Hkv, int D, int dtype) {
   if (dtype != VLC_BF16 || D != ATT_D || Hq % Hkv || Hq / Hkv > VR) return 0;
   const int64_t wgs = ((n + VR / (Hq / Hkv) - 1) / (VR / (Hq / Hkv))) * Hkv;
-  if (wgs >= 256 || n <= 0) return 0;                  // enough workgroups without splitting
+  if (wgs >= 512 || n <= 0) return 0;                  // enough workgroups without splitting
   const int64_t nsplit = 8;
   return nsplit * n * Hq * (ATT_D + 2) * 4;
 }
 
 int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const void* v_cache,
                      const int32_t* row_kv_start, const int32_t* row_kv_len, int64_t n, int Hq, int Hkv,
-                     int D, float scale, void* out, int dtype, void* ws, int64_t ws_bytes, hipStream_t st) {
+                     int D, float scale, void* out, int dtype, void* ws, int64_t ws_bytes, int64_t max_kv_len,
+                     hipStream_t st) {
   if (n <= 0) return VLC_OK;
   const int g = Hq / Hkv;
   if (dtype == VLC_BF16) {
@@ -446,11 +440,16 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
     if (q_stride % 8) return fail(VLC_ERR_SHAPE, "attention(bf16): q row stride must be a multiple of 8");
     const int rows_per_tile = VR / g;
     const int64_t tiles = (n + rows_per_tile - 1) / rows_per_tile;
-    // Few workgroups: split the key range so that about 512 are resident (two per CU).
+    // Few workgroups (512 are resident at once, two per CU): the key loop of the longest rows is the
+    // critical path, so split the key range over up to 1024 workgroups, at least 4 key blocks each.
     int nsplit = 1;
-    if (ws && tiles * Hkv < 256) {
-      nsplit = (int)((512 + tiles * Hkv - 1) / (tiles * Hkv));
+    if (ws && tiles * Hkv < 512) {
+      nsplit = (int)(1024 / (tiles * Hkv));
       if (nsplit > 8) nsplit = 8;
+      if (max_kv_len > 0) {
+        const int64_t by_len = (max_kv_len + 4 * KB - 1) / (4 * KB);
+        if (nsplit > by_len) nsplit = (int)by_len;
+      }
       while (nsplit > 1 && (int64_t)nsplit * n * Hq * (ATT_D + 2) * 4 > ws_bytes) --nsplit;
     }
     if (nsplit > 1) {
@@ -511,5 +510,5 @@ extern "C" int vlc_sparse_q_attention(const void* q, const void* k_cache, const 
   if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15)
     return fail(VLC_ERR_SHAPE, "vlc_sparse_q_attention: pointers must be 16-byte aligned");
   return vlc::launch_attention(q, (int64_t)Hq * D, k_cache, v_cache, row_kv_start, row_kv_len, n, Hq, Hkv, D,
-                               scale, out, dtype, nullptr, 0, (hipStream_t)stream);
+                               scale, out, dtype, nullptr, 0, 0, (hipStream_t)stream);
 }

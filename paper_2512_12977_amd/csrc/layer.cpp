@@ -58,22 +58,18 @@ extern "C" int64_t vlc_layer_workspace_bytes(const vlc_layer_shape* shape, int64
     return 0;
   }
   // The row buffers grow with n; the two scratch areas exist only for small n.  A workspace sized
-  // here must serve every call with n <= n_rows_max: take the row buffers at n_rows_max and the
-  // largest scratch any smaller n can ask for.
+  // here must serve every call with n <= n_rows_max: take the row buffers at n_rows_max and, for each
+  // scratch area, the largest size any smaller n can ask for.
   const vlc_layer_shape& s = *shape;
-  const Workspace top = layout(s, n_rows_max);
-  const int64_t rows_only = top.splitk;                               // scratch areas come last
-  int64_t scratch = top.total - rows_only;
+  const int64_t rows_only = layout(s, n_rows_max).splitk;             // scratch areas come last
+  const int64_t n_splitk = n_rows_max < 1535 ? n_rows_max : 1535;     // split-K never runs from 1536 rows on
   const int64_t g = s.Hq / s.Hkv;
   const int64_t rows_per_tile = g <= 128 ? 128 / g : 1;
-  int64_t n_small = ((256 + s.Hkv - 1) / s.Hkv - 1) * rows_per_tile;  // largest n whose attention may split
-  if (n_small > 1535) n_small = 1535;                                 // and split-K never runs from 1536 on
-  if (n_small > n_rows_max) n_small = n_rows_max;
-  for (int64_t n : {n_small, n_rows_max < 1535 ? n_rows_max : (int64_t)1535}) {
-    const Workspace w = layout(s, n);
-    if (w.total - w.splitk > scratch) scratch = w.total - w.splitk;
-  }
-  return rows_only + scratch;
+  int64_t n_att = ((512 + s.Hkv - 1) / s.Hkv - 1) * rows_per_tile;    // largest n whose attention may split
+  if (n_att > n_rows_max) n_att = n_rows_max;
+  const int64_t splitk_max = n_splitk > 0 ? layout(s, n_splitk).splitk_bytes : 0;
+  const int64_t att_max = n_att > 0 ? layout(s, n_att).att_bytes : 0;
+  return rows_only + align256(splitk_max) + align256(att_max);
 }
 
 extern "C" int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t n_rows, int64_t* offsets) {
@@ -160,7 +156,7 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
   VLC_MARK(4);
   rc = vlc::launch_attention(qrot, hqd, k_cache, v_cache, p->row_kv_start, p->row_kv_len, n, s.Hq, s.Hkv, s.D,
                              1.0f / sqrtf((float)s.D), attn, s.dtype, ws.att_bytes ? base + ws.att : nullptr,
-                             ws.att_bytes, st);
+                             ws.att_bytes, p->kv_rows, st);
   if (rc) return rc;
   VLC_MARK(5);
   rc = vlc::launch_gemm(attn, hqd, w->w_o, h1, H, n, H, hqd, vlc::EPI_RESIDUAL, nullptr, h_in, H, p->map,

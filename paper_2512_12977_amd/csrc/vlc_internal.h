@@ -65,7 +65,8 @@ int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t
 // attention_ws_bytes() that allows splitting the key range when there are few query rows.
 int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const void* v_cache,
                      const int32_t* row_kv_start, const int32_t* row_kv_len, int64_t n, int Hq, int Hkv,
-                     int D, float scale, void* out, int dtype, void* ws, int64_t ws_bytes, hipStream_t st);
+                     int D, float scale, void* out, int dtype, void* ws, int64_t ws_bytes, int64_t max_kv_len,
+                     hipStream_t st);   // max_kv_len: upper bound of row_kv_len if known, else 0
 int64_t attention_ws_bytes(int64_t n, int Hq, int Hkv, int D, int dtype);
 
 enum Epilogue {
