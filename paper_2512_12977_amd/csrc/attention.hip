@@ -51,7 +51,7 @@ constexpr int KB = 64;        // keys per block
 constexpr int VR = 128;       // virtual rows per workgroup
 constexpr int K_TILE_CHUNKS = KB * 16;      // [64 keys][16 chunks of 8 d]
 constexpr int V_TILE_CHUNKS = KB * 16;      // same shape
-constexpr int ATT_STAGE_CHUNKS = K_TILE_CHUNKS + V_TILE_CHUNKS;
+constexpr int ATT_STAGE_CHUNKS = K_TILE_CHUNKS + V_TILE_CHUNKS;   // one K tile + one V tile
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
     const int32_t* __restrict__ row_kv_len, int n, int Hq, int Hkv, int g, int rows_per_tile,
     float scale_log2, uint16_t* __restrict__ out, int nsplit, float* __restrict__ part_o,
     float* __restrict__ part_ml) {
-  __shared__ u32x4 lds[2 * ATT_STAGE_CHUNKS];     // 64 KB
+  __shared__ u32x4 lds[2 * ATT_STAGE_CHUNKS];     // 64 KB: K ring (2 tiles), then V ring (2 tiles)
   __shared__ int s_start[VR];
   __shared__ int s_len[VR];
 
@@ -120,19 +120,35 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
   const int64_t kv_row_elems = (int64_t)Hkv * ATT_D;
 
   // K and V tiles: this lane fills LDS chunks (wave*4 + i)*64 + lane, i < 4, of each tile, i.e.
-  // key = chunk / 16 and the logical 8-element chunk that the tile's swizzle places there.
+  // key = chunk / 16 and the logical 8-element chunk that the tile's swizzle places there.  Its
+  // byte offset from the block's first row is loop-invariant; the block base is wavefront-uniform.
+  const uint32_t kv_row_bytes = (uint32_t)Hkv * ATT_D * 2;
   int t_key[4], k_c[4], v_c[4];
+  uint32_t k_go[4], v_go[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int p = (wave * 4 + i) * 64 + lane;
     t_key[i] = p >> 4;
     k_c[i] = k_swz(t_key[i], p & 15);
     v_c[i] = v_swz(t_key[i], p & 15);
+    k_go[i] = (uint32_t)t_key[i] * kv_row_bytes + k_c[i] * 16;
+    v_go[i] = (uint32_t)t_key[i] * kv_row_bytes + v_c[i] * 16;
   }
+  // K fragment reads: key 32*mt + l32, chunk (2*ks + x) ^ (key % 16); byte offset for mt = 0, stage 0
+  int k_rd[ATT_D / 16];
+#pragma unroll
+  for (int ks = 0; ks < ATT_D / 16; ++ks) k_rd[ks] = (l32 * 16 + k_swz(l32, 2 * ks + x)) * 16;
   // transposing V reads: lane s of a 16-lane group points at key s/4, columns 4*(s%4) of the group's
   // 16-wide d range; groups 0/1 take the two d halves of a 32-wide tile, groups 0-1 / 2-3 are x = 0 / 1.
+  // Byte offset for t = r = 0, stage 0, per 32-wide d tile (the swizzle term (key%4)*4 is lane-constant).
   const int tr_key = 4 * x + ((lane & 15) >> 2);                 // + 16*t + 8*r
   const int tr_d = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);      // + 32*md
+  int v_rd[ATT_D / 32];
+#pragma unroll
+  for (int md = 0; md < ATT_D / 32; ++md) {
+    const int d0 = 32 * md + tr_d;
+    v_rd[md] = (tr_key * 16 + v_swz(tr_key, d0 >> 3)) * 16 + (d0 & 4) * 2;
+  }
 
   // Rows of different requests (different row_kv_start) may share a tile: handle one run of equal
   // start at a time; lanes outside the run see every key masked.
@@ -165,117 +181,144 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
     }
     const int last_key = seg_max - 1;               // loads never leave the run's key range
 
-#define VLC_ATT_ISSUE(kb_, stage_)                                                                             \
+    // LDS: K ring = chunks [0, 2*K_TILE), V ring = the next 2*V_TILE.
+#define VLC_ATT_ISSUE_TILE(base_, go_, c_, kb_, lds_chunk0_)                                                   \
   {                                                                                                            \
     const int key0_ = (kb_) * KB;                                                                              \
-    u32x4* sk_ = lds + (stage_) * ATT_STAGE_CHUNKS + wave * 256;                                               \
-    u32x4* sv_ = sk_ + K_TILE_CHUNKS;                                                                          \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                            \
-      const int64_t gk_ = (int64_t)min(key0_ + t_key[i], last_key) * kv_row_elems;                             \
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + gk_ + k_c[i] * 8), \
-                                       (__attribute__((address_space(3))) void*)(sk_ + i * 64), 16, 0, 0);     \
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + gk_ + v_c[i] * 8), \
-                                       (__attribute__((address_space(3))) void*)(sv_ + i * 64), 16, 0, 0);     \
+    u32x4* dst_ = lds + (lds_chunk0_) + wave * 256;                                                            \
+    if (key0_ + KB <= seg_max) { /* whole block inside the run: uniform base + invariant lane offset */        \
+      const char* blk_ = reinterpret_cast<const char*>(base_) + (int64_t)key0_ * kv_row_bytes;                 \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                            \
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(blk_ + go_[i]),       \
+                                         (__attribute__((address_space(3))) void*)(dst_ + i * 64), 16, 0, 0);  \
+    } else { /* last block of the run: rows past the end re-read the last row */                               \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                          \
+        const int64_t gk_ = (int64_t)min(key0_ + t_key[i], last_key) * kv_row_elems;                           \
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base_ + gk_ + c_[i] * 8), \
+                                         (__attribute__((address_space(3))) void*)(dst_ + i * 64), 16, 0, 0);  \
+      }                                                                                                        \
     }                                                                                                          \
   }
+#define VLC_ATT_ISSUE_K(kb_, stage_) VLC_ATT_ISSUE_TILE(kbase, k_go, k_c, kb_, (stage_) * K_TILE_CHUNKS)
+#define VLC_ATT_ISSUE_V(kb_, stage_) VLC_ATT_ISSUE_TILE(vbase, v_go, v_c, kb_, 2 * K_TILE_CHUNKS + (stage_) * V_TILE_CHUNKS)
+    // S^T of one key block: ST = K Q^T from K ring stage kst_
+#define VLC_ATT_QK(ST, kst_)                                                                                   \
+  {                                                                                                            \
+    const unsigned char* sk_ = reinterpret_cast<const unsigned char*>(lds) + (kst_) * (K_TILE_CHUNKS * 16);    \
+    _Pragma("unroll") for (int mt = 0; mt < 2; ++mt) {                                                         \
+      _Pragma("unroll") for (int e = 0; e < 16; ++e) ST[mt][e] = 0.f;                                          \
+      _Pragma("unroll") for (int ks = 0; ks < ATT_D / 16; ++ks) {                                              \
+        const u32x4 kv_ = *reinterpret_cast<const u32x4*>(sk_ + k_rd[ks] + mt * (32 * 256));                   \
+        ST[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv_), qf[ks], ST[mt], 0, 0, 0); \
+      }                                                                                                        \
+    }                                                                                                          \
+  }
+    // keys of the block beyond a lane's visible range are masked (only where the block crosses it)
+#define VLC_ATT_MASK(ST, key0_)                                                                                \
+  {                                                                                                            \
+    if ((key0_) + KB > w_min) {                                                                                \
+      _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                         \
+        _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                       \
+          const int key_ = (key0_) + 32 * mt + 8 * (j >> 2) + 4 * x + (j & 3);                                 \
+          ST[mt][j] = key_ < len ? ST[mt][j] : -INFINITY;                                                      \
+        }                                                                                                      \
+    }                                                                                                          \
+  }
+    // online softmax (base 2) of ST: branch-free, so that it shares a basic block with the next
+    // block's S^T MFMAs; leaves probabilities in ST and the rescale factor in alpha_ / grew_
+#define VLC_ATT_SOFTMAX(ST)                                                                                    \
+    float mx_ = -INFINITY;                                                                                     \
+    _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                           \
+      _Pragma("unroll") for (int j = 0; j < 16; ++j) mx_ = fmaxf(mx_, ST[mt][j]);                              \
+    mx_ = fmaxf(mx_, __shfl_xor(mx_, 32)) * scale_log2;   /* scale > 0: max commutes with it */                \
+    const float m_new_ = fmaxf(m_run, mx_);                                                                    \
+    const float m_use_ = (m_new_ == -INFINITY) ? 0.f : m_new_;                                                 \
+    const float alpha_ = __builtin_amdgcn_exp2f(m_run - m_use_);   /* m_run = -inf -> 0 */                     \
+    const bool grew_ = m_new_ > m_run;                                                                         \
+    m_run = m_new_;                                                                                            \
+    float psum_ = 0.f;                                                                                         \
+    _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                           \
+      _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                         \
+        const float p_ = __builtin_amdgcn_exp2f(fmaf(ST[mt][j], scale_log2, -m_use_));                         \
+        ST[mt][j] = p_;                                                                                        \
+        psum_ += p_;                                                                                           \
+      }                                                                                                        \
+    l_run = l_run * alpha_ + psum_;
+    // order template for the shared block: one MFMA and its K fragment read per eight vector ops
+#define VLC_ATT_INTERLEAVE()                                                                                   \
+    _Pragma("unroll") for (int g_ = 0; g_ < 16; ++g_) {                                                        \
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                       \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                       \
+      __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);                                                       \
+    }
+    // O rescale (only when some row's maximum moved) and O^T += V^T P^T from V ring stage vst_
+#define VLC_ATT_RESCALE_PV(ST, vst_)                                                                           \
+  {                                                                                                            \
+    if (__any(grew_)) {                                                                                        \
+      _Pragma("unroll") for (int i = 0; i < ATT_D / 32; ++i)                                                   \
+        _Pragma("unroll") for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha_;                                  \
+    }                                                                                                          \
+    const unsigned char* sv_ = reinterpret_cast<const unsigned char*>(lds + 2 * K_TILE_CHUNKS + (vst_) * V_TILE_CHUNKS); \
+    _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                            \
+      bf16x8 pf_;                                                                                              \
+      _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                          \
+        f32x2 pr_ = {ST[t >> 1][8 * (t & 1) + 2 * e], ST[t >> 1][8 * (t & 1) + 2 * e + 1]};                    \
+        const bf16x2 pb_ = __builtin_convertvector(pr_, bf16x2);                                               \
+        pf_[2 * e] = pb_[0];                                                                                   \
+        pf_[2 * e + 1] = pb_[1];                                                                               \
+      }                                                                                                        \
+      _Pragma("unroll") for (int md = 0; md < ATT_D / 32; ++md) {                                              \
+        s16x4 half_[2];                                                                                        \
+        _Pragma("unroll") for (int r = 0; r < 2; ++r)                                                          \
+          half_[r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(       \
+              const_cast<unsigned char*>(sv_) + v_rd[md] + (16 * t + 8 * r) * 256));                           \
+        const s16x8 vv_ = __builtin_shufflevector(half_[0], half_[1], 0, 1, 2, 3, 4, 5, 6, 7);                 \
+        o_acc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv_), pf_, o_acc[md], 0, 0, 0); \
+      }                                                                                                        \
+    }                                                                                                          \
+  }
+    // One key block j (S^T already in CUR): fetch ahead, start the next block's S^T into NXT (its MFMAs
+    // are independent of this block's softmax arithmetic, so the two interleave), finish this block.
+#define VLC_ATT_BLOCK(j_, PAR, CUR, NXT)                                                                       \
+  {                                                                                                            \
+    if ((j_) + 2 < n_blocks) VLC_ATT_ISSUE_K(kb_first + (j_) + 2, PAR)                                         \
+    if ((j_) + 1 < n_blocks) VLC_ATT_ISSUE_V(kb_first + (j_) + 1, (PAR) ^ 1)                                   \
+    const int key0b_ = (kb_first + (j_)) * KB;                                                                 \
+    if (key0b_ < w_max) { /* something visible for this wavefront in this block */                             \
+      VLC_ATT_MASK(CUR, key0b_)                                                                                \
+      VLC_ATT_QK(NXT, (PAR) ^ 1)   /* past the last block this reads a stale tile; the result is unused */     \
+      VLC_ATT_SOFTMAX(CUR)                                                                                     \
+      VLC_ATT_INTERLEAVE()                                                                                     \
+      VLC_ATT_RESCALE_PV(CUR, PAR)                                                                             \
+    }                                                                                                          \
+    VLC_ATT_WAIT_VM0();   /* this wavefront's shares of the tiles fetched above have landed */                 \
+    __syncthreads();                                                                                           \
+  }
 
-    __syncthreads();                 // the ring is free (previous run finished reading it)
+    __syncthreads();                 // the rings are free (previous run finished reading them)
+    f32x16 st_a[2], st_b[2];
     if (n_blocks > 0) {
-      VLC_ATT_ISSUE(kb_first, 0)
+      VLC_ATT_ISSUE_K(kb_first, 0)
+      VLC_ATT_ISSUE_V(kb_first, 0)
+      if (n_blocks > 1) VLC_ATT_ISSUE_K(kb_first + 1, 1)
       VLC_ATT_WAIT_VM0();
     }
     __syncthreads();
-
-    for (int kb = 0; kb < n_blocks; ++kb) {
-      const int key0 = (kb_first + kb) * KB;
-      const int stage = kb & 1;
-      const bool more = kb + 1 < n_blocks;
-      if (more) VLC_ATT_ISSUE(kb_first + kb + 1, stage ^ 1)
-
-      if (key0 < w_max) {              // something visible for this wavefront in this block
-        const u32x4* sk = lds + stage * ATT_STAGE_CHUNKS;
-        const unsigned char* sv = reinterpret_cast<const unsigned char*>(sk + K_TILE_CHUNKS);
-        // ---- S^T = K Q^T -----------------------------------------------------------------------
-        f32x16 st[2];
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-          for (int e = 0; e < 16; ++e) st[mt][e] = 0.f;
-          const int key = 32 * mt + l32;
-#pragma unroll
-          for (int ks = 0; ks < ATT_D / 16; ++ks) {
-            const u32x4 kv = sk[key * 16 + k_swz(key, 2 * ks + x)];
-            st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[ks], st[mt], 0, 0, 0);
-          }
-        }
-        // ---- online softmax (base 2) -------------------------------------------------------------
-        if (key0 + KB > w_min) {       // some lane has keys of this block beyond its range
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-              const int key = key0 + 32 * mt + 8 * (j >> 2) + 4 * x + (j & 3);
-              st[mt][j] = key < len ? st[mt][j] : -INFINITY;
-            }
-        }
-        float mx = -INFINITY;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) mx = fmaxf(mx, st[mt][j]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;          // scale > 0: max commutes with it
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // m_run = -inf -> 0
-        const bool grew = m_new > m_run;
-        m_run = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(st[mt][j], scale_log2, -m_use));
-            st[mt][j] = p;
-            psum += p;
-          }
-        l_run = l_run * alpha + psum;
-        if (__any(grew)) {             // rescale only when some row's maximum moved
-#pragma unroll
-          for (int i = 0; i < ATT_D / 32; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
-        }
-        // ---- O^T += V^T P^T ----------------------------------------------------------------------
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          bf16x8 pf;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            f32x2 pr = {st[t >> 1][8 * (t & 1) + 2 * e], st[t >> 1][8 * (t & 1) + 2 * e + 1]};
-            const bf16x2 pb = __builtin_convertvector(pr, bf16x2);
-            pf[2 * e] = pb[0];
-            pf[2 * e + 1] = pb[1];
-          }
-#pragma unroll
-          for (int md = 0; md < ATT_D / 32; ++md) {
-            const int d0 = 32 * md + tr_d;
-            s16x4 half[2];
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-              const int key = 16 * t + 8 * r + tr_key;
-              const int byte = (key * 16 + v_swz(key, d0 >> 3)) * 16 + (d0 & 4) * 2;
-              half[r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                  (__attribute__((address_space(3))) s16x4*)(const_cast<unsigned char*>(sv) + byte));
-            }
-            const s16x8 vv = __builtin_shufflevector(half[0], half[1], 0, 1, 2, 3, 4, 5, 6, 7);
-            o_acc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf, o_acc[md], 0, 0, 0);
-          }
-        }
-      }
-      if (more) VLC_ATT_WAIT_VM0();    // this wavefront's share of block kb+1 has landed
-      __syncthreads();
+    if (n_blocks > 0 && kb_first * KB < w_max) VLC_ATT_QK(st_a, 0)
+    __syncthreads();                 // K stage 0 may be refilled from here on
+    for (int j = 0; j < n_blocks; j += 2) {
+      VLC_ATT_BLOCK(j, 0, st_a, st_b)
+      if (j + 1 < n_blocks) VLC_ATT_BLOCK(j + 1, 1, st_b, st_a)
     }
-#undef VLC_ATT_ISSUE
+#undef VLC_ATT_ISSUE_TILE
+#undef VLC_ATT_ISSUE_K
+#undef VLC_ATT_ISSUE_V
+#undef VLC_ATT_QK
+#undef VLC_ATT_MASK
+#undef VLC_ATT_SOFTMAX
+#undef VLC_ATT_INTERLEAVE
+#undef VLC_ATT_RESCALE_PV
+#undef VLC_ATT_BLOCK
     seg_begin = seg_end;
   }
 
@@ -441,14 +484,15 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
     const int rows_per_tile = VR / g;
     const int64_t tiles = (n + rows_per_tile - 1) / rows_per_tile;
     // Few workgroups (512 are resident at once, two per CU): the key loop of the longest rows is the
-    // critical path, so split the key range over up to 1024 workgroups, at least 4 key blocks each.
+    // critical path, so split the key range over up to 1024 workgroups, keeping at least 8 key blocks
+    // per share (shorter shares cost more in partials and merging than they save).
     int nsplit = 1;
     if (ws && tiles * Hkv < 512) {
       nsplit = (int)(1024 / (tiles * Hkv));
       if (nsplit > 8) nsplit = 8;
       if (max_kv_len > 0) {
-        const int64_t by_len = (max_kv_len + 4 * KB - 1) / (4 * KB);
-        if (nsplit > by_len) nsplit = (int)by_len;
+        const int64_t by_len = max_kv_len / (8 * KB);
+        if (nsplit > by_len) nsplit = by_len > 1 ? (int)by_len : 1;
       }
       while (nsplit > 1 && (int64_t)nsplit * n * Hq * (ATT_D + 2) * 4 > ws_bytes) --nsplit;
     }
