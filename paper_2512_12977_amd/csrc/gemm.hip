@@ -53,7 +53,10 @@ __device__ __forceinline__ void tile_coords(int pid, int total, int tiles_m, int
 //
 // Operands reach LDS straight from global memory (global_load_lds, 16 bytes per lane, no register
 // staging) through a ring of STAGES k-tiles of 64 columns, so the next k-tile is in flight while
-// the current one is consumed.  A wavefront-level load writes 64 consecutive 16-byte chunks of LDS
+// the current one is consumed.  Inside a k-tile the instruction stream is laid out in groups of four
+// MFMAs, each preceded by its share of the next k-step's fragment reads and - in the first half of
+// the k-tile only, so every load has at least half a k-tile of latency cover - of the next k-tile's
+// global loads; sched_barrier keeps the compiler from regrouping them.  A wavefront-level load writes 64 consecutive 16-byte chunks of LDS
 // in lane order; the XOR swizzle that keeps the later 16-byte fragment reads of consecutive rows
 // in different banks is therefore applied on the global side (which chunk of its row each lane
 // fetches).  Fragments are double-buffered in registers across the four 16-wide k-steps.
@@ -63,6 +66,19 @@ __device__ __forceinline__ void tile_coords(int pid, int total, int tiles_m, int
 constexpr int BK = 64;
 
 __device__ __forceinline__ int fswz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+// One wavefront-level global -> LDS copy of 64 x 16 bytes: lane l's 16 bytes land at lds_byte_addr + 16*l.
+// Written as inline assembly rather than through the builtin because the compiler, seeing an LDS
+// write it cannot order against the fragment reads, waits for every outstanding LDS access before
+// each k-step; issued this way the loads are tracked only by the explicit vmcnt waits below (the
+// loop contains no other vector-memory instruction).  M0 holds the LDS address; the compiler never
+// keeps a live value in M0 across statements (it is reserved and written right before each use).
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_byte_addr), "v"(gptr)
+               : "memory");
+}
 
 #define VLC_WAITCNT_VM(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 
@@ -125,17 +141,16 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
     gr = gr < limit ? gr : limit - 1;
     w_src[i] = W + (int64_t)gr * K + (int64_t)kt_begin * BK + c * 8;
   }
-#define VLC_ISSUE(kt_, stage_)                                                                                   \
-  {                                                                                                              \
-    u32x4* sa_ = lds + (stage_) * STAGE_CHUNKS + wave * A_INSTR * 64;                                            \
-    u32x4* sw_ = lds + (stage_) * STAGE_CHUNKS + BM * 8 + wave * W_INSTR * 64;                                   \
-    _Pragma("unroll") for (int i = 0; i < A_INSTR; ++i)                                                          \
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_src[i] + (kt_) * BK),   \
-                                       (__attribute__((address_space(3))) void*)(sa_ + i * 64), 16, 0, 0);       \
-    _Pragma("unroll") for (int i = 0; i < W_INSTR; ++i)                                                          \
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(w_src[i] + (kt_) * BK),   \
-                                       (__attribute__((address_space(3))) void*)(sw_ + i * 64), 16, 0, 0);       \
-  }
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+  // LDS byte address of this wavefront's i-th load of a stage (A part first, then W)
+#define VLC_LDS_DST(stage_, i_)                                                                              \
+  (lds_base + (uint32_t)(((stage_) * STAGE_CHUNKS +                                                           \
+                          ((i_) < A_INSTR ? wave * A_INSTR * 64 + (i_) * 64                                  \
+                                          : BM * 8 + wave * W_INSTR * 64 + ((i_) - A_INSTR) * 64)) * 16))
+#define VLC_SRC(kt_, i_) ((i_) < A_INSTR ? a_src[(i_) < A_INSTR ? (i_) : 0] + (kt_) * BK                      \
+                                         : w_src[(i_) >= A_INSTR ? (i_) - A_INSTR : 0] + (kt_) * BK)
+#define VLC_ISSUE(kt_, stage_)                                                                               \
+  _Pragma("unroll") for (int i = 0; i < LOADS; ++i) dma16(VLC_SRC(kt_, i), VLC_LDS_DST(stage_, i));
 
   // fragment positions inside a stage (chunk units) for every 16-wide k-step
   int w_off[NT][KS], a_off[MT][KS];
@@ -164,43 +179,63 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-#define VLC_COMPUTE_TILE(kt_)                                                                                    \
-  {                                                                                                              \
-    const u32x4* st_ = lds + ((kt_) % STAGES) * STAGE_CHUNKS;                                                    \
-    bf16x8 wf[2][NT], af[2][MT];                                                                                 \
+  // One k-tile: KS k-steps of G groups of four MFMAs.  WITH_LOADS: the loads of k-tile nkt_ (into
+  // stage nst_) are issued in the first half of the groups.
+  constexpr int MPG = 4;                       // MFMAs per group
+  constexpr int G = NT * MT / MPG;             // groups per k-step
+  constexpr int TG = KS * G;                   // groups per k-tile
+  constexpr int NF = NT + MT;                  // fragments per k-step
+  static_assert(NT * MT % MPG == 0, "wavefront tile must hold a multiple of four MFMA tiles");
+#define VLC_COMPUTE_TILE(kt_, WITH_LOADS, nkt_, nst_)                                                         \
+  {                                                                                                           \
+    const u32x4* st_ = lds + ((kt_) % STAGES) * STAGE_CHUNKS;                                                 \
+    bf16x8 wf[2][NT], af[2][MT];                                                                              \
     _Pragma("unroll") for (int nt = 0; nt < NT; ++nt) wf[0][nt] = __builtin_bit_cast(bf16x8, st_[w_off[nt][0]]); \
     _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) af[0][mt] = __builtin_bit_cast(bf16x8, st_[a_off[mt][0]]); \
-    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                          \
-      if (ks + 1 < KS) {                                                                                         \
-        _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                        \
-          wf[(ks + 1) & 1][nt] = __builtin_bit_cast(bf16x8, st_[w_off[nt][ks + 1]]);                             \
-        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                        \
-          af[(ks + 1) & 1][mt] = __builtin_bit_cast(bf16x8, st_[a_off[mt][ks + 1]]);                             \
-      }                                                                                                          \
-      _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                          \
-        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                        \
-          acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][nt], af[ks & 1][mt], acc[nt][mt], 0, 0, 0); \
-    }                                                                                                            \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                       \
+      _Pragma("unroll") for (int g = 0; g < G; ++g) {                                                         \
+        if (WITH_LOADS) {                                                                                     \
+          _Pragma("unroll") for (int i = 0; i < LOADS; ++i)                                                   \
+            if (i * (TG / 2) / LOADS == ks * G + g) dma16(VLC_SRC(nkt_, i), VLC_LDS_DST(nst_, i));            \
+        }                                                                                                     \
+        if (ks + 1 < KS) {                                                                                    \
+          _Pragma("unroll") for (int f = 0; f < NF; ++f) {                                                    \
+            if (f * G / NF == g) {                                                                            \
+              if (f < NT) wf[(ks + 1) & 1][f < NT ? f : 0] = __builtin_bit_cast(bf16x8, st_[w_off[f < NT ? f : 0][ks + 1]]); \
+              else af[(ks + 1) & 1][f >= NT ? f - NT : 0] = __builtin_bit_cast(bf16x8, st_[a_off[f >= NT ? f - NT : 0][ks + 1]]); \
+            }                                                                                                 \
+          }                                                                                                   \
+        }                                                                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                                                    \
+        _Pragma("unroll") for (int j = 0; j < MPG; ++j) {                                                     \
+          const int t_ = g * MPG + j;                                                                         \
+          acc[t_ / MT][t_ % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][t_ / MT], af[ks & 1][t_ % MT], \
+                                                                          acc[t_ / MT][t_ % MT], 0, 0, 0);    \
+        }                                                                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                                                    \
+      }                                                                                                       \
+    }                                                                                                         \
   }
 
   // prologue: fill STAGES-1 stages
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
-    if (s < KT) VLC_ISSUE(s, s)
+    if (s < KT) { VLC_ISSUE(s, s) }
   int kt = 0;
   for (; kt + STAGES - 1 < KT; ++kt) {   // steady state: k-tile kt+STAGES-1 is fetched while kt is consumed
     VLC_WAITCNT_VM((STAGES - 2) * LOADS);          // this wavefront's part of k-tile kt has landed
     __syncthreads();                               // everyone's part has; stage (kt-1)%STAGES is free
-    VLC_ISSUE(kt + STAGES - 1, (kt + STAGES - 1) % STAGES)
-    VLC_COMPUTE_TILE(kt)
+    VLC_COMPUTE_TILE(kt, true, kt + STAGES - 1, (kt + STAGES - 1) % STAGES)
   }
   for (; kt < KT; ++kt) {                // drain
     const int later = KT - 1 - kt;
     if (later >= 2) { VLC_WAITCNT_VM(2 * LOADS); } else if (later == 1) { VLC_WAITCNT_VM(LOADS); } else { VLC_WAITCNT_VM(0); }
     __syncthreads();
-    VLC_COMPUTE_TILE(kt)
+    VLC_COMPUTE_TILE(kt, false, 0, 0)
   }
 #undef VLC_ISSUE
+#undef VLC_SRC
+#undef VLC_LDS_DST
 #undef VLC_COMPUTE_TILE
 
   // ---- epilogue ---------------------------------------------------------------------------------
@@ -385,7 +420,7 @@ int launch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
   return VLC_OK;
 }
 
-// Tile choice.  Many rows: 256 x 256 tiles, 8 wavefronts.  Few rows: 128 x 128 tiles, 4 wavefronts, two
+// Tile choice.  Many rows: 256 x 256 tiles, 4 wavefronts of 128 x 128.  Few rows: 128 x 128 tiles, 4 wavefronts, two
 // workgroups per CU; if that still leaves most of the 256 CUs idle, the k range is split as well.
 template <int EPI>
 int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
@@ -393,7 +428,7 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
                   void* splitk_ws, int64_t splitk_ws_bytes, hipStream_t st) {
   const int KT = (int)(K / BK);
   if (M >= 1536)
-    return launch_bf16<256, 256, 2, 4, 2, 1, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, st);
+    return launch_bf16<256, 256, 2, 2, 2, 1, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, st);
   constexpr int CN = (EPI == EPI_SWIGLU) ? 64 : 128;
   const int64_t tiles = ((M + 127) / 128) * ((N + CN - 1) / CN);
   int splits = 1;
