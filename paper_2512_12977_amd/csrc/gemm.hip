@@ -425,7 +425,7 @@ int launch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
 template <int EPI>
 int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
                   int64_t K, const void* bias, const void* resid, int64_t ldr, const int32_t* rmap,
-                  void* splitk_ws, int64_t splitk_ws_bytes, hipStream_t st) {
+                  void* splitk_ws, int64_t splitk_ws_bytes, int* deferred, hipStream_t st) {
   const int KT = (int)(K / BK);
   if (M >= 1536)
     return launch_bf16<256, 256, 2, 2, 2, 1, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, st);
@@ -434,12 +434,15 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
   int splits = 1;
   if constexpr (EPI != EPI_SWIGLU) {
     if (splitk_ws && tiles < 384) {
-      // 512 workgroups are resident at once (two per CU): pick the split count that minimises
-      // (rounds of resident workgroups) x (k-tiles per workgroup), keeping >= 8 k-tiles per split.
-      int64_t best = (int64_t)((tiles + 511) / 512) * KT;
+      // 512 workgroups are resident at once (two per CU).  Cost of a split count, in units of one
+      // workgroup's k-tile (~1.2 us): (rounds of resident workgroups) x (k-tiles per workgroup), plus
+      // a second kernel and, per split, one float matrix written and read back (8 bytes per element
+      // at ~4 TB/s = 1.7e-6 units per element).  At least 8 k-tiles per split.
+      float best = (float)((tiles + 511) / 512) * (float)KT;
       for (int sp = 2; sp <= 8; ++sp) {
         if (KT / sp < 8 || (int64_t)sp * M * N * 4 > splitk_ws_bytes) break;
-        const int64_t cost = ((tiles * sp + 511) / 512) * ((KT + sp - 1) / sp) + 2;   // +2: second launch
+        const float cost = (float)(((tiles * sp + 511) / 512) * ((KT + sp - 1) / sp)) + 2.0f +
+                           (float)sp * (float)(M * N) * 1.7e-6f;
         if (cost < best) {
           best = cost;
           splits = sp;
@@ -455,6 +458,10 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
     int rc = launch_bf16<128, 128, 2, 2, 2, 2, EPI_PARTIAL>(A, lda, W, splitk_ws, N, M, N, K, nullptr, nullptr, 0,
                                                             nullptr, splits, per, st);
     if (rc) return rc;
+    if (deferred) {   // the caller's next kernel sums the partials and applies the epilogue
+      *deferred = splits;
+      return VLC_OK;
+    }
     const int64_t threads = M * (N / 4);
     hipLaunchKernelGGL(splitk_epilogue_kernel<EPI>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
                        (const float*)splitk_ws, splits, (uint16_t*)C, ldc, (int)M, (int)N, (const uint16_t*)bias,
@@ -487,7 +494,9 @@ int64_t gemm_splitk_ws_bytes(int64_t n_rows, int64_t max_n) {
 
 int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
                 int64_t K, int epilogue, const void* bias, const void* resid, int64_t ldr,
-                const int32_t* rmap, int dtype, void* splitk_ws, int64_t splitk_ws_bytes, hipStream_t st) {
+                const int32_t* rmap, int dtype, void* splitk_ws, int64_t splitk_ws_bytes, hipStream_t st,
+                int* deferred) {
+  if (deferred) *deferred = 0;
   if (M <= 0 || N <= 0) return VLC_OK;
   if (K <= 0) return fail(VLC_ERR_SHAPE, "gemm: K=%lld", (long long)K);
   if (M > INT32_MAX || N > INT32_MAX / 2 || K > INT32_MAX)
@@ -497,10 +506,10 @@ int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
     if (N % 4 || lda % 8 || ldc % 4 || (epilogue == EPI_RESIDUAL && ldr % 4))
       return fail(VLC_ERR_SHAPE, "gemm(bf16): N, lda, ldc, ldr must keep 8-byte (A: 16-byte) alignment");
     switch (epilogue) {
-      case EPI_BIAS: return dispatch_bf16<EPI_BIAS>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, st);
-      case EPI_BIAS_F32: return dispatch_bf16<EPI_BIAS_F32>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, st);
-      case EPI_RESIDUAL: return dispatch_bf16<EPI_RESIDUAL>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, st);
-      case EPI_SWIGLU: return dispatch_bf16<EPI_SWIGLU>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, st);
+      case EPI_BIAS: return dispatch_bf16<EPI_BIAS>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, deferred, st);
+      case EPI_BIAS_F32: return dispatch_bf16<EPI_BIAS_F32>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, deferred, st);
+      case EPI_RESIDUAL: return dispatch_bf16<EPI_RESIDUAL>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, deferred, st);
+      case EPI_SWIGLU: return dispatch_bf16<EPI_SWIGLU>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, deferred, st);
     }
   } else if (dtype == VLC_F32) {
     switch (epilogue) {

@@ -145,13 +145,15 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
   rc = vlc::launch_rmsnorm(h_in, p->map, w->w_ln1, xn, n, s.H, s.eps, s.dtype, st);
   if (rc) return rc;
   VLC_MARK(2);
+  int qkv_splits = 0;   // > 0: the projection is still split-K partials, summed by the next kernel
   rc = vlc::launch_gemm(xn, H, w->w_qkv, qkv32, nqkv, n, nqkv, H, vlc::EPI_BIAS_F32, w->b_qkv, nullptr, 0,
-                        nullptr, s.dtype, skw, ws.splitk_bytes, st);
+                        nullptr, s.dtype, skw, ws.splitk_bytes, st, &qkv_splits);
   if (rc) return rc;
   // RoPE at the new positions; fresh k, v overwrite their slots (after the reused tokens were placed).
   VLC_MARK(3);
   rc = vlc::launch_rope_qk_scatter(qkv32, p->pos, p->slot, n, s.Hq, s.Hkv, s.D, freq, qrot, k_cache, v_cache,
-                                   s.dtype, st);
+                                   s.dtype, st, static_cast<const float*>(skw), qkv_splits > 0 ? qkv_splits : 1,
+                                   w->b_qkv);
   if (rc) return rc;
   VLC_MARK(4);
   rc = vlc::launch_attention(qrot, hqd, k_cache, v_cache, p->row_kv_start, p->row_kv_len, n, s.Hq, s.Hkv, s.D,
@@ -159,11 +161,16 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
                              ws.att_bytes, p->kv_rows, st);
   if (rc) return rc;
   VLC_MARK(5);
+  int o_splits = 0;
   rc = vlc::launch_gemm(attn, hqd, w->w_o, h1, H, n, H, hqd, vlc::EPI_RESIDUAL, nullptr, h_in, H, p->map,
-                        s.dtype, skw, ws.splitk_bytes, st);
+                        s.dtype, skw, ws.splitk_bytes, st, &o_splits);
   if (rc) return rc;
   VLC_MARK(6);
-  rc = vlc::launch_rmsnorm(h1, nullptr, w->w_ln2, n2, n, s.H, s.eps, s.dtype, st);
+  if (o_splits > 0)   // split-K partials: sum + residual -> h1 and the norm of h1 in one kernel
+    rc = vlc::launch_sum_residual_rmsnorm(static_cast<const float*>(skw), o_splits, h_in, p->map, w->w_ln2, h1,
+                                          n2, n, s.H, s.eps, st);
+  else
+    rc = vlc::launch_rmsnorm(h1, nullptr, w->w_ln2, n2, n, s.H, s.eps, s.dtype, st);
   if (rc) return rc;
   VLC_MARK(7);
   rc = vlc::launch_gemm(n2, H, w->w_gate_up, act, I, n, I, H, vlc::EPI_SWIGLU, nullptr, nullptr, 0, nullptr,

@@ -144,13 +144,16 @@ template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void rope_shift_kernel(
     const uint4* k_src, const uint4* v_src, uint4* k_dst, uint4* v_dst,   // may alias (in-place use)
     const int32_t* __restrict__ src_row, const int32_t* __restrict__ dst_row,
-    const int32_t* __restrict__ delta, int64_t n_tok, int Hkv, RopeFreq freq) {
+    const int32_t* __restrict__ delta, int64_t n_tok, int Hkv, int head_parts, RopeFreq freq) {
   constexpr int VEC = Chunk<T>::VEC;
   constexpr int CH = (D / 2) / VEC;                  // chunks per half head
   constexpr int HEAD_CHUNKS = 2 * CH;                // chunks per head
   const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  const int64_t tok = gid / CH;
-  const int c = (int)(gid - tok * CH);
+  const int64_t t = gid / CH;
+  const int c = (int)(gid - t * CH);
+  const int64_t tok = t / head_parts;                // head_parts > 1: the heads of a token are shared out
+  const int hpt = Hkv / head_parts;                  // heads per thread (head_parts divides Hkv)
+  const int h0 = (int)(t - tok * head_parts) * hpt;
   if (tok >= n_tok) return;
   const int64_t srow = src_row[tok], drow = dst_row[tok];
   const int d = delta[tok];
@@ -164,7 +167,7 @@ __global__ __launch_bounds__(kThreads) void rope_shift_kernel(
   const uint4* vs = do_v ? v_src + srow * row_chunks + c : nullptr;
   uint4* vd = do_v ? v_dst + drow * row_chunks + c : nullptr;
 #pragma unroll 4
-  for (int h = 0; h < Hkv; ++h) {
+  for (int h = h0; h < h0 + hpt; ++h) {
     const uint4 lo_r = ks[h * HEAD_CHUNKS];
     const uint4 hi_r = ks[h * HEAD_CHUNKS + CH];
     uint4 v_lo, v_hi;
@@ -189,13 +192,19 @@ __global__ __launch_bounds__(kThreads) void rope_shift_kernel(
   }
 }
 
+constexpr int kMaxSplits = 8;   // the GEMM never splits the k range into more parts
+
 // One thread owns VEC rotation pairs of up to HB consecutive heads of one row of the fused q|k|v
 // matrix (unrounded float).  Head index < Hq: query, rotated, written to q_out.  < Hq+Hkv: key,
 // rotated and written to its cache slot (the blend).  Otherwise: value, written to its cache slot.
 // Outputs are rounded to the storage type once, after the rotation.
-template <typename T, int D, int HB>
+// SUM: the projection was left as `splits` float partial matrices (split_stride elements apart,
+// split-K); they are added here in split order, then the bias, and the sum is also stored to
+// qkv_sum so the unrounded projection stays available to the caller.
+template <typename T, int D, int HB, bool SUM>
 __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
-    const float* __restrict__ qkv, const int32_t* __restrict__ pos, const int32_t* __restrict__ slot,
+    const float* __restrict__ qkv, int splits, int64_t split_stride, const uint16_t* __restrict__ bias,
+    float* __restrict__ qkv_sum, const int32_t* __restrict__ pos, const int32_t* __restrict__ slot,
     int64_t n, int Hq, int Hkv, int head_blocks, RopeFreq freq, uint4* __restrict__ q_out,
     uint4* __restrict__ k_cache, uint4* __restrict__ v_cache) {
   constexpr int VEC = Chunk<T>::VEC;
@@ -222,8 +231,34 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
     float lo[VEC], hi[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; i += 4) {
-      const float4 a = *reinterpret_cast<const float4*>(r + (int64_t)h * D + i);
-      const float4 b = *reinterpret_cast<const float4*>(r + (int64_t)h * D + D / 2 + i);
+      float4 a = *reinterpret_cast<const float4*>(r + (int64_t)h * D + i);
+      float4 b = *reinterpret_cast<const float4*>(r + (int64_t)h * D + D / 2 + i);
+      if constexpr (SUM) {
+        float4 pa[kMaxSplits], pb[kMaxSplits];   // independent loads first, then the sum in split order
+#pragma unroll
+        for (int k = 1; k < kMaxSplits; ++k)
+          if (k < splits) {
+            pa[k] = *reinterpret_cast<const float4*>(r + k * split_stride + (int64_t)h * D + i);
+            pb[k] = *reinterpret_cast<const float4*>(r + k * split_stride + (int64_t)h * D + D / 2 + i);
+          }
+#pragma unroll
+        for (int k = 1; k < kMaxSplits; ++k)
+          if (k < splits) {
+            a.x += pa[k].x; a.y += pa[k].y; a.z += pa[k].z; a.w += pa[k].w;
+            b.x += pb[k].x; b.y += pb[k].y; b.z += pb[k].z; b.w += pb[k].w;
+          }
+        if (bias) {
+          const uint2 ba = *reinterpret_cast<const uint2*>(bias + h * D + c * VEC + i);
+          const uint2 bb = *reinterpret_cast<const uint2*>(bias + h * D + D / 2 + c * VEC + i);
+          a.x += __uint_as_float(ba.x << 16); a.y += __uint_as_float(ba.x & 0xffff0000u);
+          a.z += __uint_as_float(ba.y << 16); a.w += __uint_as_float(ba.y & 0xffff0000u);
+          b.x += __uint_as_float(bb.x << 16); b.y += __uint_as_float(bb.x & 0xffff0000u);
+          b.z += __uint_as_float(bb.y << 16); b.w += __uint_as_float(bb.y & 0xffff0000u);
+        }
+        float* so = qkv_sum + row * ((int64_t)heads * D) + c * VEC + (int64_t)h * D;
+        *reinterpret_cast<float4*>(so + i) = a;
+        *reinterpret_cast<float4*>(so + D / 2 + i) = b;
+      }
       lo[i] = a.x; lo[i + 1] = a.y; lo[i + 2] = a.z; lo[i + 3] = a.w;
       hi[i] = b.x; hi[i + 1] = b.y; hi[i + 2] = b.z; hi[i + 3] = b.w;
     }
@@ -295,6 +330,71 @@ __global__ __launch_bounds__(kThreads) void rmsnorm_kernel(const uint4* __restri
   }
 }
 
+// Split-K partial sums [splits][n][H] (float) of a projection + residual -> h (rounded to bf16 and
+// stored), then RMSNorm of the rounded h -> y.  One workgroup per row; same summation order as the
+// stand-alone split-K epilogue (partials in split order, then the residual).
+template <int MAXC>
+__global__ __launch_bounds__(kThreads) void sum_residual_rmsnorm_kernel(
+    const float* __restrict__ part, int splits, int64_t split_stride, const uint4* __restrict__ resid,
+    const int32_t* __restrict__ rmap, const uint4* __restrict__ w, uint4* __restrict__ h,
+    uint4* __restrict__ y, int chunks, float inv_h, float eps) {
+  using CB = Chunk<uint16_t>;
+  const int64_t row = blockIdx.x;
+  const int64_t rrow = rmap ? (int64_t)rmap[row] : row;
+  float v[MAXC][8];
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = threadIdx.x + j * kThreads;
+    if (c < chunks) {
+      const float* p0 = part + row * ((int64_t)chunks * 8) + c * 8;
+      float4 pa[kMaxSplits], pb[kMaxSplits];
+#pragma unroll
+      for (int k = 0; k < kMaxSplits; ++k)
+        if (k < splits) {
+          pa[k] = *reinterpret_cast<const float4*>(p0 + k * split_stride);
+          pb[k] = *reinterpret_cast<const float4*>(p0 + k * split_stride + 4);
+        }
+      float rs[8];
+      CB::unpack(resid[rrow * chunks + c], rs);
+      float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+#pragma unroll
+      for (int k = 0; k < kMaxSplits; ++k)
+        if (k < splits) {
+          a.x += pa[k].x; a.y += pa[k].y; a.z += pa[k].z; a.w += pa[k].w;
+          b.x += pb[k].x; b.y += pb[k].y; b.z += pb[k].z; b.w += pb[k].w;
+        }
+      float o[8] = {a.x + rs[0], a.y + rs[1], a.z + rs[2], a.w + rs[3],
+                    b.x + rs[4], b.y + rs[5], b.z + rs[6], b.w + rs[7]};
+      const uint4 packed = CB::pack(o);
+      h[row * chunks + c] = packed;
+      CB::unpack(packed, v[j]);            // the norm sees the stored (rounded) values
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ss += v[j][i] * v[j][i];
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  __shared__ float red[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int i = 0; i < kThreads / 64; ++i) tot += red[i];
+  const float r = 1.0f / sqrtf(tot * inv_h + eps);
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = threadIdx.x + j * kThreads;
+    if (c < chunks) {
+      float wv[8], o[8];
+      CB::unpack(w[c], wv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = v[j][i] * r * wv[i];
+      y[row * chunks + c] = CB::pack(o);
+    }
+  }
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -319,12 +419,14 @@ int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v
                       int64_t n_tok, int Hkv, int D, const RopeFreq& f, int dtype, hipStream_t st) {
   if (n_tok <= 0) return VLC_OK;
   const int vec = dtype == VLC_BF16 ? 8 : 4;
-  const int64_t threads = n_tok * ((D / 2) / vec);
+  // few tokens: one head per thread, so that the grid still covers the chip
+  const int head_parts = n_tok * ((D / 2) / vec) < (int64_t)kThreads * 1024 ? Hkv : 1;
+  const int64_t threads = n_tok * head_parts * ((D / 2) / vec);
   const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads));
 #define VLC_LAUNCH_SHIFT(T, DD)                                                                       \
   hipLaunchKernelGGL((rope_shift_kernel<T, DD>), grid, dim3(kThreads), 0, st, (const uint4*)k_src,    \
                      (const uint4*)v_src, (uint4*)k_dst, (uint4*)v_dst, src_row, dst_row, delta,      \
-                     n_tok, Hkv, f)
+                     n_tok, Hkv, head_parts, f)
   if (dtype == VLC_BF16 && D == 128) VLC_LAUNCH_SHIFT(uint16_t, 128);
   else if (dtype == VLC_BF16 && D == 64) VLC_LAUNCH_SHIFT(uint16_t, 64);
   else if (dtype == VLC_F32 && D == 128) VLC_LAUNCH_SHIFT(float, 128);
@@ -337,21 +439,37 @@ int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v
 
 int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t* slot, int64_t n, int Hq,
                            int Hkv, int D, const RopeFreq& f, void* q_out, void* k_cache, void* v_cache,
-                           int dtype, hipStream_t st) {
+                           int dtype, hipStream_t st, const float* partials, int splits, const void* bias) {
   if (n <= 0) return VLC_OK;
-  constexpr int HB = 4;
+  if (splits > 1 && (dtype != VLC_BF16 || !partials))
+    return fail(VLC_ERR_SHAPE, "rope+scatter: split partials are a bf16-path input");
+  const int64_t split_stride = n * (int64_t)(Hq + 2 * Hkv) * D;
   const int vec = dtype == VLC_BF16 ? 8 : 4;
-  const int head_blocks = (Hq + 2 * Hkv + HB - 1) / HB;
+  const int heads = Hq + 2 * Hkv;
+  // Four heads per thread reuse each sine/cosine; with few rows one head per thread keeps the
+  // grid large enough to cover the chip.
+  const bool wide = n * ((heads + 3) / 4) * ((D / 2) / vec) >= (int64_t)kThreads * 2048;
+  const int hb = wide ? 4 : 1;
+  const int head_blocks = (heads + hb - 1) / hb;
   const int64_t threads = n * head_blocks * ((D / 2) / vec);
   const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads));
-#define VLC_LAUNCH_RQS(T, DD)                                                                         \
-  hipLaunchKernelGGL((rope_qk_scatter_kernel<T, DD, HB>), grid, dim3(kThreads), 0, st, qkv32, pos,    \
-                     slot, n, Hq, Hkv, head_blocks, f, (uint4*)q_out, (uint4*)k_cache, (uint4*)v_cache)
-  if (dtype == VLC_BF16 && D == 128) VLC_LAUNCH_RQS(uint16_t, 128);
-  else if (dtype == VLC_BF16 && D == 64) VLC_LAUNCH_RQS(uint16_t, 64);
-  else if (dtype == VLC_F32 && D == 128) VLC_LAUNCH_RQS(float, 128);
-  else if (dtype == VLC_F32 && D == 64) VLC_LAUNCH_RQS(float, 64);
+#define VLC_LAUNCH_RQS2(T, DD, SUM, HB)                                                               \
+  hipLaunchKernelGGL((rope_qk_scatter_kernel<T, DD, HB, SUM>), grid, dim3(kThreads), 0, st,           \
+                     SUM ? partials : qkv32, splits, split_stride, (const uint16_t*)bias,             \
+                     const_cast<float*>(qkv32), pos, slot, n, Hq, Hkv, head_blocks, f, (uint4*)q_out, \
+                     (uint4*)k_cache, (uint4*)v_cache)
+#define VLC_LAUNCH_RQS(T, DD, SUM)                                                                    \
+  do {                                                                                                \
+    if (wide) VLC_LAUNCH_RQS2(T, DD, SUM, 4); else VLC_LAUNCH_RQS2(T, DD, SUM, 1);                    \
+  } while (0)
+  if (splits > 1 && D == 128) VLC_LAUNCH_RQS(uint16_t, 128, true);
+  else if (splits > 1 && D == 64) VLC_LAUNCH_RQS(uint16_t, 64, true);
+  else if (dtype == VLC_BF16 && D == 128) VLC_LAUNCH_RQS(uint16_t, 128, false);
+  else if (dtype == VLC_BF16 && D == 64) VLC_LAUNCH_RQS(uint16_t, 64, false);
+  else if (dtype == VLC_F32 && D == 128) VLC_LAUNCH_RQS(float, 128, false);
+  else if (dtype == VLC_F32 && D == 64) VLC_LAUNCH_RQS(float, 64, false);
   else return fail(VLC_ERR_SHAPE, "rope+scatter: unsupported D=%d", D);
+#undef VLC_LAUNCH_RQS2
 #undef VLC_LAUNCH_RQS
   VLC_CHECK_LAUNCH("rope_qk_scatter");
   return VLC_OK;
@@ -379,6 +497,29 @@ int launch_rmsnorm(const void* x, const int32_t* map, const void* w, void* y, in
   }
 #undef VLC_LAUNCH_RMS
   VLC_CHECK_LAUNCH("rmsnorm");
+  return VLC_OK;
+}
+
+int launch_sum_residual_rmsnorm(const float* partials, int splits, const void* resid, const int32_t* rmap,
+                                const void* w, void* h, void* y, int64_t n, int H, float eps,
+                                hipStream_t st) {
+  if (n <= 0) return VLC_OK;
+  if (H % 8) return fail(VLC_ERR_SHAPE, "sum+residual+rmsnorm: H=%d not a multiple of 8", H);
+  if (splits < 1 || splits > kMaxSplits) return fail(VLC_ERR_SHAPE, "sum+residual+rmsnorm: %d splits", splits);
+  const int chunks = H / 8;
+  const dim3 grid((unsigned)n);
+  const float inv_h = 1.0f / (float)H;
+  const int64_t split_stride = n * (int64_t)H;
+#define VLC_LAUNCH_SRN(MAXC)                                                                          \
+  hipLaunchKernelGGL((sum_residual_rmsnorm_kernel<MAXC>), grid, dim3(kThreads), 0, st, partials,      \
+                     splits, split_stride, (const uint4*)resid, rmap, (const uint4*)w, (uint4*)h,     \
+                     (uint4*)y, chunks, inv_h, eps)
+  if (chunks <= kThreads * 2) VLC_LAUNCH_SRN(2);
+  else if (chunks <= kThreads * 4) VLC_LAUNCH_SRN(4);
+  else if (chunks <= kThreads * 8) VLC_LAUNCH_SRN(8);
+  else return fail(VLC_ERR_SHAPE, "sum+residual+rmsnorm: H=%d too large", H);
+#undef VLC_LAUNCH_SRN
+  VLC_CHECK_LAUNCH("sum_residual_rmsnorm");
   return VLC_OK;
 }
 

@@ -45,6 +45,12 @@ int launch_gather_rows(const void* src, int64_t row_bytes, const int32_t* idx, i
 int launch_rmsnorm(const void* x, const int32_t* map, const void* w, void* y, int64_t n, int H,
                    float eps, int dtype, hipStream_t st);
 
+// bf16 path, after a GEMM that left `splits` float partial matrices [splits][n][H]:
+// h = round(sum of partials + resid[rmap ? rmap[i] : i]) (stored), y = RMSNorm(h) * w.
+int launch_sum_residual_rmsnorm(const float* partials, int splits, const void* resid, const int32_t* rmap,
+                                const void* w, void* h, void* y, int64_t n, int H, float eps,
+                                hipStream_t st);
+
 int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
                       const int32_t* src_row, const int32_t* dst_row, const int32_t* delta,
                       int64_t n_tok, int Hkv, int D, const RopeFreq& f, int dtype, hipStream_t st);
@@ -57,9 +63,13 @@ int launch_scatter_kv(const void* k_new, const void* v_new, int64_t src_stride_e
 // From the unrounded float rows qkv32 [n, (Hq+2Hkv)*D]: q rotated at pos[i] -> q_out [n, Hq*D];
 // k rotated -> k_cache[slot[i]]; v -> v_cache[slot[i]].  Outputs have the storage type `dtype`
 // and are rounded once, after the rotation.
+// splits > 1 (bf16 path): the projection is still `splits` float partial matrices [splits][n][(Hq+2Hkv)D]
+// at `partials`; they are summed in split order, the bias (may be NULL) added, and the sum is
+// also written to qkv32.  Otherwise qkv32 is the finished projection and is only read.
 int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t* slot, int64_t n, int Hq,
                            int Hkv, int D, const RopeFreq& f, void* q_out, void* k_cache, void* v_cache,
-                           int dtype, hipStream_t st);
+                           int dtype, hipStream_t st, const float* partials = nullptr, int splits = 1,
+                           const void* bias = nullptr);
 
 // q rows have a row stride of q_stride elements (dense q: Hq*D).  ws: optional float scratch of
 // attention_ws_bytes() that allows splitting the key range when there are few query rows.
@@ -78,9 +88,13 @@ enum Epilogue {
 // C[M,N] = epilogue(A[M,K] (row stride lda) * W[N(or 2N),K]^T); C row stride ldc.
 // splitk_ws: optional float scratch for split-K partials (used when the output has few tiles);
 // gemm_splitk_ws_bytes gives a size that lets every GEMM of a layer with n rows split freely.
+// deferred (optional): if the k range was split, the epilogue kernel is NOT run, *deferred is the
+// number of float partial matrices [splits][M][N] left at splitk_ws and the caller's next kernel
+// must sum them and apply the epilogue; *deferred = 0 means C is complete.
 int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
                 int64_t K, int epilogue, const void* bias, const void* resid, int64_t ldr,
-                const int32_t* rmap, int dtype, void* splitk_ws, int64_t splitk_ws_bytes, hipStream_t st);
+                const int32_t* rmap, int dtype, void* splitk_ws, int64_t splitk_ws_bytes, hipStream_t st,
+                int* deferred = nullptr);
 int64_t gemm_splitk_ws_bytes(int64_t n_rows, int64_t max_n);
 
 }  // namespace vlc
