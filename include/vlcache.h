@@ -248,7 +248,9 @@ int vlc_layer_forward(const vlc_layer_shape* shape, const vlc_layer_weights* wei
 /*
  * vlc_layer_forward with per-stage timing marks, for benchmarks: stage_events (host array of
  * VLC_LAYER_STAGES + 1 hipEvent_t handles created by the caller) - event i is recorded on `stream`
- * before stage i starts, the last one after the final stage.  Stages, in launch order:
+ * before stage i starts, the last one after the final stage; a NULL entry records nothing (each
+ * recorded event costs a few microseconds of stream time, so a caller interested in one stage
+ * passes only the two events around it).  Stages, in launch order:
  *   0 reused K/V placement (RoPE shift)   1 input RMSNorm (reads h_in through map)
  *   2 q|k|v projection                    3 RoPE of q,k + scatter of fresh k,v
  *   4 attention of the recomputed rows    5 output projection + residual

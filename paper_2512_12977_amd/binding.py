@@ -225,7 +225,7 @@ LAYER_STAGES = ("rope_shift", "rmsnorm1", "qkv_gemm", "rope_scatter", "attention
 
 def vlc_layer_forward_timed(shape: LayerShape, weights: LayerWeights, plan: LayerPlan, h_in, h_out, k_cache,
                             v_cache, workspace, stage_events, stream=None) -> None:
-    """stage_events: ctypes array of len(LAYER_STAGES)+1 hipEvent_t handles (c_void_p)."""
+    """stage_events: ctypes array of len(LAYER_STAGES)+1 hipEvent_t handles (c_void_p); NULL entries are skipped."""
     _check(lib().vlc_layer_forward_timed(C.addressof(shape), C.addressof(weights), C.addressof(plan),
                                          _dev(h_in), _dev(h_out), _dev(k_cache), _dev(v_cache), _dev(workspace),
                                          workspace.numel() * workspace.element_size(), _stream(stream),

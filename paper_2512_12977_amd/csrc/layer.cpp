@@ -91,7 +91,7 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
   // optional stage timing: ev[i] is recorded before stage i, ev[VLC_LAYER_STAGES] after the last
 #define VLC_MARK(i)                                                                     \
   do {                                                                                  \
-    if (ev) VLC_CHECK_HIP(hipEventRecord((hipEvent_t)ev[i], (hipStream_t)stream));      \
+    if (ev && ev[i]) VLC_CHECK_HIP(hipEventRecord((hipEvent_t)ev[i], (hipStream_t)stream)); \
   } while (0)
   int rc = check_shape(shape, who);
   if (rc) return rc;
@@ -197,8 +197,6 @@ extern "C" int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_l
                                        void* v_cache, void* workspace, int64_t workspace_bytes, void* stream,
                                        void* const* stage_events) {
   if (!stage_events) return fail(VLC_ERR_NULL, "vlc_layer_forward_timed: stage_events is NULL");
-  for (int i = 0; i <= VLC_LAYER_STAGES; ++i)
-    if (!stage_events[i]) return fail(VLC_ERR_NULL, "vlc_layer_forward_timed: stage_events[%d] is NULL", i);
   return layer_forward_impl(shape, w, p, h_in, h_out, k_cache, v_cache, workspace, workspace_bytes, stream,
                             stage_events);
 }
