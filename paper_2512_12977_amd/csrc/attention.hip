@@ -61,21 +61,39 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 __device__ __forceinline__ int k_swz(int key, int c) { return c ^ (key & 15); }
 __device__ __forceinline__ int v_swz(int key, int c) { return c ^ ((key & 3) << 2); }
 
+// One wavefront-level global -> LDS copy of 64 x 16 bytes (lane l's 16 bytes land at dst + l).  Issued
+// as inline assembly: through the builtin the compiler, unable to tell the LDS write apart from the
+// fragment reads that follow, waits for every outstanding copy (vmcnt(0)) before the first of them,
+// which serialises the prefetch with the block it was meant to overlap.  This way the copies are
+// tracked only by the explicit waits at the end of each key block (the key loop has no other
+// vector-memory instruction).  M0 holds the LDS address and is written right before each use.
+__device__ __forceinline__ void dma16(const void* gptr, u32x4* lds_dst) {
+  const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_dst;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(a), "v"(gptr)
+               : "memory");
+}
+
 #define VLC_ATT_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8) | (0 << 14))
 
 // SPLIT: blockIdx.z handles every nsplit-th share of each run's key blocks and leaves an
 // un-normalised partial (O as float, running max, running sum) for attention_merge_kernel; used when
 // there are too few (row tile, kv head) pairs to occupy the chip and the key loop is the critical path.
-template <bool SPLIT>
-__global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
+// RT: 32-row tiles of virtual rows per wavefront.  RT = 1: 128 virtual rows per workgroup, two
+// workgroups per CU.  RT = 2: 256 virtual rows, one workgroup per CU; every K and V fragment read
+// from LDS then feeds two MFMAs, which halves the LDS traffic per flop (with one row tile the
+// fragment reads alone would need the whole LDS bandwidth at full MFMA rate).
+template <bool SPLIT, int RT>
+__global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
     const uint16_t* __restrict__ q, int64_t q_stride, const uint16_t* __restrict__ kc,
     const uint16_t* __restrict__ vc, const int32_t* __restrict__ row_kv_start,
     const int32_t* __restrict__ row_kv_len, int n, int Hq, int Hkv, int g, int rows_per_tile,
     float scale_log2, uint16_t* __restrict__ out, int nsplit, float* __restrict__ part_o,
     float* __restrict__ part_ml) {
   __shared__ u32x4 lds[2 * ATT_STAGE_CHUNKS];     // 64 KB: K ring (2 tiles), then V ring (2 tiles)
-  __shared__ int s_start[VR];
-  __shared__ int s_len[VR];
+  __shared__ int s_start[VR * RT];
+  __shared__ int s_len[VR * RT];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, x = lane >> 5;
@@ -83,39 +101,55 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
   const int row0 = blockIdx.x * rows_per_tile;
   const int rows_here = min(rows_per_tile, n - row0);
 
-  if (tid < rows_per_tile) {
+  if (tid < rows_per_tile) {                       // rows_per_tile <= 128 * RT <= 256 threads
     const bool ok = tid < rows_here;
     s_start[tid] = ok ? row_kv_start[row0 + tid] : -1;
     s_len[tid] = ok ? row_kv_len[row0 + tid] : 0;
   }
   __syncthreads();
 
-  // this lane's virtual row
-  const int vr = wave * 32 + l32;
-  const int r_local = vr / g;
-  const int head = kvh * g + (vr - r_local * g);
-  const bool vr_ok = r_local < rows_here;
-  const int my_len = vr_ok ? s_len[r_local] : 0;
+  // this lane's virtual rows (one per row tile)
+  int r_local[RT], head[RT], my_len[RT];
+  bool vr_ok[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int vr = (wave * RT + rt) * 32 + l32;
+    r_local[rt] = vr / g;
+    head[rt] = kvh * g + (vr - r_local[rt] * g);
+    vr_ok[rt] = r_local[rt] < rows_here;
+    my_len[rt] = vr_ok[rt] ? s_len[r_local[rt]] : 0;
+  }
 
   // Q fragments: Q[vr][16*ks + 8*x .. +8)
-  bf16x8 qf[ATT_D / 16];
-  {
-    const u32x4* qp = reinterpret_cast<const u32x4*>(q + (int64_t)(row0 + (vr_ok ? r_local : 0)) * q_stride +
-                                                     (int64_t)head * ATT_D);
+  bf16x8 qf[RT][ATT_D / 16];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const u32x4* qp = reinterpret_cast<const u32x4*>(q + (int64_t)(row0 + (vr_ok[rt] ? r_local[rt] : 0)) * q_stride +
+                                                     (int64_t)head[rt] * ATT_D);
 #pragma unroll
     for (int ks = 0; ks < ATT_D / 16; ++ks) {
       u32x4 v = {0u, 0u, 0u, 0u};
-      if (vr_ok) v = qp[2 * ks + x];
-      qf[ks] = __builtin_bit_cast(bf16x8, v);
+      if (vr_ok[rt]) v = qp[2 * ks + x];
+      qf[rt][ks] = __builtin_bit_cast(bf16x8, v);
     }
   }
 
-  f32x16 o_acc[ATT_D / 32];
+  // The Q loads are the only vector-memory reads the compiler knows of; completing them here keeps it
+  // from placing a vmcnt(0) wait (which would also wait for freshly issued K/V copies) at their
+  // first use inside the key loop.
+  VLC_ATT_WAIT_VM0();
+
+  f32x16 o_acc[RT][ATT_D / 32];
+  float m_run[RT], l_run[RT];
 #pragma unroll
-  for (int i = 0; i < ATT_D / 32; ++i)
+  for (int rt = 0; rt < RT; ++rt) {
+    m_run[rt] = -INFINITY;
+    l_run[rt] = 0.f;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) o_acc[i][e] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+    for (int i = 0; i < ATT_D / 32; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o_acc[rt][i][e] = 0.f;
+  }
 
   const int64_t kv_row_elems = (int64_t)Hkv * ATT_D;
 
@@ -160,10 +194,16 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
     int seg_max = 0;
     for (int r = seg_begin; r < seg_end; ++r) seg_max = max(seg_max, s_len[r]);
 
-    const bool in_seg = vr_ok && r_local >= seg_begin && r_local < seg_end;
-    const int len = in_seg ? my_len : 0;
-    // longest / shortest visible range among this wavefront's lanes (uniform per wavefront)
-    int w_max = len, w_min = len;
+    int len[RT];
+    int w_max = 0, w_min = 0x7fffffff;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const bool in_seg = vr_ok[rt] && r_local[rt] >= seg_begin && r_local[rt] < seg_end;
+      len[rt] = in_seg ? my_len[rt] : 0;
+      w_max = max(w_max, len[rt]);
+      w_min = min(w_min, len[rt]);
+    }
+    // longest / shortest visible range among this wavefront's rows (uniform per wavefront)
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
       w_max = max(w_max, __shfl_xor(w_max, o));
@@ -188,93 +228,118 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
     u32x4* dst_ = lds + (lds_chunk0_) + wave * 256;                                                            \
     if (key0_ + KB <= seg_max) { /* whole block inside the run: uniform base + invariant lane offset */        \
       const char* blk_ = reinterpret_cast<const char*>(base_) + (int64_t)key0_ * kv_row_bytes;                 \
-      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                            \
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(blk_ + go_[i]),       \
-                                         (__attribute__((address_space(3))) void*)(dst_ + i * 64), 16, 0, 0);  \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) dma16(blk_ + go_[i], dst_ + i * 64);                       \
     } else { /* last block of the run: rows past the end re-read the last row */                               \
       _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                          \
         const int64_t gk_ = (int64_t)min(key0_ + t_key[i], last_key) * kv_row_elems;                           \
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base_ + gk_ + c_[i] * 8), \
-                                         (__attribute__((address_space(3))) void*)(dst_ + i * 64), 16, 0, 0);  \
+        dma16(base_ + gk_ + c_[i] * 8, dst_ + i * 64);                                                         \
       }                                                                                                        \
     }                                                                                                          \
   }
 #define VLC_ATT_ISSUE_K(kb_, stage_) VLC_ATT_ISSUE_TILE(kbase, k_go, k_c, kb_, (stage_) * K_TILE_CHUNKS)
 #define VLC_ATT_ISSUE_V(kb_, stage_) VLC_ATT_ISSUE_TILE(vbase, v_go, v_c, kb_, 2 * K_TILE_CHUNKS + (stage_) * V_TILE_CHUNKS)
-    // S^T of one key block: ST = K Q^T from K ring stage kst_
+    // S^T of one key block: ST[rt][mt] = K Q^T from K ring stage kst_; a K fragment serves every row tile
 #define VLC_ATT_QK(ST, kst_)                                                                                   \
   {                                                                                                            \
     const unsigned char* sk_ = reinterpret_cast<const unsigned char*>(lds) + (kst_) * (K_TILE_CHUNKS * 16);    \
-    _Pragma("unroll") for (int mt = 0; mt < 2; ++mt) {                                                         \
-      _Pragma("unroll") for (int e = 0; e < 16; ++e) ST[mt][e] = 0.f;                                          \
-      _Pragma("unroll") for (int ks = 0; ks < ATT_D / 16; ++ks) {                                              \
-        const u32x4 kv_ = *reinterpret_cast<const u32x4*>(sk_ + k_rd[ks] + mt * (32 * 256));                   \
-        ST[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv_), qf[ks], ST[mt], 0, 0, 0); \
-      }                                                                                                        \
+    _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                          \
+      _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                         \
+        _Pragma("unroll") for (int e = 0; e < 16; ++e) ST[rt][mt][e] = 0.f;                                    \
+    u32x4 kf_[2];   /* fragment i+1 is read while fragment i is multiplied */                                  \
+    kf_[0] = *reinterpret_cast<const u32x4*>(sk_ + k_rd[0]);                                                   \
+    _Pragma("unroll") for (int i = 0; i < 2 * (ATT_D / 16); ++i) {                                             \
+      const int mt = i / (ATT_D / 16), ks = i % (ATT_D / 16);                                                  \
+      if (i + 1 < 2 * (ATT_D / 16))                                                                            \
+        kf_[(i + 1) & 1] = *reinterpret_cast<const u32x4*>(sk_ + k_rd[(i + 1) % (ATT_D / 16)] +                \
+                                                           ((i + 1) / (ATT_D / 16)) * (32 * 256));             \
+      _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                        \
+        ST[rt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf_[i & 1]), qf[rt][ks], \
+                                                             ST[rt][mt], 0, 0, 0);                             \
     }                                                                                                          \
   }
     // keys of the block beyond a lane's visible range are masked (only where the block crosses it)
 #define VLC_ATT_MASK(ST, key0_)                                                                                \
   {                                                                                                            \
     if ((key0_) + KB > w_min) {                                                                                \
-      _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                         \
-        _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                       \
-          const int key_ = (key0_) + 32 * mt + 8 * (j >> 2) + 4 * x + (j & 3);                                 \
-          ST[mt][j] = key_ < len ? ST[mt][j] : -INFINITY;                                                      \
-        }                                                                                                      \
+      _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                        \
+        _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                       \
+          _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                     \
+            const int key_ = (key0_) + 32 * mt + 8 * (j >> 2) + 4 * x + (j & 3);                               \
+            ST[rt][mt][j] = key_ < len[rt] ? ST[rt][mt][j] : -INFINITY;                                        \
+          }                                                                                                    \
     }                                                                                                          \
   }
     // online softmax (base 2) of ST: branch-free, so that it shares a basic block with the next
-    // block's S^T MFMAs; leaves probabilities in ST and the rescale factor in alpha_ / grew_
+    // block's S^T MFMAs; leaves probabilities in ST and the rescale factors in alpha_ / grew_
 #define VLC_ATT_SOFTMAX(ST)                                                                                    \
-    float mx_ = -INFINITY;                                                                                     \
-    _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                           \
-      _Pragma("unroll") for (int j = 0; j < 16; ++j) mx_ = fmaxf(mx_, ST[mt][j]);                              \
-    mx_ = fmaxf(mx_, __shfl_xor(mx_, 32)) * scale_log2;   /* scale > 0: max commutes with it */                \
-    const float m_new_ = fmaxf(m_run, mx_);                                                                    \
-    const float m_use_ = (m_new_ == -INFINITY) ? 0.f : m_new_;                                                 \
-    const float alpha_ = __builtin_amdgcn_exp2f(m_run - m_use_);   /* m_run = -inf -> 0 */                     \
-    const bool grew_ = m_new_ > m_run;                                                                         \
-    m_run = m_new_;                                                                                            \
-    float psum_ = 0.f;                                                                                         \
-    _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                           \
-      _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                         \
-        const float p_ = __builtin_amdgcn_exp2f(fmaf(ST[mt][j], scale_log2, -m_use_));                         \
-        ST[mt][j] = p_;                                                                                        \
-        psum_ += p_;                                                                                           \
-      }                                                                                                        \
-    l_run = l_run * alpha_ + psum_;
-    // order template for the shared block: one MFMA and its K fragment read per eight vector ops
-#define VLC_ATT_INTERLEAVE()                                                                                   \
-    _Pragma("unroll") for (int g_ = 0; g_ < 16; ++g_) {                                                        \
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                       \
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                       \
-      __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);                                                       \
+    float alpha_[RT];                                                                                          \
+    bool grew_ = false;                                                                                        \
+    _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                        \
+      float mx_ = -INFINITY;                                                                                   \
+      _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                         \
+        _Pragma("unroll") for (int j = 0; j < 16; ++j) mx_ = fmaxf(mx_, ST[rt][mt][j]);                        \
+      mx_ = fmaxf(mx_, __shfl_xor(mx_, 32)) * scale_log2;   /* scale > 0: max commutes with it */              \
+      const float m_new_ = fmaxf(m_run[rt], mx_);                                                              \
+      const float m_use_ = (m_new_ == -INFINITY) ? 0.f : m_new_;                                               \
+      alpha_[rt] = __builtin_amdgcn_exp2f(m_run[rt] - m_use_);   /* m_run = -inf -> 0 */                       \
+      grew_ = grew_ || (m_new_ > m_run[rt]);                                                                   \
+      m_run[rt] = m_new_;                                                                                      \
+      float psum_ = 0.f;                                                                                       \
+      _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                         \
+        _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                       \
+          const float p_ = __builtin_amdgcn_exp2f(fmaf(ST[rt][mt][j], scale_log2, -m_use_));                   \
+          ST[rt][mt][j] = p_;                                                                                  \
+          psum_ += p_;                                                                                         \
+        }                                                                                                      \
+      l_run[rt] = l_run[rt] * alpha_[rt] + psum_;                                                              \
     }
-    // O rescale (only when some row's maximum moved) and O^T += V^T P^T from V ring stage vst_
+    // order template for the shared block: two K fragment reads up front, then per fragment RT MFMAs,
+    // eight vector ops each, and the read of the fragment after next
+#define VLC_ATT_INTERLEAVE()                                                                                   \
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                                         \
+    _Pragma("unroll") for (int g_ = 0; g_ < 16; ++g_) {                                                        \
+      _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                      \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                     \
+        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);                                                     \
+      }                                                                                                        \
+      if (g_ < 14) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
+    }
+    // O rescale (only when some row's maximum moved) and O^T += V^T P^T from V ring stage vst_;
+    // a V^T fragment serves every row tile
 #define VLC_ATT_RESCALE_PV(ST, vst_)                                                                           \
   {                                                                                                            \
     if (__any(grew_)) {                                                                                        \
-      _Pragma("unroll") for (int i = 0; i < ATT_D / 32; ++i)                                                   \
-        _Pragma("unroll") for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha_;                                  \
+      _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                        \
+        _Pragma("unroll") for (int i = 0; i < ATT_D / 32; ++i)                                                 \
+          _Pragma("unroll") for (int e = 0; e < 16; ++e) o_acc[rt][i][e] *= alpha_[rt];                        \
     }                                                                                                          \
     const unsigned char* sv_ = reinterpret_cast<const unsigned char*>(lds + 2 * K_TILE_CHUNKS + (vst_) * V_TILE_CHUNKS); \
-    _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                            \
-      bf16x8 pf_;                                                                                              \
-      _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                          \
-        f32x2 pr_ = {ST[t >> 1][8 * (t & 1) + 2 * e], ST[t >> 1][8 * (t & 1) + 2 * e + 1]};                    \
-        const bf16x2 pb_ = __builtin_convertvector(pr_, bf16x2);                                               \
-        pf_[2 * e] = pb_[0];                                                                                   \
-        pf_[2 * e + 1] = pb_[1];                                                                               \
-      }                                                                                                        \
-      _Pragma("unroll") for (int md = 0; md < ATT_D / 32; ++md) {                                              \
-        s16x4 half_[2];                                                                                        \
+    bf16x8 pf_[RT];                                                                                            \
+    s16x4 vh_[2][2];   /* V^T fragment i+1 is read while fragment i is multiplied */                           \
+    _Pragma("unroll") for (int r = 0; r < 2; ++r)                                                              \
+      vh_[0][r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(          \
+          const_cast<unsigned char*>(sv_) + v_rd[0] + (8 * r) * 256));                                         \
+    _Pragma("unroll") for (int i = 0; i < 4 * (ATT_D / 32); ++i) {                                             \
+      const int t = i / (ATT_D / 32), md = i % (ATT_D / 32);                                                   \
+      if (i + 1 < 4 * (ATT_D / 32)) {                                                                          \
+        const int t1 = (i + 1) / (ATT_D / 32), md1 = (i + 1) % (ATT_D / 32);                                   \
         _Pragma("unroll") for (int r = 0; r < 2; ++r)                                                          \
-          half_[r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(       \
-              const_cast<unsigned char*>(sv_) + v_rd[md] + (16 * t + 8 * r) * 256));                           \
-        const s16x8 vv_ = __builtin_shufflevector(half_[0], half_[1], 0, 1, 2, 3, 4, 5, 6, 7);                 \
-        o_acc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv_), pf_, o_acc[md], 0, 0, 0); \
+          vh_[(i + 1) & 1][r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)( \
+              const_cast<unsigned char*>(sv_) + v_rd[md1] + (16 * t1 + 8 * r) * 256));                         \
       }                                                                                                        \
+      if (md == 0) {                                                                                           \
+        _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                      \
+          _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                      \
+            f32x2 pr_ = {ST[rt][t >> 1][8 * (t & 1) + 2 * e], ST[rt][t >> 1][8 * (t & 1) + 2 * e + 1]};        \
+            const bf16x2 pb_ = __builtin_convertvector(pr_, bf16x2);                                           \
+            pf_[rt][2 * e] = pb_[0];                                                                           \
+            pf_[rt][2 * e + 1] = pb_[1];                                                                       \
+          }                                                                                                    \
+      }                                                                                                        \
+      const s16x8 vv_ = __builtin_shufflevector(vh_[i & 1][0], vh_[i & 1][1], 0, 1, 2, 3, 4, 5, 6, 7);         \
+      _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                        \
+        o_acc[rt][md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv_), pf_[rt],      \
+                                                                o_acc[rt][md], 0, 0, 0);                       \
     }                                                                                                          \
   }
     // One key block j (S^T already in CUR): fetch ahead, start the next block's S^T into NXT (its MFMAs
@@ -296,7 +361,7 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
   }
 
     __syncthreads();                 // the rings are free (previous run finished reading them)
-    f32x16 st_a[2], st_b[2];
+    f32x16 st_a[RT][2], st_b[RT][2];
     if (n_blocks > 0) {
       VLC_ATT_ISSUE_K(kb_first, 0)
       VLC_ATT_ISSUE_V(kb_first, 0)
@@ -322,39 +387,40 @@ __global__ __launch_bounds__(256, 2) void attention_bf16_kernel(
     seg_begin = seg_end;
   }
 
-  // ---- normalise and store: lane holds d = 32*md + 8*(j/4) + 4*x + j%4 of its virtual row ------
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (SPLIT) {
-    if (vr_ok) {
-      const int64_t rh = ((int64_t)blockIdx.z * n + (row0 + r_local)) * Hq + head;
+  // ---- normalise and store: lane holds d = 32*md + 8*(j/4) + 4*x + j%4 of its virtual rows ------
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const float l_tot = l_run[rt] + __shfl_xor(l_run[rt], 32);
+    if (!vr_ok[rt]) continue;
+    if (SPLIT) {
+      const int64_t rh = ((int64_t)blockIdx.z * n + (row0 + r_local[rt])) * Hq + head[rt];
       float* po = part_o + rh * ATT_D;
 #pragma unroll
       for (int md = 0; md < ATT_D / 32; ++md)
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd)
           *reinterpret_cast<float4*>(po + 32 * md + 8 * qd + 4 * x) =
-              make_float4(o_acc[md][4 * qd], o_acc[md][4 * qd + 1], o_acc[md][4 * qd + 2], o_acc[md][4 * qd + 3]);
+              make_float4(o_acc[rt][md][4 * qd], o_acc[rt][md][4 * qd + 1], o_acc[rt][md][4 * qd + 2],
+                          o_acc[rt][md][4 * qd + 3]);
       if (x == 0) {
-        part_ml[2 * rh] = m_run;
+        part_ml[2 * rh] = m_run[rt];
         part_ml[2 * rh + 1] = l_tot;
       }
+    } else {
+      const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+      uint16_t* op = out + ((int64_t)(row0 + r_local[rt]) * Hq + head[rt]) * ATT_D;
+#pragma unroll
+      for (int md = 0; md < ATT_D / 32; ++md)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          f32x2 a0 = {o_acc[rt][md][4 * qd] * inv, o_acc[rt][md][4 * qd + 1] * inv};
+          f32x2 a1 = {o_acc[rt][md][4 * qd + 2] * inv, o_acc[rt][md][4 * qd + 3] * inv};
+          u32x2 w;
+          w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a0, bf16x2));
+          w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a1, bf16x2));
+          *reinterpret_cast<u32x2*>(op + 32 * md + 8 * qd + 4 * x) = w;
+        }
     }
-    return;
-  }
-  if (vr_ok) {
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    uint16_t* op = out + ((int64_t)(row0 + r_local) * Hq + head) * ATT_D;
-#pragma unroll
-    for (int md = 0; md < ATT_D / 32; ++md)
-#pragma unroll
-      for (int qd = 0; qd < 4; ++qd) {
-        f32x2 a0 = {o_acc[md][4 * qd] * inv, o_acc[md][4 * qd + 1] * inv};
-        f32x2 a1 = {o_acc[md][4 * qd + 2] * inv, o_acc[md][4 * qd + 3] * inv};
-        u32x2 w;
-        w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a0, bf16x2));
-        w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a1, bf16x2));
-        *reinterpret_cast<u32x2*>(op + 32 * md + 8 * qd + 4 * x) = w;
-      }
   }
 }
 
@@ -481,13 +547,16 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
     if (D != ATT_D) return fail(VLC_ERR_SHAPE, "attention(bf16): D=%d unsupported (128 only)", D);
     if (g > VR) return fail(VLC_ERR_SHAPE, "attention(bf16): Hq/Hkv=%d exceeds %d", g, VR);
     if (q_stride % 8) return fail(VLC_ERR_SHAPE, "attention(bf16): q row stride must be a multiple of 8");
-    const int rows_per_tile = VR / g;
+    // Many rows: 256 virtual rows per workgroup (two row tiles per wavefront, one workgroup per
+    // CU).  Few rows: 128 virtual rows, two workgroups per CU, so that more workgroups exist.
+    const bool wide = false;   // (two row tiles per wavefront: register allocation not yet clean)
+    const int rows_per_tile = (wide ? 2 * VR : VR) / g;
     const int64_t tiles = (n + rows_per_tile - 1) / rows_per_tile;
     // Few workgroups (512 are resident at once, two per CU): the key loop of the longest rows is the
     // critical path, so split the key range over up to 1024 workgroups, keeping at least 8 key blocks
     // per share (shorter shares cost more in partials and merging than they save).
     int nsplit = 1;
-    if (ws && tiles * Hkv < 512) {
+    if (!wide && ws && tiles * Hkv < 512) {
       nsplit = (int)(1024 / (tiles * Hkv));
       if (nsplit > 8) nsplit = 8;
       if (max_kv_len > 0) {
@@ -500,7 +569,7 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
       float* part_o = static_cast<float*>(ws);
       float* part_ml = part_o + (int64_t)nsplit * n * Hq * ATT_D;
       const dim3 grid((unsigned)tiles, (unsigned)Hkv, (unsigned)nsplit);
-      hipLaunchKernelGGL(attention_bf16_kernel<true>, grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
+      hipLaunchKernelGGL((attention_bf16_kernel<true, 1>), grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
                          (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
                          Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, nsplit, part_o,
                          part_ml);
@@ -512,10 +581,16 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
       return VLC_OK;
     }
     const dim3 grid((unsigned)tiles, (unsigned)Hkv);
-    hipLaunchKernelGGL(attention_bf16_kernel<false>, grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
-                       (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
-                       Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, 1, nullptr,
-                       nullptr);
+    if (wide)
+      hipLaunchKernelGGL((attention_bf16_kernel<false, 2>), grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
+                         (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
+                         Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, 1, nullptr,
+                         nullptr);
+    else
+      hipLaunchKernelGGL((attention_bf16_kernel<false, 1>), grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
+                         (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
+                         Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, 1, nullptr,
+                         nullptr);
     VLC_CHECK_LAUNCH("attention_bf16");
     return VLC_OK;
   }
