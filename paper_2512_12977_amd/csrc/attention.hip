@@ -75,6 +75,18 @@ __device__ __forceinline__ void dma16(const void* gptr, u32x4* lds_dst) {
                : "memory");
 }
 
+// max / sum over the two lanes (l, l ^ 32) that share a virtual row, in both of them: the swap puts
+// the upper half's values beside the lower half's without an LDS round trip (a ds_bpermute here
+// would also make the wavefront wait for every fragment read in flight)
+__device__ __forceinline__ float pair_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 #define VLC_ATT_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8) | (0 << 14))
 
 // SPLIT: blockIdx.z handles every nsplit-th share of each run's key blocks and leaves an
@@ -278,7 +290,7 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
       float mx_ = -INFINITY;                                                                                   \
       _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                         \
         _Pragma("unroll") for (int j = 0; j < 16; ++j) mx_ = fmaxf(mx_, ST[rt][mt][j]);                        \
-      mx_ = fmaxf(mx_, __shfl_xor(mx_, 32)) * scale_log2;   /* scale > 0: max commutes with it */              \
+      mx_ = pair_max(mx_) * scale_log2;   /* scale > 0: max commutes with it */                                \
       const float m_new_ = fmaxf(m_run[rt], mx_);                                                              \
       const float m_use_ = (m_new_ == -INFINITY) ? 0.f : m_new_;                                               \
       alpha_[rt] = __builtin_amdgcn_exp2f(m_run[rt] - m_use_);   /* m_run = -inf -> 0 */                       \
@@ -390,7 +402,7 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
   // ---- normalise and store: lane holds d = 32*md + 8*(j/4) + 4*x + j%4 of its virtual rows ------
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    const float l_tot = l_run[rt] + __shfl_xor(l_run[rt], 32);
+    const float l_tot = pair_sum(l_run[rt]);
     if (!vr_ok[rt]) continue;
     if (SPLIT) {
       const int64_t rh = ((int64_t)blockIdx.z * n + (row0 + r_local[rt])) * Hq + head[rt];
