@@ -26,7 +26,8 @@ Readings of points the paper leaves open are marked "reading:" where they apply.
 Pins (tests/test_oracle_*.py): rate 1.0 equals full prefill; exact-prefix reuse at
 rate 0 equals full prefill; the same with every position shifted by a constant;
 rope_shift(d) o rope_shift(-d) = id and composition with direct RoPE; brute-force
-dense attention on tiny inputs; planner closed forms and exhaustive optimum.
+dense attention on tiny inputs; planner closed forms and exhaustive optimum; the first-token
+head against a Hugging Face Qwen2 causal LM with the same weights, and closed forms.
 Parity unpinned: agreement with the authors' own rate lists / prototype numerics
 (their code and tables are not available).
 """
@@ -354,3 +355,28 @@ def full_prefill(shape, weights, emb, request, store):
         h, K, V = layer_forward(shape, W, h, slots, request.pos_start + slots, K, V, store)
         out.append({"slots": slots, "h": h, "K": K, "V": V})
     return out
+
+
+# ----------------------------------------------------------------------------------------------
+# first output token (what the paper's time-to-first-token ends with; Sec. 5.1 "TTFT", Tables 2-5)
+# ----------------------------------------------------------------------------------------------
+def first_token_logits(shape, Wh, h_last, store):
+    """Output scores of the rows h_last [m, H] of the last layer (one row per request: its last slot).
+
+    reading: the paper measures time to the first token but does not describe the output stage;
+    the Qwen decoders it evaluates end with a final RMSNorm (weight Wh["w_norm_f"]) followed by the
+    output matrix Wh["w_lm"] [vocab, H] without bias, and that is what is computed here.  The normed
+    row is rounded to the storage type, the scores are not.
+    """
+    w_norm = store(Wh["w_norm_f"])
+    w_lm = store(Wh["w_lm"])
+    xn = store(rmsnorm(store(h_last), w_norm, shape.eps))
+    return linear(xn, w_lm)
+
+
+def first_token(logits):
+    """Greedy choice: index of the largest score of every row; of equal scores the lowest index.
+
+    reading: the first token is taken greedily (the paper reports latency, not a sampling rule).
+    """
+    return np.argmax(np.asarray(logits, dtype=np.float64), axis=-1).astype(np.int64)

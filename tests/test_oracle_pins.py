@@ -189,6 +189,27 @@ def test_attention_special_cases():
 # ------------------------------------------------------------------------------------------
 # decoder layer: full prefill equals the Qwen2 decoder layer of the `transformers` library
 # ------------------------------------------------------------------------------------------
+def load_qwen2_layer(layer, shape, W, bias):
+    """Copy one layer of vlc_synth weights into a `transformers` Qwen2DecoderLayer (float64)."""
+    Hq, Hkv, D = shape.Hq, shape.Hkv, shape.D
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    wq, wk, wv = np.split(W["w_qkv"], [Hq * D, (Hq + Hkv) * D], axis=0)
+    layer.self_attn.q_proj.weight.copy_(t(wq))
+    layer.self_attn.k_proj.weight.copy_(t(wk))
+    layer.self_attn.v_proj.weight.copy_(t(wv))
+    b = W["b_qkv"] if bias else np.zeros(shape.n_qkv)
+    bq, bk, bv = np.split(b, [Hq * D, (Hq + Hkv) * D])
+    layer.self_attn.q_proj.bias.copy_(t(bq))
+    layer.self_attn.k_proj.bias.copy_(t(bk))
+    layer.self_attn.v_proj.bias.copy_(t(bv))
+    layer.self_attn.o_proj.weight.copy_(t(W["w_o"]))
+    layer.mlp.gate_proj.weight.copy_(t(W["w_gate_up"][:shape.I]))
+    layer.mlp.up_proj.weight.copy_(t(W["w_gate_up"][shape.I:]))
+    layer.mlp.down_proj.weight.copy_(t(W["w_down"]))
+    layer.input_layernorm.weight.copy_(t(W["w_ln1"]))
+    layer.post_attention_layernorm.weight.copy_(t(W["w_ln2"]))
+
+
 @pytest.mark.parametrize("bias", [False, True])
 def test_full_prefill_layer_vs_transformers_qwen2(bias):
     """The paper evaluates on Qwen-VL decoders and leaves layer details to that family; the
@@ -206,24 +227,9 @@ def test_full_prefill_layer_vs_transformers_qwen2(bias):
                       rms_norm_eps=shape.eps, vocab_size=8, max_position_embeddings=4096)
     cfg._attn_implementation = "eager"
     layer = Qwen2DecoderLayer(cfg, 0).double()
-    Hq, Hkv, D = shape.Hq, shape.Hkv, shape.D
     t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
     with torch.no_grad():
-        wq, wk, wv = np.split(W["w_qkv"], [Hq * D, (Hq + Hkv) * D], axis=0)
-        layer.self_attn.q_proj.weight.copy_(t(wq))
-        layer.self_attn.k_proj.weight.copy_(t(wk))
-        layer.self_attn.v_proj.weight.copy_(t(wv))
-        b = W["b_qkv"] if bias else np.zeros(shape.n_qkv)
-        bq, bk, bv = np.split(b, [Hq * D, (Hq + Hkv) * D])
-        layer.self_attn.q_proj.bias.copy_(t(bq))
-        layer.self_attn.k_proj.bias.copy_(t(bk))
-        layer.self_attn.v_proj.bias.copy_(t(bv))
-        layer.self_attn.o_proj.weight.copy_(t(W["w_o"]))
-        layer.mlp.gate_proj.weight.copy_(t(W["w_gate_up"][:shape.I]))
-        layer.mlp.up_proj.weight.copy_(t(W["w_gate_up"][shape.I:]))
-        layer.mlp.down_proj.weight.copy_(t(W["w_down"]))
-        layer.input_layernorm.weight.copy_(t(W["w_ln1"]))
-        layer.post_attention_layernorm.weight.copy_(t(W["w_ln2"]))
+        load_qwen2_layer(layer, shape, W, bias)
         x = t(emb)[None]
         pos = torch.arange(5, 5 + S)[None]
         cos, sin = Qwen2RotaryEmbedding(cfg)(x, pos)
@@ -235,6 +241,80 @@ def test_full_prefill_layer_vs_transformers_qwen2(bias):
     got = orc.full_prefill(shape, [W], emb, req, orc.store_exact)[0]["h"]
     # the library builds cos/sin in float32, hence 1e-6 rather than 1e-12
     np.testing.assert_allclose(got, ref, atol=2e-6, rtol=0)
+
+
+# ------------------------------------------------------------------------------------------
+# first output token: final norm + output matrix + greedy choice
+# ------------------------------------------------------------------------------------------
+def test_first_token_vs_transformers_qwen2_causal_lm():
+    """Whole stack: two oracle layers of full prefill, then the first-token head, against the
+    library's Qwen2ForCausalLM with the same weights (scores of the last position, fp64)."""
+    from transformers import Qwen2Config, Qwen2ForCausalLM
+
+    shape = syn.SHAPES["tiny_bias"]
+    Ws = [syn.layer_weights(shape, 21, l) for l in range(shape.L)]
+    Wh = syn.head_weights(shape, 21)
+    S = 29
+    emb = np.random.default_rng(22).standard_normal((S, shape.H))
+    cfg = Qwen2Config(hidden_size=shape.H, num_attention_heads=shape.Hq, num_key_value_heads=shape.Hkv,
+                      intermediate_size=shape.I, num_hidden_layers=shape.L, rope_theta=shape.rope_base,
+                      rms_norm_eps=shape.eps, vocab_size=shape.vocab, max_position_embeddings=4096,
+                      tie_word_embeddings=False)
+    cfg._attn_implementation = "eager"
+    model = Qwen2ForCausalLM(cfg).double().eval()
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    with torch.no_grad():
+        for l in range(shape.L):
+            load_qwen2_layer(model.model.layers[l], shape, Ws[l], True)
+        model.model.norm.weight.copy_(t(Wh["w_norm_f"]))
+        model.lm_head.weight.copy_(t(Wh["w_lm"]))
+        ref = model(inputs_embeds=t(emb)[None], position_ids=torch.arange(S)[None]).logits[0, -1].numpy()
+    req = syn.Request([syn.Segment(0, S, False)], 0)
+    h = orc.full_prefill(shape, Ws, emb, req, orc.store_exact)[-1]["h"]
+    got = orc.first_token_logits(shape, Wh, h[-1:], orc.store_exact)[0]
+    assert got.shape == (shape.vocab,)
+    np.testing.assert_allclose(got, ref, atol=5e-6, rtol=0)     # the library's cos/sin are float32
+    assert orc.first_token(got[None])[0] == int(np.argmax(ref))
+
+
+def test_first_token_head_closed_forms():
+    shape = syn.SHAPES["tiny"]
+    H = shape.H
+    rng = np.random.default_rng(23)
+    x = rng.standard_normal((3, H))
+    # unit norm weight, output matrix = signed unit rows: score v is +-x[v] / rms(x)
+    Wh = {"w_norm_f": np.ones(H), "w_lm": np.concatenate([np.eye(H), -np.eye(H)])}
+    lg = orc.first_token_logits(shape, Wh, x, orc.store_exact)
+    rms = np.sqrt(np.mean(x * x, axis=1, keepdims=True) + shape.eps)
+    np.testing.assert_allclose(lg[:, :H], x / rms, atol=1e-13)
+    np.testing.assert_allclose(lg[:, H:], -x / rms, atol=1e-13)
+    tok = orc.first_token(lg)
+    j = np.argmax(np.abs(x), axis=1)
+    want = np.where(x[np.arange(3), j] > 0, j, j + H)
+    np.testing.assert_array_equal(tok, want)
+    # the norm weight scales column-wise before the product (not after)
+    w = rng.uniform(0.5, 2.0, H)
+    Wh2 = {"w_norm_f": w, "w_lm": rng.standard_normal((7, H))}
+    lg2 = orc.first_token_logits(shape, Wh2, x, orc.store_exact)
+    np.testing.assert_allclose(lg2, ((x / rms) * w) @ Wh2["w_lm"].T, atol=1e-12)
+    # scaling a row leaves its scores unchanged up to eps (RMSNorm), so it keeps its token
+    lg3 = orc.first_token_logits(shape, Wh2, 3.0 * x, orc.store_exact)
+    np.testing.assert_allclose(lg3, lg2, rtol=2e-6, atol=1e-9)
+
+
+def test_first_token_ties_take_lowest_index():
+    lg = np.array([[0.0, 2.0, 2.0, -1.0], [5.0, 5.0, 5.0, 5.0], [-3.0, -2.0, -2.0, -2.0]])
+    np.testing.assert_array_equal(orc.first_token(lg), [1, 0, 1])
+
+
+def test_first_token_bf16_contract_rounds_inputs_not_scores():
+    shape = syn.SHAPES["tiny_bf16"]
+    Wh = syn.head_weights(shape, 24)
+    x = np.random.default_rng(25).standard_normal((2, shape.H))
+    lg = orc.first_token_logits(shape, Wh, x, orc.store_bf16)
+    xn = orc.store_bf16(orc.rmsnorm(orc.store_bf16(x), orc.store_bf16(Wh["w_norm_f"]), shape.eps))
+    np.testing.assert_array_equal(lg, xn @ orc.store_bf16(Wh["w_lm"]).T)
+    assert np.any(lg != orc.store_bf16(lg))          # scores themselves stay unrounded
 
 
 # ------------------------------------------------------------------------------------------

@@ -30,6 +30,7 @@ class Shape:
     dtype: str        # "f32" | "bf16"  (storage type of the GPU path)
     qkv_bias: bool
     eps: float = 1e-6
+    vocab: int = 512  # rows of the output (LM head) matrix
 
     @property
     def g(self) -> int:
@@ -48,9 +49,9 @@ SHAPES: Dict[str, Shape] = {
     "tiny_bf16": Shape("tiny_bf16", L=2, H=256, Hq=4, Hkv=2, D=128, I=512, rope_base=1e4,
                        dtype="bf16", qkv_bias=True),
     "7b": Shape("7b", L=28, H=3584, Hq=28, Hkv=4, D=128, I=18944, rope_base=1e6,
-                dtype="bf16", qkv_bias=True),
+                dtype="bf16", qkv_bias=True, vocab=152064),
     "72b": Shape("72b", L=80, H=8192, Hq=64, Hkv=8, D=128, I=29568, rope_base=1e6,
-                 dtype="bf16", qkv_bias=True),
+                 dtype="bf16", qkv_bias=True, vocab=152064),
 }
 
 
@@ -223,6 +224,13 @@ def layer_weights(shape: Shape, seed: int, layer: int) -> Dict[str, Optional[np.
             w += np.float32(1.0)
         out[nm] = w
     return out
+
+
+def head_weights(shape: Shape, seed: int) -> Dict[str, np.ndarray]:
+    """Final norm weight [H] (1 + N(0, 0.02^2)) and output matrix [vocab, H] (N(0, 0.02^2)), float32."""
+    w_norm = normal_f32([seed, 3000, 0], shape.H, 0.02) + np.float32(1.0)
+    w_lm = normal_f32([seed, 3000, 1], shape.vocab * shape.H, 0.02).reshape(shape.vocab, shape.H)
+    return {"w_norm_f": w_norm, "w_lm": w_lm}
 
 
 def embedding_rows(wl: Workload) -> np.ndarray:
