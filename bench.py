@@ -123,6 +123,7 @@ def main() -> int:
                     help="layers whose weights/caches come from the seeded host generator (rest: device RNG)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full", action="store_true", help="skip the full-recompute comparison")
+    ap.add_argument("--no-first-token", action="store_true", help="skip the first-token head timing")
     ap.add_argument("--cpu-layers", type=int, default=None, help="layers of the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain row copy of 1 GiB through vlc_gather_rows "
@@ -297,6 +298,45 @@ def main() -> int:
     except Exception:
         pass
 
+    # ---- first output token of every request (final norm + output matrix + greedy choice) ---------
+    # Not part of `value` (the metric is the per-layer path); reported beside it as the tail that
+    # turns the prefill latency into a time-to-first-token-like figure.  Head weights: device RNG.
+    first_tok = None
+    if not args.no_first_token:
+        vocab = sh.vocab
+        w_norm_f = (1.0 + 0.02 * torch.randn(sh.H, generator=gen, device=dev)).to(dt)
+        w_out = torch.empty((vocab, sh.H), device=dev, dtype=dt)
+        for v0 in range(0, vocab, 16384):      # in slabs: the float32 staging copy stays small
+            w_out[v0:v0 + 16384] = (0.02 * torch.randn((min(16384, vocab - v0), sh.H), generator=gen, device=dev)).to(dt)
+        # row of each request's last slot inside the last layer's output (rows are slot-ordered per request)
+        kvs = plans.host["kv_start"][L - 1, :plans.n_rows[L - 1]]
+        last_rows = np.asarray([int(np.flatnonzero(kvs == rq.kv_start)[-1]) for rq in wl.requests])
+        d_rows = torch.from_numpy(last_rows.astype(np.int32)).to(dev)
+        n_rq = len(last_rows)
+        logits = torch.empty((n_rq, vocab), device=dev, dtype=torch.float32)
+        token = torch.empty((n_rq,), device=dev, dtype=torch.int32)
+        code = vlc.VLC_BF16 if sh.dtype == "bf16" else vlc.VLC_F32
+        ws_ft = torch.empty(max(256, vlc.vlc_first_token_workspace_bytes(sh.H, n_rq, code)), device=dev, dtype=torch.uint8)
+        h_last = hbuf[(L - 1) & 1]
+        for _ in range(3):
+            vlc.vlc_first_token(h_last, d_rows, sh.eps, w_norm_f, w_out, logits, token, ws_ft)
+        torch.cuda.synchronize()
+        reps = 20
+        e3 = hev.create(2)
+        hev.record(e3[0], stream)
+        for _ in range(reps):
+            vlc.vlc_first_token(h_last, d_rows, sh.eps, w_norm_f, w_out, logits, token, ws_ft)
+        hev.record(e3[1], stream)
+        torch.cuda.synchronize()
+        ft_us = hev.elapsed_ms(e3[0], e3[1]) / reps * 1e3
+        hev.destroy(e3)
+        ft_bytes = vocab * sh.H * (2 if sh.dtype == "bf16" else 4) + n_rq * vocab * 4 * 2
+        first_tok = {"avg_us": round(ft_us, 2), "requests": n_rq, "vocab": vocab,
+                     "gbs": round(ft_bytes / (ft_us * 1e-6) / 1e9, 1),
+                     "frac_of_hbm_peak": round(ft_bytes / (ft_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4),
+                     "bound": "hbm (the output matrix is read once)"}
+        del w_out, logits
+
     # ---- full recompute through the same kernels ---------------------------------------------------
     full_ms = None
     if full:
@@ -372,6 +412,8 @@ def main() -> int:
         "tokens_per_s_per_layer": {"min": round(float(per_layer_tps.min()), 1),
                                    "median": round(float(np.median(per_layer_tps)), 1),
                                    "max": round(float(per_layer_tps.max()), 1)},
+        "first_token": first_tok,
+        "ttft_like_ms": None if first_tok is None else round(ms_per_step + first_tok["avg_us"] * 1e-3, 4),
         "roofline": roofline,
         "stages": stages,
         "stages_source": "separate untimed pass with all stage events (3 steps); the timed steps record only the two events around the dominant stage of each layer",

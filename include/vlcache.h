@@ -263,6 +263,27 @@ int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_layer_weight
                             void* v_cache, void* workspace, int64_t workspace_bytes, void* stream,
                             void* const* stage_events);
 
+/*
+ * First output token of each request - where the paper's time-to-first-token ends (Sec. 5.1; Tables
+ * 2-5 report TTFT).  The paper does not describe the output stage; as in the Qwen decoders it
+ * evaluates, row rows[r] of the last layer's output h [n, H] (the request's last slot, a text token
+ * and therefore always recomputed) goes through the final RMSNorm (weight w_norm [H], eps) and the
+ * output matrix w_out [vocab, H] (row-major, no bias):
+ *   logits[r, v] = sum_c RMSNorm(h[rows[r]])[c] * w_out[v, c]     float, not rounded
+ *   token[r]     = index of the largest logits[r, :], the lowest index among equal ones
+ * The normed row is rounded to `dtype` before the product (storage contract of the layer).
+ * All pointers are device memory: h, w_norm, w_out of `dtype`; rows int32 [n_req] with values in
+ * [0, n) (not checked); logits float [n_req, vocab]; token int32 [n_req]; workspace of at least
+ * vlc_first_token_workspace_bytes(H, n_req, dtype) bytes, 256-byte aligned, caller-owned like every
+ * buffer.  Requirements: H a multiple of 64, vocab a multiple of 4, n_req >= 0 (0: no-op).
+ * Errors: VLC_ERR_NULL, VLC_ERR_SHAPE, VLC_ERR_DTYPE, VLC_ERR_WORKSPACE, VLC_ERR_HIP (launch failure).
+ * Enqueues three kernels on `stream` and returns without synchronising.
+ */
+int64_t vlc_first_token_workspace_bytes(int H, int64_t n_req, int dtype);
+int vlc_first_token(const void* h, const int32_t* rows, int64_t n_req, int H, int64_t vocab, float eps,
+                    const void* w_norm, const void* w_out, float* logits, int32_t* token, void* workspace,
+                    int64_t workspace_bytes, int dtype, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

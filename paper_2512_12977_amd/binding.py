@@ -68,6 +68,10 @@ def lib():
         L.vlc_layer_workspace_layout.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
         L.vlc_layer_forward.argtypes = [C.c_void_p] * 8 + [C.c_int64, C.c_void_p]
         L.vlc_layer_forward_timed.argtypes = [C.c_void_p] * 8 + [C.c_int64, C.c_void_p, C.c_void_p]
+        L.vlc_first_token_workspace_bytes.restype = C.c_int64
+        L.vlc_first_token_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int]
+        L.vlc_first_token.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int64, C.c_float] + \
+                                     [C.c_void_p] * 5 + [C.c_int64, C.c_int, C.c_void_p]
         _LIB = L
     return _LIB
 
@@ -230,3 +234,20 @@ def vlc_layer_forward_timed(shape: LayerShape, weights: LayerWeights, plan: Laye
                                          _dev(h_in), _dev(h_out), _dev(k_cache), _dev(v_cache), _dev(workspace),
                                          workspace.numel() * workspace.element_size(), _stream(stream),
                                          C.addressof(stage_events)))
+
+
+def vlc_first_token_workspace_bytes(H: int, n_req: int, dtype_code: int) -> int:
+    b = lib().vlc_first_token_workspace_bytes(int(H), int(n_req), int(dtype_code))
+    if b == 0 and n_req > 0:
+        raise VlcError(2, last_error())
+    return int(b)
+
+
+def vlc_first_token(h, rows, eps: float, w_norm, w_out, logits, token, workspace, stream=None) -> None:
+    """h [n, H]; rows int32 [n_req]; w_out [vocab, H]; logits float32 [n_req, vocab]; token int32 [n_req]."""
+    n_req = rows.numel()
+    H = h.shape[-1]
+    vocab = w_out.shape[0]
+    _check(lib().vlc_first_token(_dev(h), _dev(rows), n_req, H, vocab, float(eps), _dev(w_norm), _dev(w_out),
+                                 _dev(logits), _dev(token), _dev(workspace),
+                                 workspace.numel() * workspace.element_size(), _dtype_code(h), _stream(stream)))

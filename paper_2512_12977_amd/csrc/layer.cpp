@@ -200,3 +200,41 @@ extern "C" int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_l
   return layer_forward_impl(shape, w, p, h_in, h_out, k_cache, v_cache, workspace, workspace_bytes, stream,
                             stage_events);
 }
+
+// ---------------------------------------------------------------------------------------------
+// first output token: final RMSNorm of one row per request, output matrix, greedy choice
+// ---------------------------------------------------------------------------------------------
+extern "C" int64_t vlc_first_token_workspace_bytes(int H, int64_t n_req, int dtype) {
+  if (H <= 0 || n_req < 0 || (dtype != VLC_F32 && dtype != VLC_BF16)) {
+    fail(VLC_ERR_SHAPE, "vlc_first_token_workspace_bytes: H=%d n_req=%lld dtype=%d", H, (long long)n_req, dtype);
+    return 0;
+  }
+  return align256(n_req * (int64_t)H * (dtype == VLC_BF16 ? 2 : 4));   // the normed rows
+}
+
+extern "C" int vlc_first_token(const void* h, const int32_t* rows, int64_t n_req, int H, int64_t vocab,
+                               float eps, const void* w_norm, const void* w_out, float* logits,
+                               int32_t* token, void* workspace, int64_t workspace_bytes, int dtype,
+                               void* stream) {
+  const char* who = "vlc_first_token";
+  if (dtype != VLC_F32 && dtype != VLC_BF16) return fail(VLC_ERR_DTYPE, "%s: dtype=%d", who, dtype);
+  if (n_req < 0 || H <= 0 || H % 64 || vocab <= 0 || vocab % 4 || !(eps >= 0.f))
+    return fail(VLC_ERR_SHAPE, "%s: n_req=%lld H=%d vocab=%lld (H multiple of 64, vocab multiple of 4)", who,
+                (long long)n_req, H, (long long)vocab);
+  if (n_req == 0) return VLC_OK;
+  if (!h || !rows || !w_norm || !w_out || !logits || !token) return fail(VLC_ERR_NULL, "%s: NULL pointer", who);
+  const int64_t need = vlc_first_token_workspace_bytes(H, n_req, dtype);
+  if (!workspace || workspace_bytes < need)
+    return fail(VLC_ERR_WORKSPACE, "%s: workspace of %lld bytes, %lld needed", who, (long long)workspace_bytes,
+                (long long)need);
+  if ((uintptr_t)workspace & 255) return fail(VLC_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned", who);
+  hipStream_t st = (hipStream_t)stream;
+  int rc = vlc::launch_rmsnorm(h, rows, w_norm, workspace, n_req, H, eps, dtype, st);
+  if (rc) return rc;
+  // The output matrix is streamed once (vocab * H elements); with a handful of rows this GEMM is
+  // bound by reading it, and the 128-row MFMA tile (mostly padding) costs about as much time.
+  rc = vlc::launch_gemm(workspace, H, w_out, logits, vocab, n_req, vocab, H, vlc::EPI_BIAS_F32, nullptr, nullptr, 0,
+                        nullptr, dtype, nullptr, 0, st);
+  if (rc) return rc;
+  return vlc::launch_argmax_rows(logits, n_req, vocab, token, st);
+}

@@ -395,6 +395,35 @@ __global__ __launch_bounds__(kThreads) void sum_residual_rmsnorm_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Greedy choice: index of the largest score of a row, the lowest index among equal scores.  One
+// workgroup per row; NaNs never win.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void argmax_rows_kernel(const float* __restrict__ x, int64_t cols,
+                                                               int32_t* __restrict__ out) {
+  const float* r = x + (int64_t)blockIdx.x * cols;
+  float best = -INFINITY;
+  int64_t bi = cols;                                   // "none yet": larger than every real index
+  for (int64_t c = threadIdx.x; c < cols; c += kThreads) {
+    const float v = r[c];
+    if (v > best || (v == best && c < bi)) { best = v; bi = c; }
+  }
+  __shared__ float sv[kThreads];
+  __shared__ int64_t si[kThreads];
+  sv[threadIdx.x] = best;
+  si[threadIdx.x] = bi;
+  __syncthreads();
+  for (int o = kThreads / 2; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) {
+      const float v = sv[threadIdx.x + o];
+      const int64_t c = si[threadIdx.x + o];
+      if (v > sv[threadIdx.x] || (v == sv[threadIdx.x] && c < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = c; }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = si[0] < cols ? (int32_t)si[0] : 0;   // all NaN / -inf: index 0
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -520,6 +549,14 @@ int launch_sum_residual_rmsnorm(const float* partials, int splits, const void* r
   else return fail(VLC_ERR_SHAPE, "sum+residual+rmsnorm: H=%d too large", H);
 #undef VLC_LAUNCH_SRN
   VLC_CHECK_LAUNCH("sum_residual_rmsnorm");
+  return VLC_OK;
+}
+
+int launch_argmax_rows(const float* x, int64_t rows, int64_t cols, int32_t* out, hipStream_t st) {
+  if (rows <= 0) return VLC_OK;
+  if (cols <= 0 || cols > INT32_MAX) return fail(VLC_ERR_SHAPE, "argmax: cols=%lld", (long long)cols);
+  hipLaunchKernelGGL(argmax_rows_kernel, dim3((unsigned)rows), dim3(kThreads), 0, st, x, cols, out);
+  VLC_CHECK_LAUNCH("argmax_rows");
   return VLC_OK;
 }
 

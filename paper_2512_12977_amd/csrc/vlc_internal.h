@@ -51,6 +51,9 @@ int launch_sum_residual_rmsnorm(const float* partials, int splits, const void* r
                                 const void* w, void* h, void* y, int64_t n, int H, float eps,
                                 hipStream_t st);
 
+// out[r] = index of the largest x[r, :] (lowest index among equals); x float [rows, cols]
+int launch_argmax_rows(const float* x, int64_t rows, int64_t cols, int32_t* out, hipStream_t st);
+
 int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
                       const int32_t* src_row, const int32_t* dst_row, const int32_t* delta,
                       int64_t n_tok, int Hkv, int D, const RopeFreq& f, int dtype, hipStream_t st);
