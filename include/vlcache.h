@@ -277,7 +277,7 @@ int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_layer_weight
  * vlc_first_token_workspace_bytes(H, n_req, dtype) bytes, 256-byte aligned, caller-owned like every
  * buffer.  Requirements: H a multiple of 64, vocab a multiple of 4, n_req >= 0 (0: no-op).
  * Errors: VLC_ERR_NULL, VLC_ERR_SHAPE, VLC_ERR_DTYPE, VLC_ERR_WORKSPACE, VLC_ERR_HIP (launch failure).
- * Enqueues three kernels on `stream` and returns without synchronising.
+ * Enqueues four kernels on `stream` and returns without synchronising.
  */
 int64_t vlc_first_token_workspace_bytes(int H, int64_t n_req, int dtype);
 int vlc_first_token(const void* h, const int32_t* rows, int64_t n_req, int H, int64_t vocab, float eps,

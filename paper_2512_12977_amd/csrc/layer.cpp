@@ -209,7 +209,8 @@ extern "C" int64_t vlc_first_token_workspace_bytes(int H, int64_t n_req, int dty
     fail(VLC_ERR_SHAPE, "vlc_first_token_workspace_bytes: H=%d n_req=%lld dtype=%d", H, (long long)n_req, dtype);
     return 0;
   }
-  return align256(n_req * (int64_t)H * (dtype == VLC_BF16 ? 2 : 4));   // the normed rows
+  return align256(n_req * (int64_t)H * (dtype == VLC_BF16 ? 2 : 4)) +   // the normed rows
+         align256(vlc::argmax_ws_bytes(n_req));                           // partial choices
 }
 
 extern "C" int vlc_first_token(const void* h, const int32_t* rows, int64_t n_req, int H, int64_t vocab,
@@ -231,10 +232,14 @@ extern "C" int vlc_first_token(const void* h, const int32_t* rows, int64_t n_req
   hipStream_t st = (hipStream_t)stream;
   int rc = vlc::launch_rmsnorm(h, rows, w_norm, workspace, n_req, H, eps, dtype, st);
   if (rc) return rc;
-  // The output matrix is streamed once (vocab * H elements); with a handful of rows this GEMM is
-  // bound by reading it, and the 128-row MFMA tile (mostly padding) costs about as much time.
-  rc = vlc::launch_gemm(workspace, H, w_out, logits, vocab, n_req, vocab, H, vlc::EPI_BIAS_F32, nullptr, nullptr, 0,
-                        nullptr, dtype, nullptr, 0, st);
+  // The output matrix is streamed once (vocab * H elements).  Up to 8 requests (bf16): a kernel that
+  // does exactly that, one matrix row per wavefront pass.  Otherwise the GEMM (128-row MFMA tiles).
+  if (dtype == VLC_BF16 && n_req <= 8 && (int64_t)n_req * H * 2 <= 159 * 1024)
+    rc = vlc::launch_rows_times_matrix_bf16(workspace, w_out, logits, n_req, vocab, H, st);
+  else
+    rc = vlc::launch_gemm(workspace, H, w_out, logits, vocab, n_req, vocab, H, vlc::EPI_BIAS_F32, nullptr, nullptr, 0,
+                          nullptr, dtype, nullptr, 0, st);
   if (rc) return rc;
-  return vlc::launch_argmax_rows(logits, n_req, vocab, token, st);
+  char* part = static_cast<char*>(workspace) + align256(n_req * (int64_t)H * (dtype == VLC_BF16 ? 2 : 4));
+  return vlc::launch_argmax_rows(logits, n_req, vocab, token, part, st);
 }

@@ -396,32 +396,118 @@ __global__ __launch_bounds__(kThreads) void sum_residual_rmsnorm_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Greedy choice: index of the largest score of a row, the lowest index among equal scores.  One
-// workgroup per row; NaNs never win.
+// Scores of a few rows against a large matrix: out[r, v] = x[r, :] . W[v, :], bf16 inputs, float
+// accumulation (v_dot2c_f32_bf16: two products per instruction, no unpacking).  The matrix is read
+// exactly once, a wavefront streaming one whole row at a time (16 bytes per lane, consecutive
+// lanes consecutive chunks); the m <= MAXM rows of x sit in LDS.  HBM-bound: 2 bytes per matrix
+// element against 2 * m flops.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void argmax_rows_kernel(const float* __restrict__ x, int64_t cols,
-                                                               int32_t* __restrict__ out) {
-  const float* r = x + (int64_t)blockIdx.x * cols;
-  float best = -INFINITY;
-  int64_t bi = cols;                                   // "none yet": larger than every real index
-  for (int64_t c = threadIdx.x; c < cols; c += kThreads) {
-    const float v = r[c];
-    if (v > best || (v == best && c < bi)) { best = v; bi = c; }
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+__device__ __forceinline__ float dot8_bf16(const uint4& a, const uint4& b, float acc) {
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), acc, false);
+  return acc;
+}
+
+constexpr int kGemvThreads = 512;
+
+template <int MAXM>
+__global__ __launch_bounds__(kGemvThreads) void rows_times_matrix_bf16_kernel(
+    const uint4* __restrict__ x, const uint4* __restrict__ W, float* __restrict__ out, int m, int chunks,
+    int64_t V) {
+  extern __shared__ uint4 xs[];                          // [m][chunks]
+  for (int i = threadIdx.x; i < m * chunks; i += kGemvThreads) xs[i] = x[i];
+  __syncthreads();
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * (kGemvThreads / 64) + (threadIdx.x >> 6);
+  const int64_t n_waves = (int64_t)gridDim.x * (kGemvThreads / 64);
+  for (int64_t v = wave; v < V; v += n_waves) {
+    const uint4* wr = W + v * chunks;
+    float acc[MAXM];
+#pragma unroll
+    for (int r = 0; r < MAXM; ++r) acc[r] = 0.f;
+#pragma unroll 4
+    for (int c = lane; c < chunks; c += 64) {
+      const uint4 w = wr[c];
+#pragma unroll
+      for (int r = 0; r < MAXM; ++r)
+        if (r < m) acc[r] = dot8_bf16(w, xs[r * chunks + c], acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < MAXM; ++r) {
+      if (r < m) {                                       // m is uniform: every lane takes part in the exchange
+        float s = acc[r];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+        if (lane == 0) out[(int64_t)r * V + v] = s;
+      }
+    }
   }
-  __shared__ float sv[kThreads];
-  __shared__ int64_t si[kThreads];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Greedy choice: index of the largest score of a row, the lowest index among equal scores; NaNs
+// never win.  Two passes: kArgmaxSlices workgroups per row each scan a slice of the columns (16
+// bytes per lane) and leave their best (value, index); one workgroup per row then picks among those.
+// ---------------------------------------------------------------------------------------------
+constexpr int kArgmaxSlices = 64;
+
+__device__ __forceinline__ void take_better(float v, int64_t c, float& best, int64_t& bi) {
+  if (v > best || (v == best && c < bi)) { best = v; bi = c; }
+}
+
+// best of the whole workgroup in sv[0] / si[0]
+__device__ __forceinline__ void block_best(float best, int64_t bi, float* sv, int64_t* si) {
   sv[threadIdx.x] = best;
   si[threadIdx.x] = bi;
   __syncthreads();
   for (int o = kThreads / 2; o > 0; o >>= 1) {
-    if ((int)threadIdx.x < o) {
-      const float v = sv[threadIdx.x + o];
-      const int64_t c = si[threadIdx.x + o];
-      if (v > sv[threadIdx.x] || (v == sv[threadIdx.x] && c < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = c; }
-    }
+    if ((int)threadIdx.x < o) take_better(sv[threadIdx.x + o], si[threadIdx.x + o], sv[threadIdx.x], si[threadIdx.x]);
     __syncthreads();
   }
-  if (threadIdx.x == 0) out[blockIdx.x] = si[0] < cols ? (int32_t)si[0] : 0;   // all NaN / -inf: index 0
+}
+
+__global__ __launch_bounds__(kThreads) void argmax_slices_kernel(const float* __restrict__ x, int64_t cols,
+                                                                 float* __restrict__ part_v,
+                                                                 int64_t* __restrict__ part_i) {
+  const int64_t row = blockIdx.y;
+  const int64_t quads = cols / 4;                      // cols is a multiple of 4
+  const int64_t per = (quads + kArgmaxSlices - 1) / kArgmaxSlices;
+  const int64_t q0 = blockIdx.x * per, q1 = min(quads, q0 + per);
+  const float4* r = reinterpret_cast<const float4*>(x + row * cols);
+  float best = -INFINITY;
+  int64_t bi = cols;                                   // "none yet": larger than every real index
+  for (int64_t q = q0 + threadIdx.x; q < q1; q += kThreads) {
+    const float4 v = r[q];
+    take_better(v.x, 4 * q, best, bi);
+    take_better(v.y, 4 * q + 1, best, bi);
+    take_better(v.z, 4 * q + 2, best, bi);
+    take_better(v.w, 4 * q + 3, best, bi);
+  }
+  __shared__ float sv[kThreads];
+  __shared__ int64_t si[kThreads];
+  block_best(best, bi, sv, si);
+  if (threadIdx.x == 0) {
+    part_v[row * kArgmaxSlices + blockIdx.x] = sv[0];
+    part_i[row * kArgmaxSlices + blockIdx.x] = si[0];
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void argmax_pick_kernel(const float* __restrict__ part_v,
+                                                               const int64_t* __restrict__ part_i, int64_t cols,
+                                                               int32_t* __restrict__ out) {
+  const int64_t row = blockIdx.x;
+  float best = -INFINITY;
+  int64_t bi = cols;
+  if (threadIdx.x < kArgmaxSlices)
+    take_better(part_v[row * kArgmaxSlices + threadIdx.x], part_i[row * kArgmaxSlices + threadIdx.x], best, bi);
+  __shared__ float sv[kThreads];
+  __shared__ int64_t si[kThreads];
+  block_best(best, bi, sv, si);
+  if (threadIdx.x == 0) out[row] = si[0] < cols ? (int32_t)si[0] : 0;   // all NaN / -inf: index 0
 }
 
 }  // namespace
@@ -552,11 +638,43 @@ int launch_sum_residual_rmsnorm(const float* partials, int splits, const void* r
   return VLC_OK;
 }
 
-int launch_argmax_rows(const float* x, int64_t rows, int64_t cols, int32_t* out, hipStream_t st) {
+int launch_rows_times_matrix_bf16(const void* x, const void* W, float* out, int64_t m, int64_t V, int H,
+                                  hipStream_t st) {
+  if (m <= 0 || V <= 0) return VLC_OK;
+  if (m > 8 || H % 8) return fail(VLC_ERR_SHAPE, "rows x matrix: m=%lld (at most 8), H=%d", (long long)m, H);
+  const int chunks = H / 8;
+  const size_t lds = (size_t)m * chunks * 16;
+  if (lds > 160 * 1024 - 1024) return fail(VLC_ERR_SHAPE, "rows x matrix: %lld rows of %d do not fit LDS", (long long)m, H);
+  // two workgroups per CU where LDS allows, one otherwise; every wavefront loops over its rows
+  const int per_cu = lds <= 79 * 1024 ? 2 : 1;
+  int64_t blocks = 256 * per_cu;
+  const int64_t max_blocks = (V + kGemvThreads / 64 - 1) / (kGemvThreads / 64);
+  if (blocks > max_blocks) blocks = max_blocks;
+  static bool attr_set = false;
+  if (!attr_set) {
+    VLC_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rows_times_matrix_bf16_kernel<8>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(rows_times_matrix_bf16_kernel<8>, dim3((unsigned)blocks), dim3(kGemvThreads), lds, st,
+                     (const uint4*)x, (const uint4*)W, out, (int)m, chunks, V);
+  VLC_CHECK_LAUNCH("rows_times_matrix_bf16");
+  return VLC_OK;
+}
+
+int64_t argmax_ws_bytes(int64_t rows) { return rows * kArgmaxSlices * 16; }
+
+int launch_argmax_rows(const float* x, int64_t rows, int64_t cols, int32_t* out, void* ws, hipStream_t st) {
   if (rows <= 0) return VLC_OK;
-  if (cols <= 0 || cols > INT32_MAX) return fail(VLC_ERR_SHAPE, "argmax: cols=%lld", (long long)cols);
-  hipLaunchKernelGGL(argmax_rows_kernel, dim3((unsigned)rows), dim3(kThreads), 0, st, x, cols, out);
-  VLC_CHECK_LAUNCH("argmax_rows");
+  if (cols <= 0 || cols > INT32_MAX || cols % 4 || rows > 65535)
+    return fail(VLC_ERR_SHAPE, "argmax: rows=%lld cols=%lld (cols a multiple of 4)", (long long)rows, (long long)cols);
+  float* part_v = static_cast<float*>(ws);
+  int64_t* part_i = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + rows * kArgmaxSlices * 8);   // 8-byte aligned
+  hipLaunchKernelGGL(argmax_slices_kernel, dim3(kArgmaxSlices, (unsigned)rows), dim3(kThreads), 0, st, x, cols,
+                     part_v, part_i);
+  VLC_CHECK_LAUNCH("argmax_slices");
+  hipLaunchKernelGGL(argmax_pick_kernel, dim3((unsigned)rows), dim3(kThreads), 0, st, part_v, part_i, cols, out);
+  VLC_CHECK_LAUNCH("argmax_pick");
   return VLC_OK;
 }
 

@@ -63,6 +63,7 @@ def test_first_token_small(name):
     h = np.random.default_rng(32).standard_normal((61, shape.H)).astype(np.float32)
     check(h, [60, 3, 17], Wh, shape)
     check(h, [0], Wh, shape)                                      # a single request
+    check(h, [5, 9, 60, 1, 2, 33, 34, 35, 8, 7, 6], Wh, shape)    # more than 8 requests: the GEMM path
 
 
 def test_first_token_equal_scores_take_lowest_index():
