@@ -109,8 +109,14 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, x = lane >> 5;
-  const int kvh = blockIdx.y;
-  const int row0 = blockIdx.x * rows_per_tile;
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The remap hands every XCD
+  // one contiguous range of (kv head, row tile) pairs, so the workgroups resident on an XCD at the
+  // same time are neighbouring row tiles of one request and kv head and stream the same K/V.
+  const int lin = blockIdx.y * gridDim.x + blockIdx.x, total = gridDim.x * gridDim.y;
+  const int per = total / 8;
+  const int vid = lin < per * 8 ? (lin % 8) * per + lin / 8 : lin;
+  const int kvh = vid / gridDim.x;
+  const int row0 = (vid - kvh * gridDim.x) * rows_per_tile;
   const int rows_here = min(rows_per_tile, n - row0);
 
   if (tid < rows_per_tile) {                       // rows_per_tile <= 128 * RT <= 256 threads
