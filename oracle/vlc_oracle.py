@@ -166,25 +166,46 @@ def reused_slots(segments, counts):
 # ----------------------------------------------------------------------------------------------
 # rotary position embedding
 # ----------------------------------------------------------------------------------------------
-def rope_angles(pos, D, base):
-    """angle[t, i] = pos[t] * base**(-2 i / D), i in [0, D/2)."""
+def rope_axes(D, section):
+    """Which position axis (0 temporal, 1 height, 2 width) drives each of the D/2 rotation frequencies
+    under 3-axis RoPE with `section` = (t, h, w) frequency counts.
+
+    reading: the paper's main models are Qwen3-VL decoders (Sec. 5.1) and it does not restate their
+    rotary layout; that family interleaves the axes over the frequency index i: height takes
+    i = 1, 4, 7, ... below 3 * section[1], width i = 2, 5, 8, ... below 3 * section[2], the
+    temporal axis everything else.  An empty section means ordinary 1-D RoPE (axis 0 everywhere).
+    """
+    ax = np.zeros(D // 2, dtype=np.int64)
+    if section:
+        i = np.arange(D // 2)
+        ax[(i % 3 == 1) & (i < 3 * section[1])] = 1
+        ax[(i % 3 == 2) & (i < 3 * section[2])] = 2
+    return ax
+
+
+def rope_angles(pos, D, base, section=()):
+    """angle[t, i] = pos[t, axis(i)] * base**(-2 i / D), i in [0, D/2); pos [n] (one id for all axes) or [n, 3]."""
     i = np.arange(D // 2, dtype=np.float64)
     inv_freq = np.power(np.float64(base), -2.0 * i / D)
-    return np.asarray(pos, dtype=np.float64)[:, None] * inv_freq[None, :]
+    pos = np.asarray(pos, dtype=np.float64)
+    if pos.ndim == 1:
+        return pos[:, None] * inv_freq[None, :]
+    return pos[:, rope_axes(D, section)] * inv_freq[None, :]
 
 
-def rope_rotate(x, pos, base):
+def rope_rotate(x, pos, base, section=()):
     """Rotate x[t, head, :] by the angles of position pos[t] (may be negative).
 
     reading: the paper does not give the pairing; the Qwen-family convention is used: element i
     pairs with element i + D/2;  lo' = lo cos - hi sin,  hi' = hi cos + lo sin.
     Because rotations compose, calling this on keys that were already rotated at position q with
-    pos = p - q leaves them rotated at p (Sec. 4.2 stores keys un-rotated, i.e. q = 0).
+    pos = p - q leaves them rotated at p (Sec. 4.2 stores keys un-rotated, i.e. q = 0); with 3-axis
+    positions that holds axis by axis, and a shift common to all axes is a 1-D pos.
     """
     x = np.asarray(x, dtype=np.float64)
     D = x.shape[-1]
     half = D // 2
-    ang = rope_angles(pos, D, base)
+    ang = rope_angles(pos, D, base, section)
     c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
     lo, hi = x[..., :half], x[..., half:]
     return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
@@ -245,7 +266,7 @@ def layer_stages(shape, W, x, slots, pos, K, V, store, forced=None):
 
     x      [n, H]  hidden states of those rows (already gathered, storage-rounded)
     slots  [n]     their slot indices (ascending)
-    pos    [n]     their position ids
+    pos    [n]     their position ids, or [n, 3] (temporal, height, width) under 3-axis RoPE
     K, V   [S, Hkv, D]  the request's keys/values for this layer with every slot that is NOT in
            `slots` already filled (reused image tokens, rotated to their new position); rows at
            `slots` are overwritten here with the fresh k, v  (the blend of Sec. 4.2).
@@ -273,8 +294,16 @@ def layer_stages(shape, W, x, slots, pos, K, V, store, forced=None):
     r["xn"] = store(rmsnorm(x, W["w_ln1"], shape.eps))
     r["qkv"] = linear(fed("xn", r["xn"]), W["w_qkv"], W.get("b_qkv"))
     qkv = fed("qkv", r["qkv"])
-    r["q"] = store(rope_rotate(qkv[:, :Hq * D].reshape(n, Hq, D), pos, shape.rope_base))
-    k = store(rope_rotate(qkv[:, Hq * D:(Hq + Hkv) * D].reshape(n, Hkv, D), pos, shape.rope_base))
+    q = qkv[:, :Hq * D].reshape(n, Hq, D)
+    k = qkv[:, Hq * D:(Hq + Hkv) * D].reshape(n, Hkv, D)
+    if W.get("w_qnorm") is not None:
+        # reading (Qwen3 family, the paper's main models): RMSNorm over the head dimension of every
+        # q and k head, before the rotation; unrounded like the projection it follows
+        q = rmsnorm(q, W["w_qnorm"], shape.eps)
+        k = rmsnorm(k, W["w_knorm"], shape.eps)
+    section = getattr(shape, "mrope_section", ())
+    r["q"] = store(rope_rotate(q, pos, shape.rope_base, section))
+    k = store(rope_rotate(k, pos, shape.rope_base, section))
     v = store(qkv[:, (Hq + Hkv) * D:].reshape(n, Hkv, D))
     K[slots] = k
     V[slots] = v
@@ -306,7 +335,14 @@ def blended_kv_before_scatter(shape, request, counts, Kc, Vc, store):
     V = np.zeros((S, shape.Hkv, shape.D), dtype=np.float64)
     slot, row, old = reused_slots(request.segments, counts)
     if slot.size:
-        delta = (request.pos_start + slot) - old
+        if getattr(request, "pos3", None) is not None:
+            # 3-axis ids: a reused image keeps its grid, so every axis of every token moves by the
+            # shift of the image's first (temporal) id; `old` counts from that id token by token
+            t_in_seg = np.concatenate([np.arange(c, seg.length) for seg, c in
+                                       zip([g for g in request.segments if g.is_image], counts)])
+            delta = np.asarray(request.pos3)[slot, 0] - (old - t_in_seg)
+        else:
+            delta = (request.pos_start + slot) - old
         K[slot] = store(rope_rotate(np.asarray(Kc, dtype=np.float64)[row], delta, shape.rope_base))
         V[slot] = np.asarray(Vc, dtype=np.float64)[row]
     return K, V
@@ -336,10 +372,17 @@ def selective_prefill(shape, weights, emb, request, counts_per_layer, cache, sto
         x = prev_h[where]
         Kc, Vc = cache[l]
         K, V = blended_kv_before_scatter(shape, request, counts, store(Kc), store(Vc), store)
-        h, K, V = layer_forward(shape, W, x, slots, request.pos_start + slots, K, V, store)
+        h, K, V = layer_forward(shape, W, x, slots, positions_of(request, slots), K, V, store)
         out.append({"slots": slots, "h": h, "K": K, "V": V})
         prev_slots, prev_h = slots, h
     return out
+
+
+def positions_of(request, slots):
+    """Position ids of the given slots: [n], or [n, 3] when the request carries 3-axis ids."""
+    if getattr(request, "pos3", None) is not None:
+        return np.asarray(request.pos3, dtype=np.int64)[slots]
+    return request.pos_start + np.asarray(slots, dtype=np.int64)
 
 
 def full_prefill(shape, weights, emb, request, store):
@@ -352,7 +395,7 @@ def full_prefill(shape, weights, emb, request, store):
     for W in weights:
         K = np.zeros((S, shape.Hkv, shape.D), dtype=np.float64)
         V = np.zeros((S, shape.Hkv, shape.D), dtype=np.float64)
-        h, K, V = layer_forward(shape, W, h, slots, request.pos_start + slots, K, V, store)
+        h, K, V = layer_forward(shape, W, h, slots, positions_of(request, slots), K, V, store)
         out.append({"slots": slots, "h": h, "K": K, "V": V})
     return out
 

@@ -244,6 +244,114 @@ def test_full_prefill_layer_vs_transformers_qwen2(bias):
 
 
 # ------------------------------------------------------------------------------------------
+# Qwen3-VL-shaped variant: per-head q/k RMSNorm and interleaved 3-axis RoPE
+# ------------------------------------------------------------------------------------------
+def q3_setup(d=0):
+    """text 7 | image 4 x 6 | text 5 | image 3 x 3 | text 6 with grid position ids, all ids moved by d."""
+    shape = syn.SHAPES["tiny_q3"]
+    parts = [("text", 7), ("image", 4, 6), ("text", 5), ("image", 3, 3), ("text", 6)]
+    pos3 = syn.grid_positions(parts, start=d)
+    segs, at, crow = [], 0, 0
+    for prt in parts:
+        n = prt[1] if prt[0] == "text" else prt[1] * prt[2]
+        if prt[0] == "image":
+            segs.append(syn.Segment(at, n, True, int(syn.grid_positions(parts)[at, 0]), crow))   # cached at shift 0
+            crow += n
+        else:
+            segs.append(syn.Segment(at, n, False))
+        at += n
+    req = syn.Request(segs, 0, 0, pos3)
+    W = [syn.layer_weights(shape, 41, l) for l in range(2)]
+    emb = np.random.default_rng(42).standard_normal((at, shape.H))
+    return shape, req, W, emb
+
+
+def test_grid_positions_layout():
+    p = syn.grid_positions([("text", 3), ("image", 2, 3), ("text", 2)], start=10)
+    want = [[10, 10, 10], [11, 11, 11], [12, 12, 12],
+            [13, 13, 13], [13, 13, 14], [13, 13, 15], [13, 14, 13], [13, 14, 14], [13, 14, 15],
+            [16, 16, 16], [17, 17, 17]]
+    np.testing.assert_array_equal(p, want)
+
+
+def test_rope_axes_vs_transformers_interleaved_mrope():
+    from transformers.models.qwen3_vl.modeling_qwen3_vl import Qwen3VLTextRotaryEmbedding
+    for D, section in ((128, (24, 20, 20)), (64, (12, 10, 10)), (64, (16, 8, 8))):
+        freqs = torch.stack([torch.full((1, 2, D // 2), float(a)) for a in range(3)])    # axis id as the value
+        got = Qwen3VLTextRotaryEmbedding.apply_interleaved_mrope(None, freqs.clone(), list(section))[0, 0].numpy()
+        np.testing.assert_array_equal(orc.rope_axes(D, section), got.astype(np.int64))
+    np.testing.assert_array_equal(orc.rope_axes(8, ()), [0, 0, 0, 0])
+    # one id on all axes is ordinary RoPE whatever the section
+    x = np.random.default_rng(5).standard_normal((3, 2, 64))
+    p = np.array([3, 17, 400])
+    np.testing.assert_array_equal(orc.rope_rotate(x, np.stack([p, p, p], 1), 1e4, (12, 10, 10)), orc.rope_rotate(x, p, 1e4))
+
+
+def test_full_prefill_layer_vs_transformers_qwen3_vl():
+    """Oracle layer with q/k norm and 3-axis positions against the library's Qwen3-VL text decoder layer (fp64)."""
+    from transformers.models.qwen3_vl.modeling_qwen3_vl import (Qwen3VLTextConfig, Qwen3VLTextDecoderLayer,
+                                                                Qwen3VLTextRotaryEmbedding)
+    shape, req, Ws, emb = q3_setup(d=3)
+    W = Ws[0]
+    S = emb.shape[0]
+    cfg = Qwen3VLTextConfig(hidden_size=shape.H, num_attention_heads=shape.Hq, num_key_value_heads=shape.Hkv,
+                            head_dim=shape.D, intermediate_size=shape.I, num_hidden_layers=1, rms_norm_eps=shape.eps,
+                            vocab_size=8, max_position_embeddings=4096, attention_bias=False,
+                            rope_parameters={"rope_type": "default", "rope_theta": shape.rope_base,
+                                             "mrope_section": list(shape.mrope_section)})
+    cfg._attn_implementation = "eager"
+    layer = Qwen3VLTextDecoderLayer(cfg, 0).double()
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    Hq, Hkv, D = shape.Hq, shape.Hkv, shape.D
+    with torch.no_grad():
+        wq, wk, wv = np.split(W["w_qkv"], [Hq * D, (Hq + Hkv) * D], axis=0)
+        layer.self_attn.q_proj.weight.copy_(t(wq))
+        layer.self_attn.k_proj.weight.copy_(t(wk))
+        layer.self_attn.v_proj.weight.copy_(t(wv))
+        layer.self_attn.o_proj.weight.copy_(t(W["w_o"]))
+        layer.self_attn.q_norm.weight.copy_(t(W["w_qnorm"]))
+        layer.self_attn.k_norm.weight.copy_(t(W["w_knorm"]))
+        layer.mlp.gate_proj.weight.copy_(t(W["w_gate_up"][:shape.I]))
+        layer.mlp.up_proj.weight.copy_(t(W["w_gate_up"][shape.I:]))
+        layer.mlp.down_proj.weight.copy_(t(W["w_down"]))
+        layer.input_layernorm.weight.copy_(t(W["w_ln1"]))
+        layer.post_attention_layernorm.weight.copy_(t(W["w_ln2"]))
+        x = t(emb)[None]
+        pos = torch.from_numpy(req.pos3.T.copy())[:, None, :]                    # [3, batch, S]
+        cos, sin = Qwen3VLTextRotaryEmbedding(cfg)(x, pos)
+        mask = torch.full((S, S), float("-inf"), dtype=torch.float64).triu(1)[None, None]
+        ref = layer(x, attention_mask=mask, position_ids=pos, position_embeddings=(cos.double(), sin.double()))
+        ref = (ref[0] if isinstance(ref, tuple) else ref)
+        ref = ref[0].numpy() if ref.dim() == 3 else ref.numpy()
+    got = orc.full_prefill(shape, [W], emb, req, orc.store_exact)[0]["h"]
+    np.testing.assert_allclose(got, ref, atol=2e-6, rtol=0)                        # the library's cos/sin are float32
+    # the norm and the axis layout matter: dropping either moves the result
+    no_norm = dict(W, w_qnorm=None, w_knorm=None)
+    assert np.max(np.abs(orc.full_prefill(shape, [no_norm], emb, req, orc.store_exact)[0]["h"] - ref)) > 1e-3
+    flat = syn.Request(req.segments, 0, 0, np.repeat(req.pos3[:, :1], 3, axis=1))
+    assert np.max(np.abs(orc.full_prefill(shape, [W], emb, flat, orc.store_exact)[0]["h"] - ref)) > 1e-4
+
+
+@pytest.mark.parametrize("d", [0, 19, -3])
+def test_three_axis_reuse_equals_full_prefill(d):
+    """The limits that fix the method also hold with 3-axis ids: a cache taken from a full prefill of
+    the same prompt, every id moved by d on all axes, nothing or little recomputed."""
+    shape, req0, W, emb = q3_setup(d=0)
+    full = orc.full_prefill(shape, W, emb, req0, orc.store_exact)
+    cache = cache_from_full_prefill(shape, W, emb, req0, full)
+    _, moved, _, _ = q3_setup(d=d)
+    for counts in ([img_counts(req0, 0)] * 2, [img_counts(req0, 5), img_counts(req0, 2)], [img_counts(req0, None)] * 2):
+        sel = orc.selective_prefill(shape, W, emb, moved, counts, cache, orc.store_exact)
+        for l in range(2):
+            np.testing.assert_allclose(sel[l]["h"], full[l]["h"][sel[l]["slots"]], atol=1e-9)
+    # moving the axes by different amounts is not a reuse the method covers: the temporal shift alone is applied
+    bad = syn.Request(moved.segments, 0, 0, moved.pos3 + np.array([0, 1, 0]))
+    if d != 0:
+        sel = orc.selective_prefill(shape, W, emb, bad, [img_counts(req0, 0)] * 2, cache, orc.store_exact)
+        assert np.max(np.abs(sel[-1]["h"] - full[-1]["h"][sel[-1]["slots"]])) > 1e-6
+
+
+# ------------------------------------------------------------------------------------------
 # first output token: final norm + output matrix + greedy choice
 # ------------------------------------------------------------------------------------------
 def test_first_token_vs_transformers_qwen2_causal_lm():

@@ -7,9 +7,9 @@ tests and the HIP path's tests/benchmark take their inputs from here, so the
 two sides see identical data without sharing any computation.
 """
 from .workloads import (Shape, Segment, Request, Workload, SHAPES, make_workload,
-                        layer_weights, head_weights, embedding_rows, cached_kv,
+                        layer_weights, head_weights, grid_positions, embedding_rows, cached_kv,
                         sensitivity_table, normal_f32, WEIGHT_NAMES)
 
 __all__ = ["Shape", "Segment", "Request", "Workload", "SHAPES", "make_workload",
-           "layer_weights", "head_weights", "embedding_rows", "cached_kv", "sensitivity_table",
+           "layer_weights", "head_weights", "grid_positions", "embedding_rows", "cached_kv", "sensitivity_table",
            "normal_f32", "WEIGHT_NAMES"]

@@ -31,6 +31,8 @@ class Shape:
     qkv_bias: bool
     eps: float = 1e-6
     vocab: int = 512  # rows of the output (LM head) matrix
+    qk_norm: bool = False                 # per-head RMSNorm of q and k before RoPE (Qwen3 family)
+    mrope_section: tuple = ()             # (t, h, w) frequency counts of 3-axis RoPE; () = 1-D RoPE
 
     @property
     def g(self) -> int:
@@ -48,6 +50,13 @@ SHAPES: Dict[str, Shape] = {
                        dtype="f32", qkv_bias=True),
     "tiny_bf16": Shape("tiny_bf16", L=2, H=256, Hq=4, Hkv=2, D=128, I=512, rope_base=1e4,
                        dtype="bf16", qkv_bias=True),
+    # Qwen3-VL-shaped variants: q/k norm, interleaved 3-axis RoPE, no q|k|v bias
+    "tiny_q3": Shape("tiny_q3", L=2, H=256, Hq=4, Hkv=2, D=64, I=512, rope_base=1e4,
+                     dtype="f32", qkv_bias=False, qk_norm=True, mrope_section=(12, 10, 10)),
+    "tiny_q3_bf16": Shape("tiny_q3_bf16", L=2, H=256, Hq=4, Hkv=2, D=128, I=512, rope_base=1e4,
+                          dtype="bf16", qkv_bias=False, qk_norm=True, mrope_section=(24, 20, 20)),
+    "q3vl_8b": Shape("q3vl_8b", L=36, H=4096, Hq=32, Hkv=8, D=128, I=12288, rope_base=5e6,
+                     dtype="bf16", qkv_bias=False, vocab=151936, qk_norm=True, mrope_section=(24, 20, 20)),
     "7b": Shape("7b", L=28, H=3584, Hq=28, Hkv=4, D=128, I=18944, rope_base=1e6,
                 dtype="bf16", qkv_bias=True, vocab=152064),
     "72b": Shape("72b", L=80, H=8192, Hq=64, Hkv=8, D=128, I=29568, rope_base=1e6,
@@ -77,6 +86,11 @@ class Request:
     segments: Sequence[Segment]
     kv_start: int     # first slot of this request in the packed KV of the batch
     pos_start: int = 0  # position id of the request's first slot (slot s has pos_start + s)
+    # 3-axis position ids [S, 3] (temporal, height, width) when the decoder uses 3-axis RoPE, else
+    # None.  Text slots carry the same id on all axes; an image's tokens share the temporal id and
+    # count rows / columns of its grid on the other two.  A reused image whose first position moved
+    # from Segment.old_pos to pos3[start, 0] has every axis of every token shifted by that difference.
+    pos3: Optional[np.ndarray] = None
 
     @property
     def S(self) -> int:
@@ -202,6 +216,7 @@ def normal_f32(seed_key: Sequence[int], n: int, scale: float = 1.0, threads: int
 
 
 WEIGHT_NAMES = ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down")
+QK_NORM_NAMES = ("w_qnorm", "w_knorm")   # only for shapes with qk_norm
 
 
 def layer_weights(shape: Shape, seed: int, layer: int) -> Dict[str, Optional[np.ndarray]]:
@@ -223,7 +238,28 @@ def layer_weights(shape: Shape, seed: int, layer: int) -> Dict[str, Optional[np.
         if nm in ("w_ln1", "w_ln2"):
             w += np.float32(1.0)
         out[nm] = w
+    for t, nm in enumerate(QK_NORM_NAMES):
+        out[nm] = (normal_f32([seed, 1000 + layer, 100 + t], shape.D, 0.02) + np.float32(1.0)) if shape.qk_norm else None
     return out
+
+
+def grid_positions(parts: Sequence[tuple], start: int = 0) -> np.ndarray:
+    """3-axis position ids [S, 3] of a prompt made of ("text", n) and ("image", rows, cols) parts, the
+    way the Qwen-VL family numbers them: text advances all three axes together; an image starting
+    at id p gives its tokens (p, p + row, p + col) in row-major order and the next part starts at
+    p + max(rows, cols)."""
+    out, p = [], start
+    for part in parts:
+        if part[0] == "text":
+            ids = p + np.arange(part[1])
+            out.append(np.stack([ids, ids, ids], axis=1))
+            p += part[1]
+        else:
+            rows, cols = part[1], part[2]
+            rr, cc = np.divmod(np.arange(rows * cols), cols)
+            out.append(np.stack([np.full(rows * cols, p), p + rr, p + cc], axis=1))
+            p += max(rows, cols)
+    return np.concatenate(out).astype(np.int64)
 
 
 def head_weights(shape: Shape, seed: int) -> Dict[str, np.ndarray]:
