@@ -40,6 +40,11 @@ DESCR = {
     "c4": "c4: 7B shape, batch of 8 requests of 16 x 1024-token images + 2048 text tokens at distinct shifts, "
           "uniform 2% recompute (18944 packed rows/layer, S=18432 per request)",
     "c4_5": "c4_5: as c4 with uniform 5% recompute (22912 packed rows/layer)",
+    "c2_q3": "c2_q3: Qwen3-VL-8B-shaped decoder (36 layers, H4096, 32q/8kv heads, D128, MLP 12288, bf16, q/k norm, "
+             "interleaved 3-axis RoPE), 512 text | 32x32-token image reused at +512 | 64 text, uniform 2% recompute "
+             "(596 rows/layer, S=1600)",
+    "c3_q3": "c3_q3: Qwen3-VL-8B shape, four 36x36-token images between 128-token text runs at shuffled positions, "
+             "layer-aware rates from a 5% mean budget (S=5824)",
     "c5": "c5: Qwen2.5-VL-72B-shaped decoder (80 layers, H8192, 64q/8kv heads, D128, MLP 29568, bf16), "
           "8 x 1296-token images + 256 text, layer-aware rates from a 3% mean budget (S=10624)",
 }
@@ -148,7 +153,7 @@ def main() -> int:
     L = sh.L
     dt = R.torch_dtype(sh.dtype)
     rec = R.make_shape(sh)
-    steps = args.steps if args.steps is not None else {"c1": 50, "c2": 20, "c3": 10, "c4": 5, "c4_5": 5, "c5": 5}[wl.name]
+    steps = args.steps if args.steps is not None else {"c1": 50, "c2": 20, "c3": 10, "c4": 5, "c4_5": 5, "c5": 5, "c2_q3": 20, "c3_q3": 10}[wl.name]
 
     # ---- plans (library planner) ---------------------------------------------------------------
     k, explicit = R.plan_for(wl)
@@ -372,7 +377,7 @@ def main() -> int:
             cores = os.cpu_count()
         req = wl.requests[0]
         # about 10-30 s of oracle work: ~1.3 s per 7B-shaped layer at 596 rows on the box's 16 host threads
-        n_layers = args.cpu_layers or {"c1": 2, "c2": 10, "c3": 3}.get(wl.name, 1)
+        n_layers = args.cpu_layers or {"c1": 2, "c2": 10, "c3": 3, "c2_q3": 10, "c3_q3": 3}.get(wl.name, 1)
         n_layers = min(n_layers, L)
         Ws = [syn.layer_weights(sh, wl.seed, l) for l in range(n_layers)]
         caches = [syn.cached_kv(wl, l) for l in range(n_layers)]

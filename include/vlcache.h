@@ -183,6 +183,12 @@ typedef struct {
   int32_t dtype;              /* VLC_F32 | VLC_BF16 */
   float eps;                  /* RMSNorm epsilon */
   double rope_base;
+  /* 3-axis RoPE (Qwen3-VL family, the paper's main models, Sec. 5.1): numbers of rotation
+   * frequencies driven by the temporal / height / width position id, interleaved over the frequency
+   * index i: height takes i = 1, 4, 7, ... below 3*mrope_h, width i = 2, 5, 8, ... below 3*mrope_w,
+   * the temporal id the rest.  All three 0: ordinary 1-D RoPE (plan->pos).  Otherwise the ids of
+   * the recomputed rows come from plan->pos3. */
+  int32_t mrope_t, mrope_h, mrope_w;
 } vlc_layer_shape;
 
 typedef struct {              /* device pointers; b_qkv may be NULL (no bias) */
@@ -193,6 +199,8 @@ typedef struct {              /* device pointers; b_qkv may be NULL (no bias) */
   const void* w_ln2;          /* [H] */
   const void* w_gate_up;      /* [2I, H], rows: gate then up */
   const void* w_down;         /* [H, I] */
+  const void* w_qnorm;        /* [D] or NULL: RMSNorm weight applied to every q head before RoPE (Qwen3 family) */
+  const void* w_knorm;        /* [D] or NULL: the same for every k head; both or neither */
 } vlc_layer_weights;
 
 typedef struct {
@@ -211,6 +219,10 @@ typedef struct {
   const void* k_pool;           /* device [pool_rows, Hkv, D] cached image keys of this layer */
   const void* v_pool;           /* device [pool_rows, Hkv, D] */
   int64_t pool_rows;
+  /* device [n, 3] (temporal, height, width ids of the recomputed rows) when the shape has 3-axis
+   * RoPE, else NULL (pos is then not read).  A reused image keeps its grid, so all three ids of all
+   * its tokens move by one amount: reuse_delta stays one number per reused token. */
+  const int32_t* pos3;
 } vlc_layer_plan;
 
 /* Bytes of workspace vlc_layer_forward needs for up to n_rows_max recomputed rows (0 on error). */
@@ -231,7 +243,7 @@ int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t n_rows, int
  * One layer (Sec. 4.1 "Basic Algorithm" / Sec. 4.2; decoder details follow the Qwen family the
  * paper evaluates): for the n recomputed rows
  *   x  = h_in[map]                       gather of the retained rows
- *   q,k,v = RMSNorm(x) Wqkv^T + b ;  RoPE(q), RoPE(k) at pos
+ *   q,k,v = RMSNorm(x) Wqkv^T + b ;  optional per-head RMSNorm of q, k ;  RoPE(q), RoPE(k) at pos (or pos3)
  *   K/V: reused image tokens placed (keys rotated by reuse_delta), then K[slot]=k, V[slot]=v
  *   a  = attention of the n rows over K/V[row_kv_start : row_kv_start + row_kv_len)
  *   h1 = x + a Wo^T ;  h_out = h1 + (silu(n2 Wg^T) * (n2 Wu^T)) Wd^T,  n2 = RMSNorm(h1)

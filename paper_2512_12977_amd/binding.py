@@ -25,11 +25,13 @@ class Segment(C.Structure):
 
 class LayerShape(C.Structure):
     _fields_ = [("H", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32), ("I", C.c_int32),
-                ("dtype", C.c_int32), ("eps", C.c_float), ("rope_base", C.c_double)]
+                ("dtype", C.c_int32), ("eps", C.c_float), ("rope_base", C.c_double),
+                ("mrope_t", C.c_int32), ("mrope_h", C.c_int32), ("mrope_w", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down")]
+    _fields_ = [(n, C.c_void_p) for n in ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down",
+                                          "w_qnorm", "w_knorm")]
 
 
 class LayerPlan(C.Structure):
@@ -37,7 +39,7 @@ class LayerPlan(C.Structure):
                 ("pos", C.c_void_p), ("row_kv_start", C.c_void_p), ("row_kv_len", C.c_void_p),
                 ("kv_rows", C.c_int64), ("n_reuse", C.c_int64), ("reuse_src", C.c_void_p),
                 ("reuse_dst", C.c_void_p), ("reuse_delta", C.c_void_p), ("k_pool", C.c_void_p),
-                ("v_pool", C.c_void_p), ("pool_rows", C.c_int64)]
+                ("v_pool", C.c_void_p), ("pool_rows", C.c_int64), ("pos3", C.c_void_p)]
 
 
 def lib_path() -> str:

@@ -46,6 +46,10 @@ int check_shape(const vlc_layer_shape* s, const char* who) {
   if (s->H % 64 || s->I % 64 || (s->Hq * s->D) % 64)
     return fail(VLC_ERR_SHAPE, "%s: H, I and Hq*D must be multiples of 64", who);
   if (!(s->rope_base > 0.0) || !(s->eps >= 0.f)) return fail(VLC_ERR_SHAPE, "%s: rope_base/eps", who);
+  if (s->mrope_t < 0 || s->mrope_h < 0 || s->mrope_w < 0 ||
+      ((s->mrope_t | s->mrope_h | s->mrope_w) != 0 && s->mrope_t + s->mrope_h + s->mrope_w != s->D / 2))
+    return fail(VLC_ERR_SHAPE, "%s: 3-axis RoPE sections %d+%d+%d must add up to D/2 = %d", who, s->mrope_t,
+                s->mrope_h, s->mrope_w, s->D / 2);
   return VLC_OK;
 }
 
@@ -105,7 +109,9 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
     return fail(VLC_ERR_NULL, "%s: reuse list or pool is NULL", who);
   const vlc_layer_shape& s = *shape;
   hipStream_t st = (hipStream_t)stream;
-  const vlc::RopeFreq freq = vlc::make_rope_freq(s.rope_base, s.D);
+  const bool mrope = s.mrope_t > 0 || s.mrope_h > 0 || s.mrope_w > 0;
+  // the reused keys move by one shift common to all axes, so their rotation needs no axis table
+  const vlc::RopeFreq freq = vlc::make_rope_freq(s.rope_base, s.D, s.mrope_h, s.mrope_w);
 
   VLC_MARK(0);
   // Reused image tokens: keys rotated by the position delta, values copied (independent of the rows).
@@ -121,8 +127,11 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
   }
   if (!w->w_ln1 || !w->w_qkv || !w->w_o || !w->w_ln2 || !w->w_gate_up || !w->w_down)
     return fail(VLC_ERR_NULL, "%s: a weight pointer is NULL", who);
-  if (!p->map || !p->slot || !p->pos || !p->row_kv_start || !p->row_kv_len || !h_in || !h_out)
+  if (!p->map || !p->slot || !(mrope ? (const void*)p->pos3 : (const void*)p->pos) || !p->row_kv_start ||
+      !p->row_kv_len || !h_in || !h_out)
     return fail(VLC_ERR_NULL, "%s: NULL pointer in plan / hidden states", who);
+  if ((w->w_qnorm == nullptr) != (w->w_knorm == nullptr))
+    return fail(VLC_ERR_NULL, "%s: w_qnorm and w_knorm come together", who);
   if (h_in == h_out) return fail(VLC_ERR_SHAPE, "%s: h_out must not alias h_in", who);
   const Workspace ws = layout(s, n);
   if (!workspace || workspace_bytes < ws.total)
@@ -153,7 +162,7 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
   VLC_MARK(3);
   rc = vlc::launch_rope_qk_scatter(qkv32, p->pos, p->slot, n, s.Hq, s.Hkv, s.D, freq, qrot, k_cache, v_cache,
                                    s.dtype, st, static_cast<const float*>(skw), qkv_splits > 0 ? qkv_splits : 1,
-                                   w->b_qkv);
+                                   w->b_qkv, mrope ? p->pos3 : nullptr, w->w_qnorm, w->w_knorm, s.eps);
   if (rc) return rc;
   VLC_MARK(4);
   rc = vlc::launch_attention(qrot, hqd, k_cache, v_cache, p->row_kv_start, p->row_kv_len, n, s.Hq, s.Hkv, s.D,

@@ -18,6 +18,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {   // round to nearest
 }
 
 // A 16-byte chunk viewed as VEC elements of T, converted to/from float.
+__device__ __forceinline__ float elem_to_float(float v) { return v; }
+__device__ __forceinline__ float elem_to_float(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }   // bf16
+
 template <typename T> struct Chunk;
 template <> struct Chunk<float> {
   static constexpr int VEC = 4;
@@ -201,10 +204,14 @@ constexpr int kMaxSplits = 8;   // the GEMM never splits the k range into more p
 // SUM: the projection was left as `splits` float partial matrices (split_stride elements apart,
 // split-K); they are added here in split order, then the bias, and the sum is also stored to
 // qkv_sum so the unrounded projection stays available to the caller.
+// pos3 (optional): per-axis position ids [n, 3]; frequency i then takes the id of axis freq.axis[i].
+// w_qn / w_kn (optional, [D]): RMSNorm over every q / k head before the rotation (a head's D values
+// are spread over CH consecutive lanes, which exchange their partial sums of squares).
 template <typename T, int D, int HB, bool SUM>
 __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
     const float* __restrict__ qkv, int splits, int64_t split_stride, const uint16_t* __restrict__ bias,
-    float* __restrict__ qkv_sum, const int32_t* __restrict__ pos, const int32_t* __restrict__ slot,
+    float* __restrict__ qkv_sum, const int32_t* __restrict__ pos, const int32_t* __restrict__ pos3,
+    const T* __restrict__ w_qn, const T* __restrict__ w_kn, float eps, const int32_t* __restrict__ slot,
     int64_t n, int Hq, int Hkv, int head_blocks, RopeFreq freq, uint4* __restrict__ q_out,
     uint4* __restrict__ k_cache, uint4* __restrict__ v_cache) {
   constexpr int VEC = Chunk<T>::VEC;
@@ -217,10 +224,17 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
   const int64_t row = t / head_blocks;
   if (row >= n) return;
   const int heads = Hq + 2 * Hkv;
-  const int p = pos[row];
   float sn[VEC], cs[VEC];
+  if (pos3) {
+    const int p3[3] = {pos3[3 * row], pos3[3 * row + 1], pos3[3 * row + 2]};
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) rope_sincos<sizeof(T) == 2>(freq.inv_freq[c * VEC + i], p, &sn[i], &cs[i]);
+    for (int i = 0; i < VEC; ++i)
+      rope_sincos<sizeof(T) == 2>(freq.inv_freq[c * VEC + i], p3[freq.axis[c * VEC + i]], &sn[i], &cs[i]);
+  } else {
+    const int p = pos[row];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) rope_sincos<sizeof(T) == 2>(freq.inv_freq[c * VEC + i], p, &sn[i], &cs[i]);
+  }
   const float* r = qkv + row * ((int64_t)heads * D) + c * VEC;
   uint4* qo = q_out + row * ((int64_t)Hq * HEAD_CHUNKS) + c;
   const int64_t dst = (int64_t)slot[row] * ((int64_t)Hkv * HEAD_CHUNKS) + c;
@@ -266,6 +280,20 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
       v_cache[dst + (h - Hq - Hkv) * HEAD_CHUNKS] = Chunk<T>::pack(lo);
       v_cache[dst + (h - Hq - Hkv) * HEAD_CHUNKS + CH] = Chunk<T>::pack(hi);
       continue;
+    }
+    if (w_qn) {   // RMSNorm over the head, float; every lane of the head's CH-lane group is here
+      float ss = 0.f;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) ss += lo[i] * lo[i] + hi[i] * hi[i];
+#pragma unroll
+      for (int o = 1; o < CH; o <<= 1) ss += __shfl_xor(ss, o);
+      const float rn = 1.0f / sqrtf(ss * (1.0f / (float)D) + eps);
+      const T* wn = (h < Hq ? w_qn : w_kn) + c * VEC;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        lo[i] = lo[i] * rn * elem_to_float(wn[i]);
+        hi[i] = hi[i] * rn * elem_to_float(wn[D / 2 + i]);
+      }
     }
     float olo[VEC], ohi[VEC];
 #pragma unroll
@@ -554,8 +582,11 @@ int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v
 
 int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t* slot, int64_t n, int Hq,
                            int Hkv, int D, const RopeFreq& f, void* q_out, void* k_cache, void* v_cache,
-                           int dtype, hipStream_t st, const float* partials, int splits, const void* bias) {
+                           int dtype, hipStream_t st, const float* partials, int splits, const void* bias,
+                           const int32_t* pos3, const void* w_qnorm, const void* w_knorm, float eps) {
   if (n <= 0) return VLC_OK;
+  if ((w_qnorm == nullptr) != (w_knorm == nullptr))
+    return fail(VLC_ERR_NULL, "rope+scatter: q and k norm weights come together");
   if (splits > 1 && (dtype != VLC_BF16 || !partials))
     return fail(VLC_ERR_SHAPE, "rope+scatter: split partials are a bf16-path input");
   const int64_t split_stride = n * (int64_t)(Hq + 2 * Hkv) * D;
@@ -571,8 +602,8 @@ int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t
 #define VLC_LAUNCH_RQS2(T, DD, SUM, HB)                                                               \
   hipLaunchKernelGGL((rope_qk_scatter_kernel<T, DD, HB, SUM>), grid, dim3(kThreads), 0, st,           \
                      SUM ? partials : qkv32, splits, split_stride, (const uint16_t*)bias,             \
-                     const_cast<float*>(qkv32), pos, slot, n, Hq, Hkv, head_blocks, f, (uint4*)q_out, \
-                     (uint4*)k_cache, (uint4*)v_cache)
+                     const_cast<float*>(qkv32), pos, pos3, (const T*)w_qnorm, (const T*)w_knorm, eps, \
+                     slot, n, Hq, Hkv, head_blocks, f, (uint4*)q_out, (uint4*)k_cache, (uint4*)v_cache)
 #define VLC_LAUNCH_RQS(T, DD, SUM)                                                                    \
   do {                                                                                                \
     if (wide) VLC_LAUNCH_RQS2(T, DD, SUM, 4); else VLC_LAUNCH_RQS2(T, DD, SUM, 1);                    \

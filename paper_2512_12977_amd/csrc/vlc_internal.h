@@ -30,10 +30,12 @@ inline int elem_size(int dtype) { return dtype == VLC_BF16 ? 2 : 4; }
   } while (0)
 
 // RoPE inverse frequencies theta_i = base^(-2i/D), i < D/2, in double; passed to kernels by value.
+// axis[i]: which position id (0 temporal, 1 height, 2 width) drives frequency i (all 0: 1-D RoPE).
 struct RopeFreq {
   double inv_freq[64];
+  unsigned char axis[64];
 };
-RopeFreq make_rope_freq(double base, int D);
+RopeFreq make_rope_freq(double base, int D, int mrope_h = 0, int mrope_w = 0);
 
 // ---- internal launchers (enqueue only; arguments already validated by the callers) ----------
 
@@ -74,10 +76,13 @@ int launch_scatter_kv(const void* k_new, const void* v_new, int64_t src_stride_e
 // splits > 1 (bf16 path): the projection is still `splits` float partial matrices [splits][n][(Hq+2Hkv)D]
 // at `partials`; they are summed in split order, the bias (may be NULL) added, and the sum is
 // also written to qkv32.  Otherwise qkv32 is the finished projection and is only read.
+// pos3 (optional, [n, 3]): per-axis position ids, selected per frequency by f.axis; else pos [n].
+// w_qnorm / w_knorm (optional, [D]): RMSNorm over each q / k head (eps) before the rotation.
 int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t* slot, int64_t n, int Hq,
                            int Hkv, int D, const RopeFreq& f, void* q_out, void* k_cache, void* v_cache,
                            int dtype, hipStream_t st, const float* partials = nullptr, int splits = 1,
-                           const void* bias = nullptr);
+                           const void* bias = nullptr, const int32_t* pos3 = nullptr,
+                           const void* w_qnorm = nullptr, const void* w_knorm = nullptr, float eps = 0.f);
 
 // q rows have a row stride of q_stride elements (dense q: Hq*D).  ws: optional float scratch of
 // attention_ws_bytes() that allows splitting the key range when there are few query rows.

@@ -17,18 +17,26 @@ def torch_dtype(name: str):
 
 def make_shape(sh) -> B.LayerShape:
     """sh: any object with H, Hq, Hkv, D, I, dtype ('f32'|'bf16'), eps, rope_base."""
+    sec = tuple(getattr(sh, "mrope_section", ())) or (0, 0, 0)
     return B.LayerShape(sh.H, sh.Hq, sh.Hkv, sh.D, sh.I, B.VLC_BF16 if sh.dtype == "bf16" else B.VLC_F32,
-                        float(sh.eps), float(sh.rope_base))
+                        float(sh.eps), float(sh.rope_base), int(sec[0]), int(sec[1]), int(sec[2]))
 
 
 def segments_of(requests: Sequence) -> List[B.Segment]:
     """Flatten requests (with .segments, .kv_start, .pos_start) into the ABI's segment records."""
     out = []
     for r in requests:
+        p3 = getattr(r, "pos3", None)
         for s in r.segments:
-            out.append(B.Segment(r.kv_start + s.start, s.length, int(s.is_image), r.pos_start + s.start,
-                                 s.old_pos, s.cache_row, r.kv_start))
+            # with 3-axis ids the segment's position is its first temporal id: an image's tokens share it,
+            # so new - old is the shift of every axis of every token (the planner's reuse delta)
+            pos = int(p3[s.start, 0]) if p3 is not None else r.pos_start + s.start
+            out.append(B.Segment(r.kv_start + s.start, s.length, int(s.is_image), pos, s.old_pos, s.cache_row,
+                                 r.kv_start))
     return out
+
+
+_WEIGHT_FIELDS = ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down", "w_qnorm", "w_knorm")
 
 
 class DeviceWeights:
@@ -38,8 +46,7 @@ class DeviceWeights:
         self.t = {}
         for name, a in W.items():
             self.t[name] = None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(device=device, dtype=dtype)
-        self.rec = B.LayerWeights(*[None if self.t[n] is None else self.t[n].data_ptr()
-                                    for n in ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down")])
+        self.rec = B.LayerWeights(*[None if self.t.get(n) is None else self.t[n].data_ptr() for n in _WEIGHT_FIELDS])
 
     @classmethod
     def random(cls, sh, dtype, seed: int, device="cuda") -> "DeviceWeights":
@@ -59,8 +66,10 @@ class DeviceWeights:
             if name in ("w_ln1", "w_ln2"):
                 w += 1.0
             self.t[name] = w.to(dtype)
-        self.rec = B.LayerWeights(*[None if self.t[n] is None else self.t[n].data_ptr()
-                                    for n in ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down")])
+        if getattr(sh, "qk_norm", False):
+            for name in ("w_qnorm", "w_knorm"):
+                self.t[name] = (1.0 + 0.02 * torch.randn((sh.D,), generator=g, device=device, dtype=torch.float32)).to(dtype)
+        self.rec = B.LayerWeights(*[None if self.t.get(n) is None else self.t[n].data_ptr() for n in _WEIGHT_FIELDS])
         return self
 
 
@@ -85,6 +94,11 @@ class DevicePlans:
                  for name in ("slot", "map", "pos", "kv_start", "kv_len")}
             d.update({name: torch.from_numpy(self.reuse[name][l, :m].copy()).to(device)
                       for name in ("src_row", "dst_slot", "delta")})
+            d["pos3"] = None
+            if any(getattr(r, "pos3", None) is not None for r in requests):
+                # 3-axis ids of the recomputed rows: packed slot -> (request, local slot) -> its ids
+                all3 = np.concatenate([np.asarray(r.pos3, dtype=np.int32) for r in requests])   # requests are packed in order
+                d["pos3"] = torch.from_numpy(np.ascontiguousarray(all3[self.host["slot"][l, :n]])).to(device)
             self.dev.append(d)
 
     def record(self, l: int, n_in: int, kv_rows: int, k_pool=None, v_pool=None) -> B.LayerPlan:
@@ -93,7 +107,8 @@ class DevicePlans:
         p = lambda t: t.data_ptr() if t is not None and t.numel() else None
         return B.LayerPlan(n_in, n, p(d["map"]), p(d["slot"]), p(d["pos"]), p(d["kv_start"]), p(d["kv_len"]),
                            kv_rows, m if k_pool is not None else 0, p(d["src_row"]), p(d["dst_slot"]),
-                           p(d["delta"]), p(k_pool), p(v_pool), 0 if k_pool is None else k_pool.shape[0])
+                           p(d["delta"]), p(k_pool), p(v_pool), 0 if k_pool is None else k_pool.shape[0],
+                           p(d["pos3"]))
 
 
 class Workspace:

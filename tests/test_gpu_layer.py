@@ -133,7 +133,7 @@ def check_layer_stage_by_stage(wl, layer=0):
     Kb, Vb = orc.blended_kv_before_scatter(sh, req, counts, st(cache[0]), st(cache[1]), st)
     forced = dict(g)
     forced["K"], forced["V"] = g_K, g_V
-    r = orc.layer_stages(sh, W, x, slots, req.pos_start + slots, Kb, Vb, st, forced=forced)
+    r = orc.layer_stages(sh, W, x, slots, orc.positions_of(req, slots), Kb, Vb, st, forced=forced)
     # every stage, on the GPU's own inputs, element-wise at the stated tolerance
     assert_close(g["xn"], r["xn"], sh.dtype, "stage xn")
     assert_close(g["qkv"], r["qkv"], sh.dtype, "stage qkv")
@@ -147,10 +147,10 @@ def check_layer_stage_by_stage(wl, layer=0):
     assert_close(g_h, r["h2"], sh.dtype, "stage down-proj + residual")
     # end to end against the free-running oracle, relative to the bf16 noise floor
     Kb, Vb = orc.blended_kv_before_scatter(sh, req, counts, st(cache[0]), st(cache[1]), st)
-    o16 = orc.layer_stages(sh, W, x, slots, req.pos_start + slots, Kb, Vb, st)
+    o16 = orc.layer_stages(sh, W, x, slots, orc.positions_of(req, slots), Kb, Vb, st)
     ex = orc.store_exact
     Kb, Vb = orc.blended_kv_before_scatter(sh, req, counts, cache[0], cache[1], ex)
-    o64 = orc.layer_stages(sh, W, np.asarray(emb, dtype=np.float64)[slots], slots, req.pos_start + slots, Kb, Vb, ex)
+    o64 = orc.layer_stages(sh, W, np.asarray(emb, dtype=np.float64)[slots], slots, orc.positions_of(req, slots), Kb, Vb, ex)
     nrm = np.linalg.norm
     floor = nrm(o16["h2"] - o64["h2"]) / nrm(o64["h2"])       # what bf16 storage costs the oracle itself
     dev = nrm(g_h - o16["h2"]) / nrm(o16["h2"])
@@ -196,3 +196,36 @@ def test_7b_shape_layer_stage_by_stage():
     for layer in (0, 1):
         dev, floor = check_layer_stage_by_stage(wl, layer)
         print("c2 layer %d: |gpu-oracle|/|oracle| = %.2e, bf16 noise floor %.2e" % (layer, dev, floor))
+
+
+# ---- Qwen3-VL-shaped layer: per-head q/k RMSNorm before the rotation, interleaved 3-axis RoPE ----
+
+def test_q3_tiny_fp32_stack_end_to_end():
+    """2-layer fp32 decoder with q/k norm and grid position ids, 13 leading image tokens recomputed."""
+    wl = syn.make_workload("c1_q3")
+    check_against_oracle(wl, layers=2, teacher_forced=False)
+    check_against_oracle(wl, layers=2, teacher_forced=False, all_rows=True)
+
+
+def test_q3_tiny_bf16_stack():
+    wl = syn.make_workload("c1_q3_bf16")
+    check_against_oracle(wl, layers=2, teacher_forced=True)
+    check_layer_stage_by_stage(wl, layer=0)
+    check_layer_stage_by_stage(wl, layer=1)
+
+
+def test_q3_two_packed_requests_images_moved_both_ways_fp32():
+    """Two packed requests; images of different grids, moved forwards and backwards from their cached ids."""
+    sh = syn.SHAPES["tiny_q3"]
+    from vlc_synth.workloads import _grid_request
+    r0 = _grid_request([("text", 20), ("image", 10, 7, 3, 0), ("text", 9)], 0)
+    r1 = _grid_request([("text", 7), ("image", 6, 10, 50, 70), ("image", 5, 8, 0, 130), ("text", 5)], r0.S)
+    wl = syn.Workload("two_q3", sh, [r0, r1], 170, "static", static_k=40, seed=13)
+    check_against_oracle(wl, layers=2, teacher_forced=False)
+
+
+def test_q3_8b_shape_layer_stage_by_stage():
+    """Qwen3-VL 8B text-decoder shape (bf16, S=1600, 596 recomputed rows): every stage against the oracle."""
+    wl = syn.make_workload("c2_q3")
+    dev, floor = check_layer_stage_by_stage(wl, 0)
+    print("c2_q3 layer 0: |gpu-oracle|/|oracle| = %.2e, bf16 noise floor %.2e" % (dev, floor))

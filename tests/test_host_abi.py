@@ -85,6 +85,38 @@ def test_token_indices_bit_exact_vs_oracle(name):
         prev = slots
 
 
+@pytest.mark.parametrize("name", ["c1_q3", "c2_q3", "c3_q3"])
+def test_reuse_deltas_with_grid_position_ids(name):
+    """3-axis ids: the runner hands the planner each run's first temporal id, so a reused image's shift is
+    (new temporal id - cached temporal id) for all of its tokens, of either sign; slots and cache rows as before."""
+    wl = syn.make_workload(name)
+    L = min(wl.shape.L, 4)
+    k, explicit = plan_steps(wl)
+    k = None if k is None else k[:L]
+    explicit = None if explicit is None else explicit[:L]
+    segs = segments_of(wl.requests)
+    out = vlc.vlc_plan_token_indices(segs, L, k=k, count_override=explicit)
+    reuse = vlc.vlc_plan_reuse_rows(segs, L, k=k, count_override=explicit)
+    req = wl.requests[0]
+    signs = set()
+    for l in range(L):
+        counts = counts_for(req, k, explicit, l)
+        s = orc.select_slots(req.segments, counts)
+        n = int(out["n_rows"][l])
+        np.testing.assert_array_equal(out["slot"][l, :n], s)
+        np.testing.assert_array_equal(out["kv_len"][l, :n], s + 1)
+        rs, rr, _ = orc.reused_slots(req.segments, counts)
+        want = np.concatenate([np.full(g.length - c, int(req.pos3[g.start, 0]) - g.old_pos)
+                               for g, c in zip([g for g in req.segments if g.is_image], counts)])
+        m = int(reuse["n_reuse"][l])
+        np.testing.assert_array_equal(reuse["src_row"][l, :m], rr)
+        np.testing.assert_array_equal(reuse["dst_slot"][l, :m], rs)
+        np.testing.assert_array_equal(reuse["delta"][l, :m], want)
+        signs |= set(np.sign(want).tolist())
+    if name == "c3_q3":
+        assert signs == {-1, 1}
+
+
 def test_workload_row_counts():
     """Row counts the benchmark configurations state."""
     def rows(name):
@@ -123,6 +155,12 @@ def test_host_error_paths():
     with pytest.raises(vlc.VlcError):
         vlc.vlc_layer_workspace_bytes(bad, 10)
     assert "Hq" in vlc.last_error()
+    ok = vlc.LayerShape(256, 4, 2, 64, 512, 0, 1e-6, 1e4, 12, 10, 10)
+    assert vlc.vlc_layer_workspace_bytes(ok, 10) > 0
+    for sec in ((12, 10, 9), (33, 0, 0), (-1, 17, 16)):       # the three axes must share the D/2 = 32 frequencies
+        with pytest.raises(vlc.VlcError):
+            vlc.vlc_layer_workspace_bytes(vlc.LayerShape(256, 4, 2, 64, 512, 0, 1e-6, 1e4, *sec), 10)
+        assert "3-axis" in vlc.last_error()
     # first-token head: argument checks come before any GPU work
     L = vlc.lib()
     assert L.vlc_first_token_workspace_bytes(256, 3, vlc.VLC_F32) >= 3 * 256 * 4
@@ -140,7 +178,7 @@ def test_workspace_size_is_monotone_in_rows():
     """A workspace sized for n_max rows must serve every call with fewer rows (the scratch areas for
     split-K GEMMs and key-split attention only exist for small row counts)."""
     from paper_2512_12977_amd.runner import make_shape
-    for name in ("7b", "72b", "tiny_bf16", "tiny"):
+    for name in ("7b", "72b", "tiny_bf16", "tiny", "q3vl_8b", "tiny_q3"):
         rec = make_shape(syn.SHAPES[name])
         prev = 0
         for n in list(range(0, 3000, 13)) + [5000, 18944, 147456]:

@@ -126,6 +126,14 @@ def _layout(parts: Sequence[tuple]) -> List[Segment]:
     return segs
 
 
+def _grid_request(parts: Sequence[tuple], kv_start: int = 0) -> "Request":
+    """A request with 3-axis position ids.  parts: ("text", n) or ("image", rows, cols, old_pos, cache_row),
+    old_pos being the temporal id the image was cached at."""
+    flat = [p if p[0] == "text" else ("image", p[1] * p[2], p[3], p[4]) for p in parts]
+    grid = [p if p[0] == "text" else ("image", p[1], p[2]) for p in parts]
+    return Request(_layout(flat), kv_start, 0, grid_positions(grid))
+
+
 def make_workload(name: str) -> Workload:
     """The benchmark/parity workloads, by short name.
 
@@ -137,6 +145,7 @@ def make_workload(name: str) -> Workload:
     c4  7B shape, batch of 8: text a_b | 16 x 1024-token images | text 2048-a_b, uniform 2 %
     c4_5  as c4 with uniform 5 %
     c5  72B shape, 8 x 1296-token images | 256 text, dynamic 3 % budget
+    c1_q3, c1_q3_bf16, c2_q3, c3_q3  the same prompts for the Qwen3-VL-shaped layer (q/k norm, 3-axis position ids)
     """
     if name == "c1":
         segs = _layout([("text", 32), ("image", 256, 0, 0), ("text", 16)])
@@ -150,6 +159,24 @@ def make_workload(name: str) -> Workload:
         segs = _layout([("text", 32), ("image", 256, 0, 0), ("text", 16)])
         return Workload("c1_bf16", SHAPES["tiny_bf16"], [Request(segs, 0)], 256, "explicit",
                         explicit_counts=13, seed=0)
+    if name in ("c1_q3", "c1_q3_bf16"):
+        # as c1 with the Qwen3-VL-shaped layer: the image is a 16 x 16 grid cached at temporal id 0
+        req = _grid_request([("text", 32), ("image", 16, 16, 0, 0), ("text", 16)])
+        return Workload(name, SHAPES["tiny_q3" if name == "c1_q3" else "tiny_q3_bf16"], [req], 256, "explicit",
+                        explicit_counts=13, seed=6)
+    if name == "c2_q3":
+        # as c2 at the Qwen3-VL 8B text-decoder shape: a 32 x 32-token image cached at temporal id 0
+        req = _grid_request([("text", 512), ("image", 32, 32, 0, 0), ("text", 64)])
+        return Workload("c2_q3", SHAPES["q3vl_8b"], [req], 1024, "static", static_k=10, seed=7)
+    if name == "c3_q3":
+        # as c3 at the Qwen3-VL 8B shape: four 36 x 36 images, reused in a shuffled order.  Cached
+        # under text|img0|text|img1|... where an image advances the ids by max(rows, cols) = 36.
+        G, X = 36, 128
+        old_pos = [X + i * (G + X) for i in range(4)]
+        parts = [("text", X)]
+        for i, j in enumerate((2, 0, 3, 1)):
+            parts += [("image", G, G, old_pos[j], j * G * G), ("text", X)]
+        return Workload("c3_q3", SHAPES["q3vl_8b"], [_grid_request(parts)], 4 * G * G, "dynamic", budget_bp=500, seed=8)
     if name == "c2":
         segs = _layout([("text", 512), ("image", 1024, 0, 0), ("text", 64)])
         return Workload("c2", SHAPES["7b"], [Request(segs, 0)], 1024, "static", static_k=10, seed=2)
