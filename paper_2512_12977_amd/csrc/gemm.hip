@@ -63,6 +63,11 @@ __device__ __forceinline__ void tile_coords(int pid, int total, int tiles_m, int
 //
 // SPLIT > 1 (few output tiles): each workgroup reduces one contiguous range of k-tiles and
 // writes float partials; splitk_epilogue_kernel sums them and applies the epilogue.
+//
+// Tail split: when the tile count is not a multiple of the workgroups the chip holds at once, the
+// last, partly filled round would cost as much as a full one.  The tiles of that round (ids from
+// full_tiles on) are then shared out over tail_splits workgroups each, along k; these write their
+// accumulators as float blocks to tail_ws and tail_reduce_kernel sums them and applies the epilogue.
 constexpr int BK = 64;
 
 __device__ __forceinline__ int fswz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
@@ -88,7 +93,8 @@ template <int BM, int BN, int WGM, int WGN, int STAGES, int OCC, int EPI>
 __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
     const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ W, uint16_t* __restrict__ C,
     int64_t ldc, int M, int N, int K, const uint16_t* __restrict__ bias, const uint16_t* __restrict__ resid,
-    int64_t ldr, const int32_t* __restrict__ rmap, int tiles_m, int tiles_n, int kt_per_split) {
+    int64_t ldr, const int32_t* __restrict__ rmap, int tiles_m, int tiles_n, int kt_per_split, int full_tiles,
+    int tail_splits, float* __restrict__ tail_ws) {
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;      // wavefront tile
   constexpr int MT = WM / 32, NT = WN / 32;        // MFMA tiles per wavefront
@@ -105,9 +111,18 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   u32x4* lds = reinterpret_cast<u32x4*>(smem);
 
   const int tiles = tiles_m * tiles_n;
-  const int split = blockIdx.x / tiles;
+  int split = 0, pid = blockIdx.x, tail_block = -1;   // tail_block >= 0: this workgroup owns one k-range of a tail tile
+  if constexpr (EPI == EPI_PARTIAL) {
+    split = blockIdx.x / tiles;
+    pid = blockIdx.x - split * tiles;
+  } else if ((int)blockIdx.x >= full_tiles) {
+    tail_block = blockIdx.x - full_tiles;
+    const int t = tail_block / tail_splits;
+    split = tail_block - t * tail_splits;
+    pid = full_tiles + t;
+  }
   int tm, tn;
-  tile_coords(blockIdx.x - split * tiles, tiles, tiles_m, tiles_n, &tm, &tn);
+  tile_coords(pid, tiles, tiles_m, tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * CN;
 
   const int tid = threadIdx.x;
@@ -116,7 +131,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   const int l32 = lane & 31, x = lane >> 5;
 
   const int kt_begin = split * kt_per_split;
-  const int kt_end = min(K / BK, kt_begin + kt_per_split);
+  const int kt_end = (EPI == EPI_PARTIAL || tail_block >= 0) ? min(K / BK, kt_begin + kt_per_split) : K / BK;
   const int KT = kt_end - kt_begin;
 
   // ---- per-lane global source of each of this wavefront's loads (k-tile kt_begin) ---------------
@@ -238,6 +253,32 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
 #undef VLC_LDS_DST
 #undef VLC_COMPUTE_TILE
 
+  // ---- tail tile: raw accumulators as a float block [BN/4][BM][4] (lanes of consecutive m write 512 contiguous bytes)
+  if constexpr (EPI != EPI_PARTIAL) {
+    if (tail_block >= 0) {
+      float* P = tail_ws + (int64_t)tail_block * (BM * BN);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int ml = wm * WM + mt * 32 + l32;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          int j0;   // row of the W tile this accumulator tile starts at
+          if constexpr (EPI == EPI_SWIGLU)
+            j0 = nt < NT / 2 ? wn * (WN / 2) + nt * 32 : BN / 2 + wn * (WN / 2) + (nt - NT / 2) * 32;
+          else
+            j0 = wn * WN + nt * 32;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int j = j0 + 4 * x + 8 * q;
+            *reinterpret_cast<float4*>(P + ((int64_t)(j >> 2) * BM + ml) * 4) =
+                make_float4(acc[nt][mt][4 * q], acc[nt][mt][4 * q + 1], acc[nt][mt][4 * q + 2], acc[nt][mt][4 * q + 3]);
+          }
+        }
+      }
+      return;
+    }
+  }
+
   // ---- epilogue ---------------------------------------------------------------------------------
   constexpr int ONT = (EPI == EPI_SWIGLU) ? NT / 2 : NT;   // output tiles along n per wavefront
   constexpr int OWN = (EPI == EPI_SWIGLU) ? WN / 2 : WN;   // output columns per wavefront
@@ -333,6 +374,57 @@ __global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float* __res
   }
 }
 
+// Sum over k-ranges of the tail tiles' float blocks + epilogue.  grid (BM * QN / 256, tail tiles), QN = quads of
+// output columns per tile; a thread owns four consecutive columns of one row.
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restrict__ P, int splits, int full_tiles,
+                                                          int tiles_m, int tiles_n, uint16_t* __restrict__ C,
+                                                          int64_t ldc, int M, int N,
+                                                          const uint16_t* __restrict__ bias,
+                                                          const uint16_t* __restrict__ resid, int64_t ldr,
+                                                          const int32_t* __restrict__ rmap) {
+  constexpr int CN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  const int t = blockIdx.y;
+  int tm, tn;
+  tile_coords(full_tiles + t, tiles_m * tiles_n, tiles_m, tiles_n, &tm, &tn);
+  const int id = blockIdx.x * 256 + threadIdx.x;
+  const int jq = id / BM, ml = id - jq * BM;          // consecutive threads: consecutive rows (contiguous float4 reads)
+  const int m = tm * BM + ml, n = tn * CN + 4 * jq;
+  if (m >= M || n >= N) return;
+  const float* base = P + (int64_t)t * splits * (BM * BN) + ((int64_t)jq * BM + ml) * 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f), u = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int k = 0; k < splits; ++k) {
+    const float4 a = *reinterpret_cast<const float4*>(base + (int64_t)k * (BM * BN));
+    s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+    if constexpr (EPI == EPI_SWIGLU) {
+      const float4 b = *reinterpret_cast<const float4*>(base + (int64_t)k * (BM * BN) + (int64_t)(BN / 8) * BM * 4);
+      u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+    }
+  }
+  if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_F32) {
+    if (bias) {
+      const uint2 b = *reinterpret_cast<const uint2*>(bias + n);
+      s.x += __uint_as_float(b.x << 16); s.y += __uint_as_float(b.x & 0xffff0000u);
+      s.z += __uint_as_float(b.y << 16); s.w += __uint_as_float(b.y & 0xffff0000u);
+    }
+  } else if constexpr (EPI == EPI_RESIDUAL) {
+    const int64_t rrow = rmap ? (int64_t)rmap[m] : (int64_t)m;
+    const uint2 b = *reinterpret_cast<const uint2*>(resid + rrow * ldr + n);
+    s.x += __uint_as_float(b.x << 16); s.y += __uint_as_float(b.x & 0xffff0000u);
+    s.z += __uint_as_float(b.y << 16); s.w += __uint_as_float(b.y & 0xffff0000u);
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    s.x = silu_f(s.x) * u.x; s.y = silu_f(s.y) * u.y; s.z = silu_f(s.z) * u.z; s.w = silu_f(s.w) * u.w;
+  }
+  if constexpr (EPI == EPI_BIAS_F32) {
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + (int64_t)m * ldc + n) = s;
+  } else {
+    uint2 o;
+    o.x = f32_to_bf16(s.x) | (f32_to_bf16(s.y) << 16);
+    o.y = f32_to_bf16(s.z) | (f32_to_bf16(s.w) << 16);
+    *reinterpret_cast<uint2*>(C + (int64_t)m * ldc + n) = o;
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // f32 SIMT kernel: 64 x 64 tile, 256 threads, 4 x 4 outputs per thread, k-tile 16
 // ---------------------------------------------------------------------------------------------
@@ -402,9 +494,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 template <int BM, int BN, int WGM, int WGN, int STAGES, int OCC, int EPI>
 int launch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
                 int64_t K, const void* bias, const void* resid, int64_t ldr, const int32_t* rmap, int splits,
-                int kt_per_split, hipStream_t st) {
+                int kt_per_split, void* tail_ws, int64_t tail_ws_bytes, hipStream_t st) {
   constexpr int CN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + CN - 1) / CN);
+  const int tiles = tiles_m * tiles_n;
   const size_t lds = (size_t)STAGES * (BM + BN) * BK * 2;
   auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, STAGES, OCC, EPI>;
   static bool attr_set = false;    // raising the dynamic LDS limit is per kernel, once per process
@@ -413,10 +506,40 @@ int launch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(WGM * WGN * 64), lds, st, (const uint16_t*)A,
-                     lda, (const uint16_t*)W, (uint16_t*)C, ldc, (int)M, (int)N, (int)K, (const uint16_t*)bias,
-                     (const uint16_t*)resid, ldr, rmap, tiles_m, tiles_n, kt_per_split);
+  // Tail split: the chip holds `slots` workgroups at once; the tiles of the last, partly filled round are
+  // shared out over as many k-ranges as fit into the idle slots (at least 8 k-tiles each).
+  constexpr int slots = 256 * OCC;
+  const int KT = (int)(K / BK);
+  int full = tiles * splits, tail = 0, tsp = 1, tkt = kt_per_split;
+  if constexpr (EPI != EPI_PARTIAL) {
+    tail = tiles % slots;
+    if (tail_ws && tail > 0 && tiles > tail) {
+      tsp = slots / tail;
+      if (tsp > KT / 8) tsp = KT / 8;
+      const int64_t fit = tail_ws_bytes / ((int64_t)tail * BM * BN * 4);
+      if (tsp > fit) tsp = (int)fit;
+    }
+    if (tsp >= 2) {
+      tkt = (KT + tsp - 1) / tsp;
+      tsp = (KT + tkt - 1) / tkt;
+      full = tiles - tail;
+    } else {
+      tail = 0;
+      tsp = 1;
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3(full + tail * tsp), dim3(WGM * WGN * 64), lds, st, (const uint16_t*)A, lda,
+                     (const uint16_t*)W, (uint16_t*)C, ldc, (int)M, (int)N, (int)K, (const uint16_t*)bias,
+                     (const uint16_t*)resid, ldr, rmap, tiles_m, tiles_n, tkt, full, tsp, (float*)tail_ws);
   VLC_CHECK_LAUNCH("gemm_bf16");
+  if constexpr (EPI != EPI_PARTIAL) {
+    if (tail > 0) {
+      hipLaunchKernelGGL((tail_reduce_kernel<BM, BN, EPI>), dim3(BM * (CN / 4) / 256, tail), dim3(256), 0, st,
+                         (const float*)tail_ws, tsp, full, tiles_m, tiles_n, (uint16_t*)C, ldc, (int)M, (int)N,
+                         (const uint16_t*)bias, (const uint16_t*)resid, ldr, rmap);
+      VLC_CHECK_LAUNCH("gemm_tail_reduce");
+    }
+  }
   return VLC_OK;
 }
 
@@ -428,7 +551,8 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
                   void* splitk_ws, int64_t splitk_ws_bytes, int* deferred, hipStream_t st) {
   const int KT = (int)(K / BK);
   if (M >= 1536)
-    return launch_bf16<256, 256, 2, 2, 2, 1, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, st);
+    return launch_bf16<256, 256, 2, 2, 2, 1, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT,
+                                                  splitk_ws, splitk_ws_bytes, st);
   constexpr int CN = (EPI == EPI_SWIGLU) ? 64 : 128;
   const int64_t tiles = ((M + 127) / 128) * ((N + CN - 1) / CN);
   int splits = 1;
@@ -451,12 +575,13 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
     }
   }
   if (splits <= 1)
-    return launch_bf16<128, 128, 2, 2, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, st);
+    return launch_bf16<128, 128, 2, 2, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT,
+                                                  splitk_ws, splitk_ws_bytes, st);
   if constexpr (EPI != EPI_SWIGLU) {
     const int per = (KT + splits - 1) / splits;
     splits = (KT + per - 1) / per;
     int rc = launch_bf16<128, 128, 2, 2, 2, 2, EPI_PARTIAL>(A, lda, W, splitk_ws, N, M, N, K, nullptr, nullptr, 0,
-                                                            nullptr, splits, per, st);
+                                                            nullptr, splits, per, nullptr, 0, st);
     if (rc) return rc;
     if (deferred) {   // the caller's next kernel sums the partials and applies the epilogue
       *deferred = splits;
@@ -485,11 +610,12 @@ int launch_f32(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, 
 
 }  // namespace
 
-// Split-K only runs when a GEMM has fewer than 384 tiles of 128 x 128, and then uses about
-// 512 / tiles splits: splits * M * N floats stay below 2 * 512 * 128 * 128 * 4 bytes.
+// Whole-GEMM split-K only runs when a GEMM has fewer than 384 tiles of 128 x 128, and then uses about
+// 512 / tiles splits: splits * M * N floats stay below 2 * 512 * 128 * 128 * 4 bytes.  The tail split
+// writes at most one float block per resident workgroup: 256 x (256 x 256) or 512 x (128 x 128) floats.
 int64_t gemm_splitk_ws_bytes(int64_t n_rows, int64_t max_n) {
   (void)max_n;
-  return n_rows < 1536 ? (int64_t)64 << 20 : 0;
+  return n_rows > 0 ? (int64_t)64 << 20 : 0;
 }
 
 int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,

@@ -26,7 +26,7 @@ Workspace layout(const vlc_layer_shape& s, int64_t n) {
   w.h1 = at;   at += align256(n * s.H * es);          // hidden after the attention residual
   w.n2 = at;   at += align256(n * s.H * es);          // post-attention-normed activations
   w.act = at;  at += align256(n * (int64_t)s.I * es); // SwiGLU product
-  w.splitk = at;                                      // float partials of split-K GEMMs (few rows only)
+  w.splitk = at;                                      // float partials of split-K GEMMs and of tail tiles
   w.splitk_bytes = s.dtype == VLC_BF16 ? vlc::gemm_splitk_ws_bytes(n, nqkv) : 0;
   at += align256(w.splitk_bytes);
   w.att = at;                                         // partials of key-split attention (few rows only)
@@ -61,17 +61,16 @@ extern "C" int64_t vlc_layer_workspace_bytes(const vlc_layer_shape* shape, int64
     fail(VLC_ERR_SHAPE, "vlc_layer_workspace_bytes: n_rows_max=%lld", (long long)n_rows_max);
     return 0;
   }
-  // The row buffers grow with n; the two scratch areas exist only for small n.  A workspace sized
+  // The row buffers grow with n; the attention scratch area exists only for small n.  A workspace sized
   // here must serve every call with n <= n_rows_max: take the row buffers at n_rows_max and, for each
   // scratch area, the largest size any smaller n can ask for.
   const vlc_layer_shape& s = *shape;
   const int64_t rows_only = layout(s, n_rows_max).splitk;             // scratch areas come last
-  const int64_t n_splitk = n_rows_max < 1535 ? n_rows_max : 1535;     // split-K never runs from 1536 rows on
   const int64_t g = s.Hq / s.Hkv;
   const int64_t rows_per_tile = g <= 128 ? 128 / g : 1;
   int64_t n_att = ((512 + s.Hkv - 1) / s.Hkv - 1) * rows_per_tile;    // largest n whose attention may split
   if (n_att > n_rows_max) n_att = n_rows_max;
-  const int64_t splitk_max = n_splitk > 0 ? layout(s, n_splitk).splitk_bytes : 0;
+  const int64_t splitk_max = layout(s, n_rows_max).splitk_bytes;      // the same for every row count > 0
   const int64_t att_max = n_att > 0 ? layout(s, n_att).att_bytes : 0;
   return rows_only + align256(splitk_max) + align256(att_max);
 }

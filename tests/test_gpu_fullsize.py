@@ -97,3 +97,67 @@ def test_c4_layer_sampled_rows():
         assert_close(forced["n2"], r["n2"], sh.dtype, "n2")
         assert_close(forced["act"], r["act"], sh.dtype, "act")
         assert_close(back(h_out[torch.from_numpy(rows).to(DEV)]), r["h2"], sh.dtype, "h_out")
+
+
+@pytest.mark.parametrize("n_text,n_image,all_rows", [(200, 5000, True), (720, 2000, False), (1600, 0, True)])
+def test_7b_layer_rows_that_leave_a_partial_round_of_gemm_tiles(n_text, n_image, all_rows):
+    """Row counts at which the output tiles of the GEMMs do not fill the chip a whole number of times
+    (5200 rows: all four GEMMs; 720 and 1600 rows: the gate|up GEMM with the 128- and the 256-row tile):
+    the tiles of the last round are then split along k and summed by a second kernel.  Every 13th row
+    (so every tile of every GEMM is sampled) is compared stage by stage with the oracle."""
+    sh = syn.SHAPES["7b"]
+    st = orc.STORE[sh.dtype]
+    dt = R.torch_dtype(sh.dtype)
+    rec = R.make_shape(sh)
+    a = n_text // 2
+    segs = [syn.Segment(0, a, False)]
+    if n_image:
+        segs.append(syn.Segment(a, n_image, True, 7, 0))
+    segs.append(syn.Segment(a + n_image, n_text - a, False))
+    req = syn.Request(segs, 0)
+    wl = syn.Workload("tail_%d_%d" % (n_text, n_image), sh, [req], max(n_image, 1), "static", static_k=0, seed=21)
+    W = syn.layer_weights(sh, wl.seed, 0)
+    emb = syn.embedding_rows(wl)
+    Kc, Vc = syn.cached_kv(wl, 0)
+    total = wl.total_slots
+    plans = R.DevicePlans(wl.requests, 1, k=np.zeros(1, dtype=np.int32), all_rows=all_rows)
+    n = plans.n_rows[0]
+    assert n == (total if all_rows else n_text)
+    ws = R.Workspace(rec, n)
+    dW = R.DeviceWeights(W, dt)
+    kp, vp = torch.from_numpy(Kc).to(DEV).to(dt), torch.from_numpy(Vc).to(DEV).to(dt)
+    kc = torch.zeros((total, sh.Hkv, sh.D), device=DEV, dtype=dt)
+    vc = torch.zeros_like(kc)
+    h_in = torch.from_numpy(emb).to(DEV).to(dt)
+    h_out = torch.empty((n, sh.H), device=DEV, dtype=dt)
+    R.run_layer(rec, dW, plans.record(0, total, total, None if all_rows else kp, None if all_rows else vp),
+                h_in, h_out, kc, vc, ws)
+    torch.cuda.synchronize()
+
+    off = vlc.vlc_layer_workspace_layout(rec, n)
+    shapes = {"xn": (n, sh.H), "qkv": (n, sh.n_qkv), "q": (n, sh.Hq * sh.D), "o": (n, sh.Hq * sh.D),
+              "h1": (n, sh.H), "n2": (n, sh.H), "act": (n, sh.I)}
+    sel = np.unique(np.concatenate([np.arange(0, n, 13), [n - 1]]))
+    sel_t = torch.from_numpy(sel).to(DEV)
+
+    def ws_rows(name):
+        tdt, size = (torch.float32, 4) if name == "qkv" else (dt, 2)
+        shp = shapes[name]
+        return back(ws.t[off[name]:off[name] + shp[0] * shp[1] * size].view(tdt).reshape(shp)[sel_t])
+
+    slots = plans.host["slot"][0, :n].astype(np.int64)
+    forced = {name: ws_rows(name) for name in ("xn", "qkv", "h1", "n2", "act")}
+    forced["q"] = ws_rows("q").reshape(len(sel), sh.Hq, sh.D)
+    forced["o"] = ws_rows("o").reshape(len(sel), sh.Hq, sh.D)
+    gK, gV = back(kc), back(vc)
+    forced["K"], forced["V"] = gK, gV
+    x = st(emb)[slots[sel]]
+    r = orc.layer_stages(sh, W, x, slots[sel], orc.positions_of(req, slots[sel]), gK.copy(), gV.copy(), st, forced=forced)
+    assert_close(forced["xn"], r["xn"], sh.dtype, "xn")
+    assert_close(forced["qkv"], r["qkv"], sh.dtype, "qkv")
+    assert_close(forced["q"], r["q"], sh.dtype, "q")
+    assert_close(forced["o"], r["o"], sh.dtype, "attention")
+    assert_close(forced["h1"], r["h1"], sh.dtype, "h1 (o-proj + residual)")
+    assert_close(forced["n2"], r["n2"], sh.dtype, "n2")
+    assert_close(forced["act"], r["act"], sh.dtype, "act (gate|up + SwiGLU)")
+    assert_close(back(h_out[sel_t]), r["h2"], sh.dtype, "h_out (down-proj + residual)")
