@@ -258,6 +258,57 @@ def linear(x, w, b=None):
     return y
 
 
+def route_top_k(logits, top_k):
+    """Expert choice of a mixture-of-experts MLP: softmax over all experts, the top_k most probable
+    (equal values: the lower expert index first), their probabilities renormalised to sum 1.
+    logits [n, E] -> (idx [n, top_k] in order of decreasing probability, weight [n, top_k])."""
+    logits = np.asarray(logits, dtype=np.float64)
+    z = logits - np.max(logits, axis=1, keepdims=True)
+    p = np.exp(z)
+    p = p / np.sum(p, axis=1, keepdims=True)
+    idx = np.argsort(-p, axis=1, kind="stable")[:, :top_k]          # stable: ties keep index order
+    w = np.take_along_axis(p, idx, axis=1)
+    return idx.astype(np.int64), w / np.sum(w, axis=1, keepdims=True)
+
+
+def moe_mlp(shape, W, n2, store, forced=None):
+    """Mixture-of-experts SwiGLU MLP of the normed rows n2 [n, H] (without the residual).
+
+    reading (the paper's Qwen3-VL-30B-A3B model; it does not restate the block): router scores
+    n2 . w_router^T, expert choice by route_top_k, every chosen expert e applies its own SwiGLU MLP
+    (w_gate_up[e] rows: gate then up; w_down[e]) and the results are summed with the renormalised
+    probabilities as weights.
+    reading (storage rounding): router scores, probabilities and weights stay unrounded floats; the
+    SwiGLU product and each expert's output row are tensors of the storage type; the weighted sum
+    is formed in float.
+    Returns dict: moe_idx [n, k], moe_w [n, k], act [n, k, I], y [n, k, H], mlp [n, H] (float sum).
+    forced: optional moe_idx / moe_w / act / y to feed to the following step instead.
+    """
+    forced = forced or {}
+    fed = lambda name, value: np.asarray(forced[name]) if name in forced else value
+    n2 = np.asarray(n2, dtype=np.float64)
+    n, k, I = n2.shape[0], shape.top_k, shape.I
+    r = {}
+    r["moe_idx"], r["moe_w"] = route_top_k(linear(n2, W["w_router"]), k)
+    idx = fed("moe_idx", r["moe_idx"]).astype(np.int64)
+    wts = np.asarray(fed("moe_w", r["moe_w"]), dtype=np.float64)
+    act = np.zeros((n, k, I), dtype=np.float64)
+    for e in np.unique(idx):
+        rows, j = np.nonzero(idx == e)
+        gu = linear(n2[rows], W["w_gate_up"][e])
+        act[rows, j] = store(silu(gu[:, :I]) * gu[:, I:])
+    r["act"] = act
+    act = np.asarray(fed("act", act), dtype=np.float64)
+    y = np.zeros((n, k, shape.H), dtype=np.float64)
+    for e in np.unique(idx):
+        rows, j = np.nonzero(idx == e)
+        y[rows, j] = store(linear(act[rows, j], W["w_down"][e]))
+    r["y"] = y
+    y = np.asarray(fed("y", y), dtype=np.float64)
+    r["mlp"] = np.einsum("nk,nkh->nh", wts, y)
+    return r
+
+
 STAGES = ("xn", "qkv", "q", "K", "V", "o", "h1", "n2", "act", "h2")
 
 
@@ -313,6 +364,11 @@ def layer_stages(shape, W, x, slots, pos, K, V, store, forced=None):
     r["h1"] = store(x + linear(fed("o", r["o"]).reshape(n, Hq * D), W["w_o"]))
     h1 = fed("h1", r["h1"])
     r["n2"] = store(rmsnorm(h1, W["w_ln2"], shape.eps))
+    if W.get("w_router") is not None:
+        m = moe_mlp(shape, W, fed("n2", r["n2"]), store, forced)
+        r.update({name: m[name] for name in ("moe_idx", "moe_w", "act", "y")})
+        r["h2"] = store(h1 + m["mlp"])
+        return r
     gu = linear(fed("n2", r["n2"]), W["w_gate_up"])
     r["act"] = store(silu(gu[:, :shape.I]) * gu[:, shape.I:])
     r["h2"] = store(h1 + linear(fed("act", r["act"]), W["w_down"]))

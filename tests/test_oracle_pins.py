@@ -2,6 +2,7 @@
 
 Each test names what it pins and the passage of the paper (arxiv 2512.12977) that fixes it.
 """
+import dataclasses
 import itertools
 import math
 
@@ -639,3 +640,119 @@ def test_planner_weights_early_layers_on_benchmark_table():
     k = orc.plan_layer_rates(sens, 700)
     assert feasible(k, 700, 150) and int(k.sum()) == 700
     assert k[0] > k[-1]
+
+
+# ---- mixture-of-experts MLP (Qwen3-VL-30B-A3B-shaped layer) -----------------------------------
+
+def test_route_top_k_by_hand():
+    """Scores 0, ln 2, ln 4 -> probabilities 1/7, 2/7, 4/7; the two largest renormalised are 2/3 and 1/3."""
+    idx, w = orc.route_top_k(np.array([[0.0, np.log(2.0), np.log(4.0)], [np.log(4.0), 0.0, np.log(2.0)]]), 2)
+    np.testing.assert_array_equal(idx, [[2, 1], [0, 2]])
+    np.testing.assert_allclose(w, [[2 / 3, 1 / 3], [2 / 3, 1 / 3]], rtol=1e-15)
+    # equal scores: the lower expert index comes first
+    idx, w = orc.route_top_k(np.array([[1.0, 3.0, 3.0, 1.0, 3.0]]), 2)
+    np.testing.assert_array_equal(idx, [[1, 2]])
+    np.testing.assert_allclose(w, [[0.5, 0.5]])
+    # top_k = all experts: the weights are the softmax itself
+    z = np.random.default_rng(0).standard_normal((4, 6))
+    idx, w = orc.route_top_k(z, 6)
+    p = np.exp(z) / np.exp(z).sum(1, keepdims=True)
+    np.testing.assert_allclose(w, np.take_along_axis(p, idx, 1), rtol=1e-14)
+    assert np.all(np.diff(w, axis=1) <= 0)
+
+
+def moe_setup(n=37):
+    shape = syn.SHAPES["tiny_moe"]
+    W = syn.layer_weights(shape, 51, 0)
+    n2 = np.random.default_rng(52).standard_normal((n, shape.H))
+    return shape, W, n2
+
+
+def test_moe_block_vs_transformers():
+    from transformers.models.qwen3_vl_moe.modeling_qwen3_vl_moe import Qwen3VLMoeTextConfig, Qwen3VLMoeTextSparseMoeBlock
+    shape, W, n2 = moe_setup()
+    cfg = Qwen3VLMoeTextConfig(hidden_size=shape.H, moe_intermediate_size=shape.I, num_experts=shape.n_experts,
+                               num_experts_per_tok=shape.top_k, hidden_act="silu")
+    blk = Qwen3VLMoeTextSparseMoeBlock(cfg).double()
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    with torch.no_grad():
+        blk.gate.weight.copy_(t(W["w_router"]))
+        blk.experts.gate_up_proj.copy_(t(W["w_gate_up"]))
+        blk.experts.down_proj.copy_(t(W["w_down"]))
+        ref = blk(t(n2)[None])[0].numpy()
+        _, ref_w, ref_idx = blk.gate(t(n2))
+    got = orc.moe_mlp(shape, W, n2, orc.store_exact)
+    np.testing.assert_array_equal(np.sort(got["moe_idx"], 1), np.sort(ref_idx.numpy(), 1))
+    np.testing.assert_allclose(np.sort(got["moe_w"], 1), np.sort(ref_w.numpy(), 1), rtol=1e-6)   # the library's softmax is float32
+    np.testing.assert_allclose(got["mlp"], ref, atol=1e-8, rtol=1e-6)
+    assert len(np.unique(got["moe_idx"])) == shape.n_experts          # the sample exercises every expert
+    # without the renormalisation, or with gate and up swapped, the result moves
+    raw = orc.route_top_k(orc.linear(n2, W["w_router"]), shape.n_experts)
+    p_sel = np.stack([raw[1][i][np.isin(raw[0][i], got["moe_idx"][i])] for i in range(len(n2))])
+    unnorm = orc.moe_mlp(shape, W, n2, orc.store_exact, forced={"moe_w": p_sel})
+    assert np.max(np.abs(unnorm["mlp"] - ref)) > 1e-3
+    swapped = dict(W, w_gate_up=np.concatenate([W["w_gate_up"][:, shape.I:], W["w_gate_up"][:, :shape.I]], axis=1))
+    assert np.max(np.abs(orc.moe_mlp(shape, swapped, n2, orc.store_exact)["mlp"] - ref)) > 1e-3
+
+
+def test_moe_with_identical_experts_is_the_dense_mlp():
+    """The weights sum to one, so experts that all hold the same matrices give the ordinary SwiGLU MLP,
+    whatever the router does."""
+    shape, W, n2 = moe_setup()
+    same = dict(W, w_gate_up=np.repeat(W["w_gate_up"][:1], shape.n_experts, 0), w_down=np.repeat(W["w_down"][:1], shape.n_experts, 0))
+    got = orc.moe_mlp(shape, same, n2, orc.store_exact)["mlp"]
+    gu = n2 @ W["w_gate_up"][0].T.astype(np.float64)
+    dense = (torch.nn.functional.silu(torch.from_numpy(gu[:, :shape.I])).numpy() * gu[:, shape.I:]) @ W["w_down"][0].T.astype(np.float64)
+    np.testing.assert_allclose(got, dense, atol=1e-12, rtol=1e-10)
+    # one expert per token and a router that can only pick expert 3: that expert's MLP alone
+    one = dataclasses.replace(shape, top_k=1)
+    router = np.zeros_like(W["w_router"])
+    router[3] = 1.0
+    pos = np.abs(n2)                                                 # positive rows: expert 3's score is the largest
+    got = orc.moe_mlp(one, dict(W, w_router=router), pos, orc.store_exact)
+    assert np.all(got["moe_idx"] == 3) and np.all(got["moe_w"] == 1.0)
+    gu = pos @ W["w_gate_up"][3].T.astype(np.float64)
+    want = (torch.nn.functional.silu(torch.from_numpy(gu[:, :shape.I])).numpy() * gu[:, shape.I:]) @ W["w_down"][3].T.astype(np.float64)
+    np.testing.assert_allclose(got["mlp"], want, atol=1e-12, rtol=1e-10)
+
+
+def test_full_prefill_moe_layer_vs_transformers():
+    """Oracle layer (q/k norm, 3-axis positions, mixture-of-experts MLP) against the library's Qwen3-VL-MoE text decoder layer (fp64)."""
+    from transformers.models.qwen3_vl_moe.modeling_qwen3_vl_moe import (Qwen3VLMoeTextConfig, Qwen3VLMoeTextDecoderLayer,
+                                                                        Qwen3VLMoeTextRotaryEmbedding)
+    _, req, _, emb = q3_setup(d=3)
+    shape = syn.SHAPES["tiny_moe"]
+    W = syn.layer_weights(shape, 53, 0)
+    S = emb.shape[0]
+    cfg = Qwen3VLMoeTextConfig(hidden_size=shape.H, num_attention_heads=shape.Hq, num_key_value_heads=shape.Hkv,
+                               head_dim=shape.D, moe_intermediate_size=shape.I, num_experts=shape.n_experts,
+                               num_experts_per_tok=shape.top_k, num_hidden_layers=1, rms_norm_eps=shape.eps,
+                               vocab_size=8, max_position_embeddings=4096, attention_bias=False, hidden_act="silu",
+                               rope_parameters={"rope_type": "default", "rope_theta": shape.rope_base,
+                                                "mrope_section": list(shape.mrope_section)})
+    cfg._attn_implementation = "eager"
+    layer = Qwen3VLMoeTextDecoderLayer(cfg, 0).double()
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    Hq, Hkv, D = shape.Hq, shape.Hkv, shape.D
+    with torch.no_grad():
+        wq, wk, wv = np.split(W["w_qkv"], [Hq * D, (Hq + Hkv) * D], axis=0)
+        layer.self_attn.q_proj.weight.copy_(t(wq))
+        layer.self_attn.k_proj.weight.copy_(t(wk))
+        layer.self_attn.v_proj.weight.copy_(t(wv))
+        layer.self_attn.o_proj.weight.copy_(t(W["w_o"]))
+        layer.self_attn.q_norm.weight.copy_(t(W["w_qnorm"]))
+        layer.self_attn.k_norm.weight.copy_(t(W["w_knorm"]))
+        layer.mlp.gate.weight.copy_(t(W["w_router"]))
+        layer.mlp.experts.gate_up_proj.copy_(t(W["w_gate_up"]))
+        layer.mlp.experts.down_proj.copy_(t(W["w_down"]))
+        layer.input_layernorm.weight.copy_(t(W["w_ln1"]))
+        layer.post_attention_layernorm.weight.copy_(t(W["w_ln2"]))
+        x = t(emb)[None]
+        pos = torch.from_numpy(req.pos3.T.copy())[:, None, :]
+        cos, sin = Qwen3VLMoeTextRotaryEmbedding(cfg)(x, pos)
+        mask = torch.full((S, S), float("-inf"), dtype=torch.float64).triu(1)[None, None]
+        ref = layer(x, attention_mask=mask, position_ids=pos, position_embeddings=(cos.double(), sin.double()))
+        ref = (ref[0] if isinstance(ref, tuple) else ref)
+        ref = ref[0].numpy() if ref.dim() == 3 else ref.numpy()
+    got = orc.full_prefill(shape, [W], emb, req, orc.store_exact)[0]["h"]
+    np.testing.assert_allclose(got, ref, atol=2e-6, rtol=0)

@@ -33,6 +33,8 @@ class Shape:
     vocab: int = 512  # rows of the output (LM head) matrix
     qk_norm: bool = False                 # per-head RMSNorm of q and k before RoPE (Qwen3 family)
     mrope_section: tuple = ()             # (t, h, w) frequency counts of 3-axis RoPE; () = 1-D RoPE
+    n_experts: int = 0                    # > 0: mixture-of-experts MLP; I is then the width of ONE expert
+    top_k: int = 0                        # experts per token
 
     @property
     def g(self) -> int:
@@ -57,6 +59,14 @@ SHAPES: Dict[str, Shape] = {
                           dtype="bf16", qkv_bias=False, qk_norm=True, mrope_section=(24, 20, 20)),
     "q3vl_8b": Shape("q3vl_8b", L=36, H=4096, Hq=32, Hkv=8, D=128, I=12288, rope_base=5e6,
                      dtype="bf16", qkv_bias=False, vocab=151936, qk_norm=True, mrope_section=(24, 20, 20)),
+    # mixture-of-experts MLP on top of the Qwen3-VL-shaped attention
+    "tiny_moe": Shape("tiny_moe", L=2, H=256, Hq=4, Hkv=2, D=64, I=128, rope_base=1e4, dtype="f32", qkv_bias=False,
+                      qk_norm=True, mrope_section=(12, 10, 10), n_experts=8, top_k=2),
+    "tiny_moe_bf16": Shape("tiny_moe_bf16", L=2, H=256, Hq=4, Hkv=2, D=128, I=128, rope_base=1e4, dtype="bf16",
+                           qkv_bias=False, qk_norm=True, mrope_section=(24, 20, 20), n_experts=8, top_k=2),
+    "q3vl_30b_a3b": Shape("q3vl_30b_a3b", L=48, H=2048, Hq=32, Hkv=4, D=128, I=768, rope_base=5e6, dtype="bf16",
+                          qkv_bias=False, vocab=151936, qk_norm=True, mrope_section=(24, 20, 20), n_experts=128,
+                          top_k=8),
     "7b": Shape("7b", L=28, H=3584, Hq=28, Hkv=4, D=128, I=18944, rope_base=1e6,
                 dtype="bf16", qkv_bias=True, vocab=152064),
     "72b": Shape("72b", L=80, H=8192, Hq=64, Hkv=8, D=128, I=29568, rope_base=1e6,
@@ -251,10 +261,14 @@ def layer_weights(shape: Shape, seed: int, layer: int) -> Dict[str, Optional[np.
 
     w_qkv rows: q heads, then k heads, then v heads.  w_gate_up rows: gate (I rows) then up (I rows).
     Linear weights ~ N(0, 0.02^2); norm weights 1 + N(0, 0.02^2); qkv bias N(0, 0.02^2) or None.
+    Mixture-of-experts shapes: w_gate_up [E, 2I, H], w_down [E, H, I] and the router matrix
+    w_router [E, H] ~ N(0, 0.02^2) (else w_router is None).
     """
-    H, I, nq = shape.H, shape.I, shape.n_qkv
+    H, I, nq, E = shape.H, shape.I, shape.n_qkv, shape.n_experts
     sizes = {"w_ln1": (H,), "w_qkv": (nq, H), "b_qkv": (nq,), "w_o": (H, shape.Hq * shape.D),
              "w_ln2": (H,), "w_gate_up": (2 * I, H), "w_down": (H, I)}
+    if E:
+        sizes["w_gate_up"], sizes["w_down"] = (E, 2 * I, H), (E, H, I)
     out: Dict[str, Optional[np.ndarray]] = {}
     for t, nm in enumerate(WEIGHT_NAMES):
         if nm == "b_qkv" and not shape.qkv_bias:
@@ -267,6 +281,7 @@ def layer_weights(shape: Shape, seed: int, layer: int) -> Dict[str, Optional[np.
         out[nm] = w
     for t, nm in enumerate(QK_NORM_NAMES):
         out[nm] = (normal_f32([seed, 1000 + layer, 100 + t], shape.D, 0.02) + np.float32(1.0)) if shape.qk_norm else None
+    out["w_router"] = normal_f32([seed, 1000 + layer, 200], E * H, 0.02).reshape(E, H) if E else None
     return out
 
 
