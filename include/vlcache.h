@@ -189,6 +189,12 @@ typedef struct {
    * the temporal id the rest.  All three 0: ordinary 1-D RoPE (plan->pos).  Otherwise the ids of
    * the recomputed rows come from plan->pos3. */
   int32_t mrope_t, mrope_h, mrope_w;
+  /* Mixture-of-experts MLP (the Qwen3-VL-30B-A3B model of Sec. 5.1): n_experts > 0 replaces the MLP
+   * by n_experts SwiGLU experts of width I each, of which every row uses top_k (1 <= top_k <= 16,
+   * n_experts <= 256): router scores row . w_router^T, the top_k largest (equal scores: lower index
+   * first), weights = softmax over all experts renormalised over the chosen ones; the experts'
+   * output rows are rounded to the storage type and summed in float.  0: one dense MLP. */
+  int32_t n_experts, top_k;
 } vlc_layer_shape;
 
 typedef struct {              /* device pointers; b_qkv may be NULL (no bias) */
@@ -201,6 +207,8 @@ typedef struct {              /* device pointers; b_qkv may be NULL (no bias) */
   const void* w_down;         /* [H, I] */
   const void* w_qnorm;        /* [D] or NULL: RMSNorm weight applied to every q head before RoPE (Qwen3 family) */
   const void* w_knorm;        /* [D] or NULL: the same for every k head; both or neither */
+  const void* w_router;       /* [n_experts, H] when n_experts > 0 (then w_gate_up is [n_experts, 2I, H] and
+                                 w_down [n_experts, H, I]), else ignored */
 } vlc_layer_weights;
 
 typedef struct {
@@ -234,9 +242,13 @@ int64_t vlc_layer_workspace_bytes(const vlc_layer_shape* shape, int64_t n_rows_m
  * layer in place).  offsets (host, [VLC_WS_FIELDS]): input-normed rows [n,H]; q|k|v projection
  * before RoPE as float [n,(Hq+2Hkv)D]; rotated queries [n,Hq,D]; attention output [n,Hq,D];
  * hidden after the attention residual [n,H]; post-attention-normed rows [n,H]; SwiGLU product
- * [n,I].  All but the second have the layer's storage type.
+ * [n,I].  All but the second have the layer's storage type.  With experts the seventh is
+ * [n*top_k, I] in grouped order and six more follow: chosen experts [n,top_k] int32, their weights
+ * [n,top_k] float, position of every (row, choice) pair in the grouped order [n,top_k] int32, the
+ * experts' output rows [n*top_k, H] (storage type, grouped order), router scores [n, n_experts]
+ * float, first pair of every expert [n_experts + 1] int32.  Without experts these six are -1.
  */
-#define VLC_WS_FIELDS 7
+#define VLC_WS_FIELDS 13
 int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t n_rows, int64_t* offsets);
 
 /*
@@ -247,6 +259,7 @@ int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t n_rows, int
  *   K/V: reused image tokens placed (keys rotated by reuse_delta), then K[slot]=k, V[slot]=v
  *   a  = attention of the n rows over K/V[row_kv_start : row_kv_start + row_kv_len)
  *   h1 = x + a Wo^T ;  h_out = h1 + (silu(n2 Wg^T) * (n2 Wu^T)) Wd^T,  n2 = RMSNorm(h1)
+ *        (with experts: h_out = h1 + sum over the row's top_k experts of weight * that expert's MLP)
  * h_in [n_in, H], h_out [n, H] (must not alias h_in), k_cache/v_cache [kv_rows, Hkv, D] updated
  * in place.  Storage rounding for VLC_BF16: normed activations, v after bias, q and k after
  * RoPE (rounded once: the projection is rotated as float), attention output, both residual sums

@@ -26,12 +26,13 @@ class Segment(C.Structure):
 class LayerShape(C.Structure):
     _fields_ = [("H", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32), ("I", C.c_int32),
                 ("dtype", C.c_int32), ("eps", C.c_float), ("rope_base", C.c_double),
-                ("mrope_t", C.c_int32), ("mrope_h", C.c_int32), ("mrope_w", C.c_int32)]
+                ("mrope_t", C.c_int32), ("mrope_h", C.c_int32), ("mrope_w", C.c_int32),
+                ("n_experts", C.c_int32), ("top_k", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down",
-                                          "w_qnorm", "w_knorm")]
+                                          "w_qnorm", "w_knorm", "w_router")]
 
 
 class LayerPlan(C.Structure):
@@ -209,7 +210,8 @@ def vlc_layer_workspace_bytes(shape: LayerShape, n_rows_max: int) -> int:
     return int(b)
 
 
-WS_FIELDS = ("xn", "qkv", "q", "o", "h1", "n2", "act")
+WS_FIELDS = ("xn", "qkv", "q", "o", "h1", "n2", "act", "moe_idx", "moe_w", "moe_pos", "moe_y", "moe_logits",
+             "moe_offset")
 
 
 def vlc_layer_workspace_layout(shape: LayerShape, n_rows: int) -> dict:

@@ -89,12 +89,18 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_byte_addr) 
 
 enum { EPI_PARTIAL = 100 };   // internal: float partial sums of one k-range (split-K)
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int OCC, int EPI>
+//
+// GROUPED (mixture-of-experts): the row tiles come from a device-resident table; entry t holds an
+// expert and the range [m0, m_end) of rows it owns (at most BM of them); the tile multiplies these
+// rows - fetched through amap when given - with that expert's matrix W + expert * w_stride.
+// Workgroups beyond the table's length (only known on the device) exit at once.
+template <int BM, int BN, int WGM, int WGN, int STAGES, int OCC, int EPI, bool GROUPED = false>
 __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
     const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ W, uint16_t* __restrict__ C,
     int64_t ldc, int M, int N, int K, const uint16_t* __restrict__ bias, const uint16_t* __restrict__ resid,
     int64_t ldr, const int32_t* __restrict__ rmap, int tiles_m, int tiles_n, int kt_per_split, int full_tiles,
-    int tail_splits, float* __restrict__ tail_ws) {
+    int tail_splits, float* __restrict__ tail_ws, const GroupTile* __restrict__ gtab,
+    const int32_t* __restrict__ g_ntiles, const int32_t* __restrict__ amap, int64_t w_stride) {
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;      // wavefront tile
   constexpr int MT = WM / 32, NT = WN / 32;        // MFMA tiles per wavefront
@@ -123,7 +129,15 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   }
   int tm, tn;
   tile_coords(pid, tiles, tiles_m, tiles_n, &tm, &tn);
-  const int m0 = tm * BM, n0 = tn * CN;
+  int m0 = tm * BM;
+  const int n0 = tn * CN;
+  if constexpr (GROUPED) {
+    if (tm >= *g_ntiles) return;
+    const GroupTile g = gtab[tm];
+    m0 = g.m0;
+    M = g.m_end;
+    W += (int64_t)g.expert * w_stride;
+  }
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -143,6 +157,9 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
     const int r = p >> 3, c = (p & 7) ^ fswz(r);
     int gr = m0 + r;
     gr = gr < M ? gr : M - 1;                              // ragged tail: re-read the last row
+    if constexpr (GROUPED) {
+      if (amap) gr = amap[gr];
+    }
     a_src[i] = A + (int64_t)gr * lda + (int64_t)kt_begin * BK + c * 8;
   }
 #pragma unroll
@@ -428,25 +445,40 @@ __global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restric
 // ---------------------------------------------------------------------------------------------
 // f32 SIMT kernel: 64 x 64 tile, 256 threads, 4 x 4 outputs per thread, k-tile 16
 // ---------------------------------------------------------------------------------------------
-template <int EPI>
+template <int EPI, bool GROUPED = false>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, int64_t lda,
                                                        const float* __restrict__ W, float* __restrict__ C,
                                                        int64_t ldc, int M, int N, int K,
                                                        const float* __restrict__ bias,
                                                        const float* __restrict__ resid, int64_t ldr,
-                                                       const int32_t* __restrict__ rmap) {
+                                                       const int32_t* __restrict__ rmap,
+                                                       const GroupTile* __restrict__ gtab,
+                                                       const int32_t* __restrict__ g_ntiles,
+                                                       const int32_t* __restrict__ amap, int64_t w_stride) {
   constexpr int T = 64, KB = 16;
   constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
   __shared__ float As[KB][T + 1];
   __shared__ float Ws[NW][KB][T + 1];
-  const int m0 = blockIdx.y * T, n0 = blockIdx.x * T;
+  int m0 = blockIdx.y * T;
+  const int n0 = blockIdx.x * T;
+  if constexpr (GROUPED) {       // see gemm_bf16_kernel
+    if ((int)blockIdx.y >= *g_ntiles) return;
+    const GroupTile g = gtab[blockIdx.y];
+    m0 = g.m0;
+    M = g.m_end;
+    W += (int64_t)g.expert * w_stride;
+  }
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   float acc[NW][4][4] = {};
   for (int k0 = 0; k0 < K; k0 += KB) {
     for (int e = threadIdx.x; e < T * KB; e += 256) {
       const int r = e / KB, kk = e % KB;
       const int m = m0 + r, n = n0 + r, k = k0 + kk;
-      As[kk][r] = (m < M && k < K) ? A[(int64_t)m * lda + k] : 0.f;
+      int64_t am = m;
+      if constexpr (GROUPED) {
+        if (amap && m < M) am = amap[m];
+      }
+      As[kk][r] = (m < M && k < K) ? A[am * lda + k] : 0.f;
       Ws[0][kk][r] = (n < N && k < K) ? W[(int64_t)n * K + k] : 0.f;
       if (EPI == EPI_SWIGLU) Ws[NW - 1][kk][r] = (n < N && k < K) ? W[(int64_t)(N + n) * K + k] : 0.f;
     }
@@ -530,7 +562,8 @@ int launch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
   }
   hipLaunchKernelGGL(kern, dim3(full + tail * tsp), dim3(WGM * WGN * 64), lds, st, (const uint16_t*)A, lda,
                      (const uint16_t*)W, (uint16_t*)C, ldc, (int)M, (int)N, (int)K, (const uint16_t*)bias,
-                     (const uint16_t*)resid, ldr, rmap, tiles_m, tiles_n, tkt, full, tsp, (float*)tail_ws);
+                     (const uint16_t*)resid, ldr, rmap, tiles_m, tiles_n, tkt, full, tsp, (float*)tail_ws,
+                     (const GroupTile*)nullptr, (const int32_t*)nullptr, (const int32_t*)nullptr, (int64_t)0);
   VLC_CHECK_LAUNCH("gemm_bf16");
   if constexpr (EPI != EPI_PARTIAL) {
     if (tail > 0) {
@@ -603,8 +636,44 @@ int launch_f32(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, 
   const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
   hipLaunchKernelGGL(gemm_f32_kernel<EPI>, grid, dim3(256), 0, st, (const float*)A, lda, (const float*)W,
                      (float*)C, ldc, (int)M, (int)N, (int)K, (const float*)bias, (const float*)resid, ldr,
-                     rmap);
+                     rmap, (const GroupTile*)nullptr, (const int32_t*)nullptr, (const int32_t*)nullptr, (int64_t)0);
   VLC_CHECK_LAUNCH("gemm_f32");
+  return VLC_OK;
+}
+
+// Grouped launches: the grid covers the largest number of row tiles the table can hold.
+template <int BM, int BN, int WGM, int WGN, int STAGES, int OCC, int EPI>
+int launch_bf16_grouped(const void* A, int64_t lda, const int32_t* amap, const void* W, int64_t w_stride, void* C,
+                        int64_t ldc, int64_t N, int64_t K, const GroupTile* gtab, const int32_t* g_ntiles,
+                        int max_tiles_m, hipStream_t st) {
+  constexpr int CN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  const int tiles_n = (int)((N + CN - 1) / CN);
+  const size_t lds = (size_t)STAGES * (BM + BN) * BK * 2;
+  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, STAGES, OCC, EPI, true>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    VLC_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  const int grid = max_tiles_m * tiles_n;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), lds, st, (const uint16_t*)A, lda, (const uint16_t*)W,
+                     (uint16_t*)C, ldc, 0, (int)N, (int)K, (const uint16_t*)nullptr, (const uint16_t*)nullptr,
+                     (int64_t)0, (const int32_t*)nullptr, max_tiles_m, tiles_n, (int)(K / BK), grid, 1,
+                     (float*)nullptr, gtab, g_ntiles, amap, w_stride);
+  VLC_CHECK_LAUNCH("gemm_bf16_grouped");
+  return VLC_OK;
+}
+
+template <int EPI>
+int launch_f32_grouped(const void* A, int64_t lda, const int32_t* amap, const void* W, int64_t w_stride, void* C,
+                       int64_t ldc, int64_t N, int64_t K, const GroupTile* gtab, const int32_t* g_ntiles,
+                       int max_tiles_m, hipStream_t st) {
+  const dim3 grid((unsigned)((N + 63) / 64), (unsigned)max_tiles_m);
+  hipLaunchKernelGGL((gemm_f32_kernel<EPI, true>), grid, dim3(256), 0, st, (const float*)A, lda, (const float*)W,
+                     (float*)C, ldc, 0, (int)N, (int)K, (const float*)nullptr, (const float*)nullptr, (int64_t)0,
+                     (const int32_t*)nullptr, gtab, g_ntiles, amap, w_stride);
+  VLC_CHECK_LAUNCH("gemm_f32_grouped");
   return VLC_OK;
 }
 
@@ -616,6 +685,43 @@ int launch_f32(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, 
 int64_t gemm_splitk_ws_bytes(int64_t n_rows, int64_t max_n) {
   (void)max_n;
   return n_rows > 0 ? (int64_t)64 << 20 : 0;
+}
+
+int gemm_group_tile_rows(int64_t rows, int n_groups, int dtype) {
+  if (dtype != VLC_BF16) return 64;
+  return rows / (n_groups > 0 ? n_groups : 1) >= 192 ? 256 : 128;
+}
+
+int launch_gemm_grouped(const void* A, int64_t lda, const int32_t* amap, const void* W, int64_t w_stride, void* C,
+                        int64_t ldc, int64_t rows, int n_groups, int64_t N, int64_t K, int epilogue,
+                        const GroupTile* tiles, const int32_t* n_tiles, int tile_rows, int dtype, hipStream_t st) {
+  if (rows <= 0 || N <= 0) return VLC_OK;
+  if (K <= 0 || n_groups <= 0) return fail(VLC_ERR_SHAPE, "grouped gemm: K=%lld groups=%d", (long long)K, n_groups);
+  if (rows > INT32_MAX || N > INT32_MAX / 2 || K > INT32_MAX)
+    return fail(VLC_ERR_SHAPE, "grouped gemm: dimension exceeds 32-bit tile indexing");
+  if (tile_rows != gemm_group_tile_rows(rows, n_groups, dtype))
+    return fail(VLC_ERR_SHAPE, "grouped gemm: the tile table was built for %d rows per tile", tile_rows);
+  const int max_tiles = (int)(rows / tile_rows) + n_groups;
+  if (epilogue != EPI_BIAS && epilogue != EPI_SWIGLU)
+    return fail(VLC_ERR_SHAPE, "grouped gemm: epilogue=%d", epilogue);
+  if (dtype == VLC_BF16) {
+    if (K % BK || N % 4 || lda % 8 || ldc % 4)
+      return fail(VLC_ERR_SHAPE, "grouped gemm(bf16): K=%lld must be a multiple of %d, N, lda, ldc aligned", (long long)K, BK);
+    if (tile_rows == 256) {
+      if (epilogue == EPI_SWIGLU)
+        return launch_bf16_grouped<256, 256, 2, 2, 2, 1, EPI_SWIGLU>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
+      return launch_bf16_grouped<256, 256, 2, 2, 2, 1, EPI_BIAS>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
+    }
+    if (epilogue == EPI_SWIGLU)
+      return launch_bf16_grouped<128, 128, 2, 2, 2, 2, EPI_SWIGLU>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
+    return launch_bf16_grouped<128, 128, 2, 2, 2, 2, EPI_BIAS>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
+  }
+  if (dtype == VLC_F32) {
+    if (epilogue == EPI_SWIGLU)
+      return launch_f32_grouped<EPI_SWIGLU>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
+    return launch_f32_grouped<EPI_BIAS>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
+  }
+  return fail(VLC_ERR_DTYPE, "grouped gemm: dtype=%d", dtype);
 }
 
 int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,

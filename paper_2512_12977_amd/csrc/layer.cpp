@@ -12,6 +12,8 @@ inline int64_t align256(int64_t b) { return (b + 255) & ~(int64_t)255; }
 
 struct Workspace {
   int64_t xn, qkv32, q, attn, h1, n2, act, splitk, splitk_bytes, att, att_bytes, total;   // byte offsets
+  // mixture-of-experts only (-1 otherwise)
+  int64_t moe_idx, moe_w, moe_pos, moe_y, moe_logits, moe_offset, moe_rank, moe_count, moe_tiles, moe_ntiles, moe_row;
 };
 
 Workspace layout(const vlc_layer_shape& s, int64_t n) {
@@ -25,7 +27,24 @@ Workspace layout(const vlc_layer_shape& s, int64_t n) {
   w.attn = at; at += align256(n * (int64_t)s.Hq * s.D * es);
   w.h1 = at;   at += align256(n * s.H * es);          // hidden after the attention residual
   w.n2 = at;   at += align256(n * s.H * es);          // post-attention-normed activations
-  w.act = at;  at += align256(n * (int64_t)s.I * es); // SwiGLU product
+  const int64_t pairs = s.n_experts > 0 ? n * s.top_k : n;
+  w.act = at;  at += align256(pairs * (int64_t)s.I * es); // SwiGLU product (per (row, expert) pair with experts)
+  w.moe_idx = w.moe_w = w.moe_pos = w.moe_y = w.moe_logits = w.moe_offset = -1;
+  w.moe_rank = w.moe_count = w.moe_tiles = w.moe_ntiles = w.moe_row = -1;
+  if (s.n_experts > 0) {
+    const int64_t E = s.n_experts;
+    w.moe_idx = at;    at += align256(pairs * 4);
+    w.moe_w = at;      at += align256(pairs * 4);
+    w.moe_pos = at;    at += align256(pairs * 4);
+    w.moe_y = at;      at += align256(pairs * (int64_t)s.H * es);
+    w.moe_logits = at; at += align256(n * E * 4);
+    w.moe_offset = at; at += align256((E + 1) * 4);
+    w.moe_rank = at;   at += align256(pairs * 4);
+    w.moe_count = at;  at += align256(E * 4);
+    w.moe_tiles = at;  at += align256((pairs / 64 + E + 1) * (int64_t)sizeof(vlc::GroupTile));   // 64: smallest tile
+    w.moe_ntiles = at; at += 256;
+    w.moe_row = at;    at += align256(pairs * 4);
+  }
   w.splitk = at;                                      // float partials of split-K GEMMs and of tail tiles
   w.splitk_bytes = s.dtype == VLC_BF16 ? vlc::gemm_splitk_ws_bytes(n, nqkv) : 0;
   at += align256(w.splitk_bytes);
@@ -50,6 +69,9 @@ int check_shape(const vlc_layer_shape* s, const char* who) {
       ((s->mrope_t | s->mrope_h | s->mrope_w) != 0 && s->mrope_t + s->mrope_h + s->mrope_w != s->D / 2))
     return fail(VLC_ERR_SHAPE, "%s: 3-axis RoPE sections %d+%d+%d must add up to D/2 = %d", who, s->mrope_t,
                 s->mrope_h, s->mrope_w, s->D / 2);
+  if (s->n_experts < 0 || s->top_k < 0 || (s->n_experts > 0 && (s->n_experts > 256 || s->top_k < 1 || s->top_k > 16 ||
+                                                               s->top_k > s->n_experts)))
+    return fail(VLC_ERR_SHAPE, "%s: n_experts=%d (0..256), top_k=%d (1..16, <= n_experts)", who, s->n_experts, s->top_k);
   return VLC_OK;
 }
 
@@ -81,7 +103,8 @@ extern "C" int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t 
   if (!offsets) return fail(VLC_ERR_NULL, "vlc_layer_workspace_layout: offsets is NULL");
   if (n_rows < 0) return fail(VLC_ERR_SHAPE, "vlc_layer_workspace_layout: n_rows=%lld", (long long)n_rows);
   const Workspace w = layout(*shape, n_rows);
-  const int64_t o[VLC_WS_FIELDS] = {w.xn, w.qkv32, w.q, w.attn, w.h1, w.n2, w.act};
+  const int64_t o[VLC_WS_FIELDS] = {w.xn,      w.qkv32, w.q,       w.attn,  w.h1,         w.n2,        w.act,
+                                    w.moe_idx, w.moe_w, w.moe_pos, w.moe_y, w.moe_logits, w.moe_offset};
   for (int i = 0; i < VLC_WS_FIELDS; ++i) offsets[i] = o[i];
   return VLC_OK;
 }
@@ -129,6 +152,7 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
   if (!p->map || !p->slot || !(mrope ? (const void*)p->pos3 : (const void*)p->pos) || !p->row_kv_start ||
       !p->row_kv_len || !h_in || !h_out)
     return fail(VLC_ERR_NULL, "%s: NULL pointer in plan / hidden states", who);
+  if (s.n_experts > 0 && !w->w_router) return fail(VLC_ERR_NULL, "%s: w_router is NULL", who);
   if ((w->w_qnorm == nullptr) != (w->w_knorm == nullptr))
     return fail(VLC_ERR_NULL, "%s: w_qnorm and w_knorm come together", who);
   if (h_in == h_out) return fail(VLC_ERR_SHAPE, "%s: h_out must not alias h_in", who);
@@ -181,6 +205,42 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
     rc = vlc::launch_rmsnorm(h1, nullptr, w->w_ln2, n2, n, s.H, s.eps, s.dtype, st);
   if (rc) return rc;
   VLC_MARK(7);
+  if (s.n_experts > 0) {
+    // router scores (float), expert choice and grouping, then the experts' gate|up GEMMs with SwiGLU over the
+    // (row, expert) pairs in grouped order (rows of n2 fetched through the position -> row list)
+    const int E = s.n_experts, K = s.top_k;
+    const int64_t pairs = n * K;
+    float* logits = reinterpret_cast<float*>(base + ws.moe_logits);
+    vlc::MoeScratch ms;
+    ms.idx = reinterpret_cast<int32_t*>(base + ws.moe_idx);
+    ms.wts = reinterpret_cast<float*>(base + ws.moe_w);
+    ms.rank = reinterpret_cast<int32_t*>(base + ws.moe_rank);
+    ms.count = reinterpret_cast<int32_t*>(base + ws.moe_count);
+    ms.offset = reinterpret_cast<int32_t*>(base + ws.moe_offset);
+    ms.tiles = reinterpret_cast<vlc::GroupTile*>(base + ws.moe_tiles);
+    ms.n_tiles = reinterpret_cast<int32_t*>(base + ws.moe_ntiles);
+    ms.pair_row = reinterpret_cast<int32_t*>(base + ws.moe_row);
+    ms.pair_pos = reinterpret_cast<int32_t*>(base + ws.moe_pos);
+    void* y = base + ws.moe_y;
+    const int tile_rows = vlc::gemm_group_tile_rows(pairs, E, s.dtype);
+    rc = vlc::launch_gemm(n2, H, w->w_router, logits, E, n, E, H,
+                          s.dtype == VLC_BF16 ? vlc::EPI_BIAS_F32 : vlc::EPI_BIAS, nullptr, nullptr, 0, nullptr,
+                          s.dtype, skw, ws.splitk_bytes, st);
+    if (rc) return rc;
+    rc = vlc::launch_moe_route(logits, n, E, K, tile_rows, ms, st);
+    if (rc) return rc;
+    rc = vlc::launch_gemm_grouped(n2, H, ms.pair_row, w->w_gate_up, 2 * I * H, act, I, pairs, E, I, H,
+                                  vlc::EPI_SWIGLU, ms.tiles, ms.n_tiles, tile_rows, s.dtype, st);
+    if (rc) return rc;
+    VLC_MARK(8);
+    rc = vlc::launch_gemm_grouped(act, I, nullptr, w->w_down, H * I, y, H, pairs, E, H, I, vlc::EPI_BIAS, ms.tiles,
+                                  ms.n_tiles, tile_rows, s.dtype, st);
+    if (rc) return rc;
+    rc = vlc::launch_moe_combine(h1, y, ms.wts, ms.pair_pos, n, K, s.H, h_out, s.dtype, st);
+    if (rc) return rc;
+    VLC_MARK(9);
+    return VLC_OK;
+  }
   rc = vlc::launch_gemm(n2, H, w->w_gate_up, act, I, n, I, H, vlc::EPI_SWIGLU, nullptr, nullptr, 0, nullptr,
                         s.dtype, skw, ws.splitk_bytes, st);
   if (rc) return rc;

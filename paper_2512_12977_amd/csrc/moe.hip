@@ -1,0 +1,218 @@
+// Mixture-of-experts MLP (the Qwen3-VL-30B-A3B-shaped layer of the paper's evaluation, Sec. 5.1):
+// expert choice per recomputed row, grouping of the (row, expert) pairs by expert for the grouped
+// GEMMs, and the weighted sum of the experts' outputs with the residual.
+//
+//   route   : per row, the top_k largest router scores (equal scores: lower expert index first),
+//             weights exp(z_k - z_max) / sum over the chosen ones (the softmax denominator over
+//             all experts cancels in the renormalised weights); each pair takes a rank inside its
+//             expert from an atomic counter (the order inside an expert does not change any result:
+//             every pair is computed on its own)
+//   plan    : exclusive scan of the expert counts -> first pair of every expert, and the table of
+//             row tiles (expert, first row, end row) the grouped GEMMs walk
+//   fill    : pair position = first pair of its expert + rank; the inverse list position -> row
+//   combine : h_out[row] = h1[row] + sum_k w[row, k] * y[position(row, k)]   (float sum, one rounding)
+#include <hip/hip_runtime.h>
+
+#include <cfloat>
+#include <climits>
+
+#include "vlc_internal.h"
+
+namespace vlc {
+namespace {
+
+constexpr int kMaxExperts = 256;   // four scores per lane
+constexpr int kMaxTopK = 16;
+
+__global__ __launch_bounds__(256) void zero_i32_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+__device__ __forceinline__ void better(float& bv, int& be, float v, int e) {
+  if (v > bv || (v == bv && e < be)) {
+    bv = v;
+    be = e;
+  }
+}
+
+// one wavefront per row
+__global__ __launch_bounds__(256) void moe_route_kernel(const float* __restrict__ logits, int64_t n, int E, int K,
+                                                        int32_t* __restrict__ idx, float* __restrict__ wts,
+                                                        int32_t* __restrict__ rank, int32_t* __restrict__ count) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n) return;
+  float v[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int e = lane + 64 * j;
+    float z = e < E ? logits[row * E + e] : -INFINITY;
+    if (e < E && !(z >= -FLT_MAX)) z = -FLT_MAX;        // NaN or -inf scores rank last but stay selectable
+    v[j] = z;
+  }
+  float my_v = 0.f, top_v = 0.f;
+  int my_e = 0;
+  for (int k = 0; k < K; ++k) {
+    float bv = -INFINITY;
+    int be = INT_MAX;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) better(bv, be, v[j], lane + 64 * j);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) better(bv, be, __shfl_xor(bv, o), __shfl_xor(be, o));
+    if (k == 0) top_v = bv;
+    if (lane == k) {
+      my_v = bv;
+      my_e = be;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (lane + 64 * j == be) v[j] = -INFINITY;         // taken
+  }
+  float ex = lane < K ? expf(my_v - top_v) : 0.f;
+  float sum = ex;
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o);   // K <= 16: lanes 0..15
+  if (lane < K) {
+    const int e = my_e < E ? my_e : E - 1;
+    idx[row * K + lane] = e;
+    wts[row * K + lane] = ex / sum;
+    rank[row * K + lane] = atomicAdd(&count[e], 1);
+  }
+}
+
+// one workgroup of 256 threads, thread e owns expert e
+__global__ __launch_bounds__(256) void moe_plan_kernel(const int32_t* __restrict__ count, int E, int tile_rows,
+                                                       int32_t* __restrict__ offset, GroupTile* __restrict__ tiles,
+                                                       int32_t* __restrict__ n_tiles) {
+  __shared__ int sc[256], stl[256];
+  const int e = threadIdx.x;
+  const int cnt = e < E ? count[e] : 0;
+  const int nt = (cnt + tile_rows - 1) / tile_rows;
+  sc[e] = cnt;
+  stl[e] = nt;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {      // inclusive scans
+    const int a = e >= o ? sc[e - o] : 0, b = e >= o ? stl[e - o] : 0;
+    __syncthreads();
+    sc[e] += a;
+    stl[e] += b;
+    __syncthreads();
+  }
+  const int off = sc[e] - cnt, toff = stl[e] - nt;
+  if (e < E) {
+    offset[e] = off;
+    for (int t = 0; t < nt; ++t) {
+      GroupTile g;
+      g.expert = e;
+      g.m0 = off + t * tile_rows;
+      g.m_end = off + cnt;
+      g.pad = 0;
+      tiles[toff + t] = g;
+    }
+  }
+  if (e == 255) {
+    offset[E] = sc[255];
+    *n_tiles = stl[255];
+  }
+}
+
+__global__ __launch_bounds__(256) void moe_fill_kernel(const int32_t* __restrict__ idx, const int32_t* __restrict__ rank,
+                                                       const int32_t* __restrict__ offset, int64_t pairs, int K,
+                                                       int32_t* __restrict__ pair_row, int32_t* __restrict__ pair_pos) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= pairs) return;
+  const int pos = offset[idx[i]] + rank[i];
+  pair_pos[i] = pos;
+  pair_row[pos] = (int32_t)(i / K);
+}
+
+__device__ __forceinline__ float ld_elem(const float* p) { return *p; }
+__device__ __forceinline__ float ld_elem(const uint16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
+__device__ __forceinline__ void st_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_elem(uint16_t* p, float v) {
+  uint32_t u = __float_as_uint(v);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  *p = (uint16_t)(u >> 16);
+}
+
+// one workgroup per row; a thread owns 16-byte chunks of the row
+template <typename T>
+__global__ __launch_bounds__(256) void moe_combine_kernel(const T* __restrict__ h1, const T* __restrict__ y,
+                                                          const float* __restrict__ wts,
+                                                          const int32_t* __restrict__ pair_pos, int K, int H,
+                                                          T* __restrict__ out) {
+  constexpr int VEC = 16 / sizeof(T);
+  const int64_t row = blockIdx.x;
+  __shared__ float w[kMaxTopK];
+  __shared__ int pos[kMaxTopK];
+  if (threadIdx.x < K) {
+    w[threadIdx.x] = wts[row * K + threadIdx.x];
+    pos[threadIdx.x] = pair_pos[row * K + threadIdx.x];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x * VEC; c < H; c += 256 * VEC) {
+    float acc[VEC];
+    uint4 raw = *reinterpret_cast<const uint4*>(h1 + row * H + c);
+    const T* hp = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+    for (int k = 0; k < K; ++k) {
+      const uint4 yr = *reinterpret_cast<const uint4*>(y + (int64_t)pos[k] * H + c);
+      const T* yp = reinterpret_cast<const T*>(&yr);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w[k], ld_elem(yp + i), acc[i]);
+    }
+    uint4 o;
+    T* op = reinterpret_cast<T*>(&o);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) st_elem(op + i, ld_elem(hp + i) + acc[i]);
+    *reinterpret_cast<uint4*>(out + row * H + c) = o;
+  }
+}
+
+}  // namespace
+
+int launch_moe_route(const float* logits, int64_t n, int n_experts, int top_k, int tile_rows, const MoeScratch& s,
+                     hipStream_t st) {
+  if (n <= 0) return VLC_OK;
+  if (n_experts < 1 || n_experts > kMaxExperts || top_k < 1 || top_k > kMaxTopK || top_k > n_experts)
+    return fail(VLC_ERR_SHAPE, "moe: n_experts=%d (<= %d), top_k=%d (<= %d, <= n_experts)", n_experts, kMaxExperts,
+                top_k, kMaxTopK);
+  if (n * top_k > INT32_MAX) return fail(VLC_ERR_SHAPE, "moe: too many (row, expert) pairs");
+  const int64_t pairs = n * top_k;
+  hipLaunchKernelGGL(zero_i32_kernel, dim3(1), dim3(256), 0, st, s.count, n_experts);
+  VLC_CHECK_LAUNCH("moe_zero");
+  hipLaunchKernelGGL(moe_route_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, logits, n, n_experts, top_k,
+                     s.idx, s.wts, s.rank, s.count);
+  VLC_CHECK_LAUNCH("moe_route");
+  hipLaunchKernelGGL(moe_plan_kernel, dim3(1), dim3(256), 0, st, (const int32_t*)s.count, n_experts, tile_rows,
+                     s.offset, s.tiles, s.n_tiles);
+  VLC_CHECK_LAUNCH("moe_plan");
+  hipLaunchKernelGGL(moe_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, st,
+                     (const int32_t*)s.idx, (const int32_t*)s.rank, (const int32_t*)s.offset, pairs, top_k,
+                     s.pair_row, s.pair_pos);
+  VLC_CHECK_LAUNCH("moe_fill");
+  return VLC_OK;
+}
+
+int launch_moe_combine(const void* h1, const void* y, const float* wts, const int32_t* pair_pos, int64_t n,
+                       int top_k, int H, void* out, int dtype, hipStream_t st) {
+  if (n <= 0) return VLC_OK;
+  if (top_k < 1 || top_k > kMaxTopK) return fail(VLC_ERR_SHAPE, "moe combine: top_k=%d", top_k);
+  if (dtype == VLC_BF16) {
+    if (H % 8) return fail(VLC_ERR_SHAPE, "moe combine: H=%d must be a multiple of 8", H);
+    hipLaunchKernelGGL(moe_combine_kernel<uint16_t>, dim3((unsigned)n), dim3(256), 0, st, (const uint16_t*)h1,
+                       (const uint16_t*)y, wts, pair_pos, top_k, H, (uint16_t*)out);
+  } else if (dtype == VLC_F32) {
+    if (H % 4) return fail(VLC_ERR_SHAPE, "moe combine: H=%d must be a multiple of 4", H);
+    hipLaunchKernelGGL(moe_combine_kernel<float>, dim3((unsigned)n), dim3(256), 0, st, (const float*)h1,
+                       (const float*)y, wts, pair_pos, top_k, H, (float*)out);
+  } else {
+    return fail(VLC_ERR_DTYPE, "moe combine: dtype=%d", dtype);
+  }
+  VLC_CHECK_LAUNCH("moe_combine");
+  return VLC_OK;
+}
+
+}  // namespace vlc

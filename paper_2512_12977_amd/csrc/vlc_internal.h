@@ -110,5 +110,39 @@ int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
                 int* deferred = nullptr);
 int64_t gemm_splitk_ws_bytes(int64_t n_rows, int64_t max_n);
 
+// Grouped GEMM (mixture-of-experts): C[m, :] = epilogue(A[amap ? amap[m] : m, :] * W[g]^T) for the rows m
+// of group g; the rows of a group are contiguous in C.  `tiles` (device) lists (group, first row, end row)
+// with at most tile_rows rows each, *n_tiles (device) says how many entries count; both are written by
+// launch_moe_plan.  rows: total number of rows over all groups; w_stride: elements between two groups'
+// matrices.  Epilogues: EPI_BIAS without a bias (plain product) and EPI_SWIGLU.
+struct GroupTile {
+  int32_t expert, m0, m_end, pad;
+};
+int gemm_group_tile_rows(int64_t rows, int n_groups, int dtype);
+int launch_gemm_grouped(const void* A, int64_t lda, const int32_t* amap, const void* W, int64_t w_stride, void* C,
+                        int64_t ldc, int64_t rows, int n_groups, int64_t N, int64_t K, int epilogue,
+                        const GroupTile* tiles, const int32_t* n_tiles, int tile_rows, int dtype, hipStream_t st);
+
+// Mixture-of-experts routing.  All pointers device.  launch_moe_route: from router scores [n, E] (float)
+// writes the chosen experts idx [n, K], weights wts [n, K], the grouped order (offset [E + 1]: first pair
+// of every expert; pair_pos [n, K]: position of a pair; pair_row [n * K]: row of the pair at a position)
+// and the tile table of the grouped GEMMs (tiles [n * K / tile_rows + E], n_tiles [1]).  rank [n, K] and
+// count [E] are scratch.  launch_moe_combine: out[r] = h1[r] + sum_k wts[r, k] * y[pair_pos[r, k]].
+struct MoeScratch {
+  int32_t* idx;
+  float* wts;
+  int32_t* rank;
+  int32_t* count;
+  int32_t* offset;
+  GroupTile* tiles;
+  int32_t* n_tiles;
+  int32_t* pair_row;
+  int32_t* pair_pos;
+};
+int launch_moe_route(const float* logits, int64_t n, int n_experts, int top_k, int tile_rows, const MoeScratch& s,
+                     hipStream_t st);
+int launch_moe_combine(const void* h1, const void* y, const float* wts, const int32_t* pair_pos, int64_t n,
+                       int top_k, int H, void* out, int dtype, hipStream_t st);
+
 }  // namespace vlc
 #endif

@@ -19,7 +19,8 @@ def make_shape(sh) -> B.LayerShape:
     """sh: any object with H, Hq, Hkv, D, I, dtype ('f32'|'bf16'), eps, rope_base."""
     sec = tuple(getattr(sh, "mrope_section", ())) or (0, 0, 0)
     return B.LayerShape(sh.H, sh.Hq, sh.Hkv, sh.D, sh.I, B.VLC_BF16 if sh.dtype == "bf16" else B.VLC_F32,
-                        float(sh.eps), float(sh.rope_base), int(sec[0]), int(sec[1]), int(sec[2]))
+                        float(sh.eps), float(sh.rope_base), int(sec[0]), int(sec[1]), int(sec[2]),
+                        int(getattr(sh, "n_experts", 0)), int(getattr(sh, "top_k", 0)))
 
 
 def segments_of(requests: Sequence) -> List[B.Segment]:
@@ -36,7 +37,7 @@ def segments_of(requests: Sequence) -> List[B.Segment]:
     return out
 
 
-_WEIGHT_FIELDS = ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down", "w_qnorm", "w_knorm")
+_WEIGHT_FIELDS = ("w_ln1", "w_qkv", "b_qkv", "w_o", "w_ln2", "w_gate_up", "w_down", "w_qnorm", "w_knorm", "w_router")
 
 
 class DeviceWeights:
@@ -57,6 +58,9 @@ class DeviceWeights:
         nq = (sh.Hq + 2 * sh.Hkv) * sh.D
         sizes = {"w_ln1": (sh.H,), "w_qkv": (nq, sh.H), "b_qkv": (nq,), "w_o": (sh.H, sh.Hq * sh.D),
                  "w_ln2": (sh.H,), "w_gate_up": (2 * sh.I, sh.H), "w_down": (sh.H, sh.I)}
+        E = getattr(sh, "n_experts", 0)
+        if E:
+            sizes.update({"w_gate_up": (E, 2 * sh.I, sh.H), "w_down": (E, sh.H, sh.I), "w_router": (E, sh.H)})
         self.t = {}
         for name, size in sizes.items():
             if name == "b_qkv" and not sh.qkv_bias:

@@ -156,6 +156,7 @@ def make_workload(name: str) -> Workload:
     c4_5  as c4 with uniform 5 %
     c5  72B shape, 8 x 1296-token images | 256 text, dynamic 3 % budget
     c1_q3, c1_q3_bf16, c2_q3, c3_q3  the same prompts for the Qwen3-VL-shaped layer (q/k norm, 3-axis position ids)
+    c1_moe, c1_moe_bf16, c2_moe, c4_moe  the same with a mixture-of-experts MLP (c2_moe, c4_moe: 30B-A3B shape)
     """
     if name == "c1":
         segs = _layout([("text", 32), ("image", 256, 0, 0), ("text", 16)])
@@ -174,6 +175,25 @@ def make_workload(name: str) -> Workload:
         req = _grid_request([("text", 32), ("image", 16, 16, 0, 0), ("text", 16)])
         return Workload(name, SHAPES["tiny_q3" if name == "c1_q3" else "tiny_q3_bf16"], [req], 256, "explicit",
                         explicit_counts=13, seed=6)
+    if name in ("c1_moe", "c1_moe_bf16"):
+        # as c1_q3 with a mixture-of-experts MLP (8 experts, 2 per token)
+        req = _grid_request([("text", 32), ("image", 16, 16, 0, 0), ("text", 16)])
+        return Workload(name, SHAPES["tiny_moe" if name == "c1_moe" else "tiny_moe_bf16"], [req], 256, "explicit",
+                        explicit_counts=13, seed=9)
+    if name == "c2_moe":
+        # as c2_q3 at the Qwen3-VL-30B-A3B text-decoder shape (128 experts, 8 per token)
+        req = _grid_request([("text", 512), ("image", 32, 32, 0, 0), ("text", 64)])
+        return Workload("c2_moe", SHAPES["q3vl_30b_a3b"], [req], 1024, "static", static_k=10, seed=10)
+    if name == "c4_moe":
+        # a batch of 8 long prompts at the 30B-A3B shape: text a_b | 16 images of 32 x 32 tokens | text 2048 - a_b
+        NI, X, B = 16, 2048, 8
+        a = np.random.default_rng(11).choice(np.arange(1, 1025), size=B, replace=False)
+        reqs, at = [], 0
+        for b in range(B):
+            parts = [("text", int(a[b]))] + [("image", 32, 32, j * 32, j * 1024) for j in range(NI)] + [("text", X - int(a[b]))]
+            reqs.append(_grid_request(parts, at))
+            at += X + NI * 1024
+        return Workload("c4_moe", SHAPES["q3vl_30b_a3b"], reqs, NI * 1024, "static", static_k=10, seed=11)
     if name == "c2_q3":
         # as c2 at the Qwen3-VL 8B text-decoder shape: a 32 x 32-token image cached at temporal id 0
         req = _grid_request([("text", 512), ("image", 32, 32, 0, 0), ("text", 64)])
