@@ -232,6 +232,24 @@ def main() -> int:
     for _ in range(args.warmup):
         run_step(sel_recs)
     torch.cuda.synchronize()
+    expert_load = None
+    if sh.n_experts:
+        # how evenly the synthetic router spreads the (row, expert) pairs: one untimed pass, layer by layer
+        hit, peak = [], []
+        h_in = emb
+        for l in range(L):
+            h_out = hbuf[l & 1]
+            vlc.vlc_layer_forward(rec, weights[l].rec, sel_recs[l], h_in, h_out, kcache[l], vcache[l], ws.t)
+            torch.cuda.synchronize()
+            off = vlc.vlc_layer_workspace_layout(rec, plans.n_rows[l])["moe_idx"]
+            idx = ws.t[off:off + plans.n_rows[l] * sh.top_k * 4].view(torch.int32)
+            cnt = torch.bincount(idx.long(), minlength=sh.n_experts).float()
+            hit.append(int((cnt > 0).sum().item()))
+            peak.append(float((cnt.max() / cnt.mean()).item()))
+            h_in = h_out
+        expert_load = {"experts_hit": {"min": min(hit), "median": float(np.median(hit)), "max": max(hit)},
+                       "largest_over_mean_load": {"min": round(min(peak), 2), "median": round(float(np.median(peak)), 2),
+                                                  "max": round(max(peak), 2)}, "experts": sh.n_experts}
     psteps = 3
     pev = [[hev.create(NS + 1) for _ in range(L)] for _ in range(psteps)]
     for s in range(psteps):
@@ -432,6 +450,7 @@ def main() -> int:
         "config": {"workload": DESCR[wl.name], "layers": L, "requests": n_req,
                    "rows_per_layer": [int(rows.min()), int(np.median(rows)), int(rows.max())],
                    "slots": total},
+        "expert_load": expert_load,
         "prefill_latency_ms": round(ms_per_step, 4),
         "gpu_busy_ms_per_step": round(gpu_ms, 4),
         "full_recompute_latency_ms": None if full_ms is None else round(full_ms, 4),

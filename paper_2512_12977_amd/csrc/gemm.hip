@@ -179,8 +179,14 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   (lds_base + (uint32_t)(((stage_) * STAGE_CHUNKS +                                                           \
                           ((i_) < A_INSTR ? wave * A_INSTR * 64 + (i_) * 64                                  \
                                           : BM * 8 + wave * W_INSTR * 64 + ((i_) - A_INSTR) * 64)) * 16))
-#define VLC_SRC(kt_, i_) ((i_) < A_INSTR ? a_src[(i_) < A_INSTR ? (i_) : 0] + (kt_) * BK                      \
-                                         : w_src[(i_) >= A_INSTR ? (i_) - A_INSTR : 0] + (kt_) * BK)
+  // GROUPED: the k-tiles are walked from a tile-dependent start, wrapping round.  Every matrix of a group is
+  // read once, cold, by workgroups that start together; with a row pitch that is a power of two they would
+  // all ask the same memory channels for the same k at the same time.
+  int k_rot = 0;
+  if constexpr (GROUPED) k_rot = (tn * 5 + tm * 3) % KT;
+#define VLC_KT(kt_) (GROUPED ? ((kt_) + k_rot < KT ? (kt_) + k_rot : (kt_) + k_rot - KT) : (kt_))
+#define VLC_SRC(kt_, i_) ((i_) < A_INSTR ? a_src[(i_) < A_INSTR ? (i_) : 0] + VLC_KT(kt_) * BK                \
+                                         : w_src[(i_) >= A_INSTR ? (i_) - A_INSTR : 0] + VLC_KT(kt_) * BK)
 #define VLC_ISSUE(kt_, stage_)                                                                               \
   _Pragma("unroll") for (int i = 0; i < LOADS; ++i) dma16(VLC_SRC(kt_, i), VLC_LDS_DST(stage_, i));
 
@@ -213,11 +219,11 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
 
   // One k-tile: KS k-steps of G groups of four MFMAs.  WITH_LOADS: the loads of k-tile nkt_ (into
   // stage nst_) are issued in the first half of the groups.
-  constexpr int MPG = 4;                       // MFMAs per group
+  constexpr int MPG = (NT * MT) % 4 == 0 ? 4 : 2;   // MFMAs per group
   constexpr int G = NT * MT / MPG;             // groups per k-step
   constexpr int TG = KS * G;                   // groups per k-tile
   constexpr int NF = NT + MT;                  // fragments per k-step
-  static_assert(NT * MT % MPG == 0, "wavefront tile must hold a multiple of four MFMA tiles");
+  static_assert(NT * MT % MPG == 0, "wavefront tile must hold whole groups of MFMA tiles");
 #define VLC_COMPUTE_TILE(kt_, WITH_LOADS, nkt_, nst_)                                                         \
   {                                                                                                           \
     const u32x4* st_ = lds + ((kt_) % STAGES) * STAGE_CHUNKS;                                                 \
@@ -267,6 +273,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   }
 #undef VLC_ISSUE
 #undef VLC_SRC
+#undef VLC_KT
 #undef VLC_LDS_DST
 #undef VLC_COMPUTE_TILE
 
@@ -687,9 +694,14 @@ int64_t gemm_splitk_ws_bytes(int64_t n_rows, int64_t max_n) {
   return n_rows > 0 ? (int64_t)64 << 20 : 0;
 }
 
+// Rows per tile of the grouped GEMMs, from the mean number of rows per group.  Few rows per group: every
+// matrix is streamed from HBM exactly once and nothing is reused, so the tile is small (64 x 128) and the
+// ring three stages deep - with two workgroups per CU that keeps 64 KB of matrix data in flight per CU,
+// what the HBM latency needs; a two-stage ring of 128 x 128 tiles stalls at half of that.
 int gemm_group_tile_rows(int64_t rows, int n_groups, int dtype) {
   if (dtype != VLC_BF16) return 64;
-  return rows / (n_groups > 0 ? n_groups : 1) >= 192 ? 256 : 128;
+  const int64_t mean = rows / (n_groups > 0 ? n_groups : 1);
+  return mean >= 192 ? 256 : (mean >= 56 ? 128 : 64);
 }
 
 int launch_gemm_grouped(const void* A, int64_t lda, const int32_t* amap, const void* W, int64_t w_stride, void* C,
@@ -711,6 +723,11 @@ int launch_gemm_grouped(const void* A, int64_t lda, const int32_t* amap, const v
       if (epilogue == EPI_SWIGLU)
         return launch_bf16_grouped<256, 256, 2, 2, 2, 1, EPI_SWIGLU>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
       return launch_bf16_grouped<256, 256, 2, 2, 2, 1, EPI_BIAS>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
+    }
+    if (tile_rows == 64) {
+      if (epilogue == EPI_SWIGLU)
+        return launch_bf16_grouped<64, 128, 2, 2, 3, 2, EPI_SWIGLU>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
+      return launch_bf16_grouped<64, 128, 2, 2, 3, 2, EPI_BIAS>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
     }
     if (epilogue == EPI_SWIGLU)
       return launch_bf16_grouped<128, 128, 2, 2, 2, 2, EPI_SWIGLU>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);

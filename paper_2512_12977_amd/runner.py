@@ -66,7 +66,8 @@ class DeviceWeights:
             if name == "b_qkv" and not sh.qkv_bias:
                 self.t[name] = None
                 continue
-            w = torch.randn(size, generator=g, device=device, dtype=torch.float32) * 0.02
+            w = torch.randn(size, generator=g, device=device, dtype=torch.float32)
+            w *= getattr(sh, "residual_proj_scale", 0.02) if name in ("w_o", "w_down") else 0.02
             if name in ("w_ln1", "w_ln2"):
                 w += 1.0
             self.t[name] = w.to(dtype)

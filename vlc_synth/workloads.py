@@ -35,6 +35,14 @@ class Shape:
     mrope_section: tuple = ()             # (t, h, w) frequency counts of 3-axis RoPE; () = 1-D RoPE
     n_experts: int = 0                    # > 0: mixture-of-experts MLP; I is then the width of ONE expert
     top_k: int = 0                        # experts per token
+    # Scale of the synthetic inputs.  With experts the rows must stay as different from one another as a
+    # trained model's are, or the router sends every row to the same few experts (a trained router is
+    # balanced): text rows are then drawn at the scale of the image rows (1.0 instead of 0.02) and the
+    # two projections that write into the residual stream (w_o, w_down) at 0.02 / sqrt(2 L) instead
+    # of 0.02, so that the residual stream is not taken over by the mean of the values that uniform
+    # attention over random keys adds to every row.
+    text_scale: float = 0.02
+    residual_proj_scale: float = 0.02
 
     @property
     def g(self) -> int:
@@ -61,12 +69,14 @@ SHAPES: Dict[str, Shape] = {
                      dtype="bf16", qkv_bias=False, vocab=151936, qk_norm=True, mrope_section=(24, 20, 20)),
     # mixture-of-experts MLP on top of the Qwen3-VL-shaped attention
     "tiny_moe": Shape("tiny_moe", L=2, H=256, Hq=4, Hkv=2, D=64, I=128, rope_base=1e4, dtype="f32", qkv_bias=False,
-                      qk_norm=True, mrope_section=(12, 10, 10), n_experts=8, top_k=2),
+                      qk_norm=True, mrope_section=(12, 10, 10), n_experts=8, top_k=2, text_scale=1.0,
+                      residual_proj_scale=0.01),
     "tiny_moe_bf16": Shape("tiny_moe_bf16", L=2, H=256, Hq=4, Hkv=2, D=128, I=128, rope_base=1e4, dtype="bf16",
-                           qkv_bias=False, qk_norm=True, mrope_section=(24, 20, 20), n_experts=8, top_k=2),
+                           qkv_bias=False, qk_norm=True, mrope_section=(24, 20, 20), n_experts=8, top_k=2,
+                           text_scale=1.0, residual_proj_scale=0.01),
     "q3vl_30b_a3b": Shape("q3vl_30b_a3b", L=48, H=2048, Hq=32, Hkv=4, D=128, I=768, rope_base=5e6, dtype="bf16",
                           qkv_bias=False, vocab=151936, qk_norm=True, mrope_section=(24, 20, 20), n_experts=128,
-                          top_k=8),
+                          top_k=8, text_scale=1.0, residual_proj_scale=0.02 / 96 ** 0.5),
     "7b": Shape("7b", L=28, H=3584, Hq=28, Hkv=4, D=128, I=18944, rope_base=1e6,
                 dtype="bf16", qkv_bias=True, vocab=152064),
     "72b": Shape("72b", L=80, H=8192, Hq=64, Hkv=8, D=128, I=29568, rope_base=1e6,
@@ -280,7 +290,8 @@ def layer_weights(shape: Shape, seed: int, layer: int) -> Dict[str, Optional[np.
     """Weights of one decoder layer, float32, torch-Linear layout [out, in].
 
     w_qkv rows: q heads, then k heads, then v heads.  w_gate_up rows: gate (I rows) then up (I rows).
-    Linear weights ~ N(0, 0.02^2); norm weights 1 + N(0, 0.02^2); qkv bias N(0, 0.02^2) or None.
+    Linear weights ~ N(0, 0.02^2) (w_o and w_down: N(0, shape.residual_proj_scale^2), the same unless the shape
+    says otherwise); norm weights 1 + N(0, 0.02^2); qkv bias N(0, 0.02^2) or None.
     Mixture-of-experts shapes: w_gate_up [E, 2I, H], w_down [E, H, I] and the router matrix
     w_router [E, H] ~ N(0, 0.02^2) (else w_router is None).
     """
@@ -295,7 +306,7 @@ def layer_weights(shape: Shape, seed: int, layer: int) -> Dict[str, Optional[np.
             out[nm] = None
             continue
         n = int(np.prod(sizes[nm]))
-        w = normal_f32([seed, 1000 + layer, t], n, 0.02).reshape(sizes[nm])
+        w = normal_f32([seed, 1000 + layer, t], n, shape.residual_proj_scale if nm in ("w_o", "w_down") else 0.02).reshape(sizes[nm])
         if nm in ("w_ln1", "w_ln2"):
             w += np.float32(1.0)
         out[nm] = w
@@ -334,12 +345,12 @@ def head_weights(shape: Shape, seed: int) -> Dict[str, np.ndarray]:
 def embedding_rows(wl: Workload) -> np.ndarray:
     """Input hidden rows [total_slots, H], float32, for every slot of every request.
 
-    Text slots: rows of a 1024-row N(0, 0.02^2) table at random ids.  Image slots: N(0, 1)
+    Text slots: rows of a 1024-row N(0, shape.text_scale^2) table (0.02 by default) at random ids.  Image slots: N(0, 1)
     (stand-in for the cached vision-encoder output of that image).
     """
     H = wl.shape.H
     rng = np.random.default_rng([wl.seed, 7])
-    table = normal_f32([wl.seed, 8], 1024 * H, 0.02).reshape(1024, H)
+    table = normal_f32([wl.seed, 8], 1024 * H, wl.shape.text_scale).reshape(1024, H)
     emb = np.empty((wl.total_slots, H), dtype=np.float32)
     for r_i, req in enumerate(wl.requests):
         for s_i, seg in enumerate(req.segments):
