@@ -312,7 +312,7 @@ def moe_mlp(shape, W, n2, store, forced=None):
 STAGES = ("xn", "qkv", "q", "K", "V", "o", "h1", "n2", "act", "h2")
 
 
-def layer_stages(shape, W, x, slots, pos, K, V, store, forced=None):
+def layer_stages(shape, W, x, slots, pos, K, V, store, forced=None, kv_rows=None):
     """One decoder layer for the query rows `slots` of one request; returns every stage's result.
 
     x      [n, H]  hidden states of those rows (already gathered, storage-rounded)
@@ -324,6 +324,9 @@ def layer_stages(shape, W, x, slots, pos, K, V, store, forced=None):
     forced optional dict stage-name -> array: where present, the NEXT stage is fed this value
            instead of the one computed here (used by tests to check each stage of another
            implementation against this one on identical inputs).
+    kv_rows optional indices into the row list: only these rows store their fresh k, v (default: all);
+           the other rows are still computed and still attend, but the keys/values already in K, V at
+           their slots stay (the layer-wise sensitivity measurement of Sec. 3.2 needs this).
     Returns a dict with the stages named in STAGES; K and V are the blended caches (updated in place).
 
     reading (decoder details, which the paper leaves to the Qwen family): pre-norm RMSNorm,
@@ -356,8 +359,12 @@ def layer_stages(shape, W, x, slots, pos, K, V, store, forced=None):
     r["q"] = store(rope_rotate(q, pos, shape.rope_base, section))
     k = store(rope_rotate(k, pos, shape.rope_base, section))
     v = store(qkv[:, (Hq + Hkv) * D:].reshape(n, Hkv, D))
-    K[slots] = k
-    V[slots] = v
+    if kv_rows is None:
+        K[slots] = k
+        V[slots] = v
+    else:
+        K[np.asarray(slots)[kv_rows]] = k[kv_rows]
+        V[np.asarray(slots)[kv_rows]] = v[kv_rows]
     r["K"], r["V"] = K, V
     r["o"] = store(attention_rows(fed("q", r["q"]), fed("K", K), fed("V", V), np.asarray(slots) + 1,
                                   1.0 / np.sqrt(D)))
@@ -375,9 +382,9 @@ def layer_stages(shape, W, x, slots, pos, K, V, store, forced=None):
     return r
 
 
-def layer_forward(shape, W, x, slots, pos, K, V, store):
+def layer_forward(shape, W, x, slots, pos, K, V, store, kv_rows=None):
     """layer_stages without the intermediate results: (h_out [n, H], K, V)."""
-    r = layer_stages(shape, W, x, slots, pos, K, V, store)
+    r = layer_stages(shape, W, x, slots, pos, K, V, store, kv_rows=kv_rows)
     return r["h2"], r["K"], r["V"]
 
 
@@ -454,6 +461,67 @@ def full_prefill(shape, weights, emb, request, store):
         h, K, V = layer_forward(shape, W, h, slots, positions_of(request, slots), K, V, store)
         out.append({"slots": slots, "h": h, "K": K, "V": V})
     return out
+
+
+# ----------------------------------------------------------------------------------------------
+# layer-wise sensitivity S_i(r) (Sec. 3.2 "Layer-wise Importance Difference", Sec. 4.1 Eq. 5)
+# ----------------------------------------------------------------------------------------------
+def profile_prefill(shape, weights, emb, request, layer_i, counts_i, cache, store):
+    """The measurement pass behind Eq. 5: the image keys/values of a cache built under another prompt
+    are used in ALL layers, and only in layer `layer_i` the leading counts_i[j] tokens of image j
+    keep their freshly computed k, v.  Returns the last layer's hidden rows of every slot [S, H].
+
+    reading: Sec. 3.2 injects the mismatched cache into all layers while recomputing some image
+    tokens "in a single layer".  A token can only be recomputed in layer i if its hidden state
+    reaches layer i, which the fast path's non-increasing rates guarantee but a single-layer
+    recompute does not; so this measurement computes every slot in every layer (an ordinary forward
+    pass) and overrides which keys/values the attention sees: cached ones for image tokens, except
+    the chosen tokens in layer i.  Image rows still attend and still feed the next layer.
+    """
+    S = request.S
+    slots = np.arange(S, dtype=np.int64)
+    n_img = sum(1 for g in request.segments if g.is_image)
+    h = store(emb)
+    for l, W in enumerate(weights):
+        counts = list(counts_i) if l == layer_i else [0] * n_img
+        Kc, Vc = cache[l]
+        K, V = blended_kv_before_scatter(shape, request, counts, store(Kc), store(Vc), store)
+        reused, _, _ = reused_slots(request.segments, counts)
+        keep = np.setdiff1d(slots, reused)
+        h, K, V = layer_forward(shape, W, h, slots, positions_of(request, slots), K, V, store, kv_rows=keep)
+    return h
+
+
+def sensitivity_profile(shape, weights, head, samples, steps, store):
+    """S[i, j] = mean over samples of MSE(z_orig, z_reuse(i, steps[j])) (Eq. 5), steps on the k/500 grid.
+
+    Each sample is a dict:
+      cache_request, cache_emb   the prompt the cache is built under (replacement text | image) and its rows
+      request, emb               the evaluated prompt (text | image | answer); its image segments point into
+                                 the cache (old_pos = position under the cache prompt, cache_row)
+      answer_rows                slots whose output scores are compared (the decoding text)
+    Phases (Sec. 3.2): (1) full prefill of the cache prompt, its image K/V per layer are the cache;
+    (2) full prefill of the evaluated prompt gives z_orig; (3) for every layer i and step k the pass
+    of profile_prefill gives z_reuse(i, k).  MSE = mean over answer rows and vocabulary of the squared
+    score difference.
+    """
+    L = len(weights)
+    out = np.zeros((L, len(steps)), dtype=np.float64)
+    for smp in samples:
+        creq = smp["cache_request"]
+        full_c = full_prefill(shape, weights, smp["cache_emb"], creq, store)
+        img = np.concatenate([g.start + np.arange(g.length) for g in creq.segments if g.is_image])
+        cache = [(full_c[l]["K"][img], full_c[l]["V"][img]) for l in range(L)]
+        req = smp["request"]
+        rows = np.asarray(smp["answer_rows"], dtype=np.int64)
+        z_orig = first_token_logits(shape, head, full_prefill(shape, weights, smp["emb"], req, store)[-1]["h"][rows], store)
+        for i in range(L):
+            for j, k in enumerate(steps):
+                counts = image_counts(req.segments, k=int(k))
+                h = profile_prefill(shape, weights, smp["emb"], req, i, counts, cache, store)
+                z = first_token_logits(shape, head, h[rows], store)
+                out[i, j] += np.mean((z - z_orig) ** 2)
+    return out / max(len(samples), 1)
 
 
 # ----------------------------------------------------------------------------------------------

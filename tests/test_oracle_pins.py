@@ -756,3 +756,64 @@ def test_full_prefill_moe_layer_vs_transformers():
         ref = ref[0].numpy() if ref.dim() == 3 else ref.numpy()
     got = orc.full_prefill(shape, [W], emb, req, orc.store_exact)[0]["h"]
     np.testing.assert_allclose(got, ref, atol=2e-6, rtol=0)
+
+
+# ---- layer-wise sensitivity measurement (Sec. 3.2, Eq. 5) --------------------------------------
+
+def profile_setup(L=2, same_prompt=False, shift=5):
+    shape = dataclasses.replace(syn.SHAPES["tiny"], L=L)
+    W = [syn.layer_weights(shape, 61, l) for l in range(L)]
+    head = syn.head_weights(shape, 61)
+    smp = syn.profile_sample(shape, 62, t_cache_text=9 + shift, t_text=9, t_image=40, t_answer=6)
+    if same_prompt:     # the cache is built under the evaluated prompt's own text
+        smp = dict(smp, cache_emb=smp["emb"][:9 + 40].copy(),
+                   cache_request=syn.Request([syn.Segment(0, 9, False), syn.Segment(9, 40, True, 9, 0)], 0),
+                   request=syn.Request([syn.Segment(0, 9, False), syn.Segment(9, 40, True, 9, 0), syn.Segment(49, 6, False)], 0))
+    return shape, W, head, smp
+
+
+def test_sensitivity_is_zero_when_the_cache_matches():
+    """A cache built under the same text and positions holds exactly the keys/values a forward pass computes,
+    so no layer and no rate changes the scores."""
+    shape, W, head, smp = profile_setup(same_prompt=True)
+    S = orc.sensitivity_profile(shape, W, head, [smp], [0, 100, 500], orc.store_exact)
+    assert S.shape == (2, 3)
+    np.testing.assert_allclose(S, 0.0, atol=1e-24)
+
+
+def test_sensitivity_mismatched_cache():
+    shape, W, head, smp = profile_setup(L=3)
+    steps = [0, 150, 500]
+    S = orc.sensitivity_profile(shape, W, head, [smp], steps, orc.store_exact)
+    assert np.all(S[:, 0] > 1e-10)                      # pure reuse of a mismatched cache costs something
+    np.testing.assert_allclose(S[:, 0], S[0, 0], rtol=1e-12)      # rate 0: the layer index is immaterial
+    # The first layer's keys/values of an image do not depend on the prompt (they come from the image rows
+    # alone, re-rotated to the new position), so recomputing there changes nothing ...
+    np.testing.assert_allclose(S[0], S[0, 0], rtol=1e-9)
+    # ... deeper layers do depend on it, and recomputing ALL image tokens in the last layer restores the scores
+    # only if no other layer is mismatched: not so here (layer 1 still is), but it must help
+    assert S[2, 2] < S[2, 0] and S[1, 2] != pytest.approx(S[1, 0], rel=1e-3)
+    # the mean over samples: the same sample twice gives the same table
+    np.testing.assert_allclose(orc.sensitivity_profile(shape, W[:2], head, [smp, smp], steps, orc.store_exact),
+                               orc.sensitivity_profile(shape, W[:2], head, [smp], steps, orc.store_exact), rtol=1e-12)
+
+
+def test_sensitivity_one_and_two_layer_models():
+    """One layer: its cached image keys/values equal the fresh ones, every entry is zero.  Two layers: only layer 1
+    is mismatched, so recomputing all image tokens there is the original forward pass (S = 0).  And on the text
+    rows the measurement pass of a one-layer model is the fast path (image rows' outputs feed nothing)."""
+    shape, W, head, smp = profile_setup(L=1)
+    S = orc.sensitivity_profile(shape, W, head, [smp], [0, 500], orc.store_exact)
+    np.testing.assert_allclose(S, 0.0, atol=1e-24)
+    shape2, W2, head2, smp2 = profile_setup(L=2)
+    S2 = orc.sensitivity_profile(shape2, W2, head2, [smp2], [0, 250, 500], orc.store_exact)
+    assert S2[1, 0] > 1e-10 and S2[1, 2] < 1e-24 and 0 < S2[1, 1]
+    req = smp["request"]
+    full_c = orc.full_prefill(shape, W, smp["cache_emb"], smp["cache_request"], orc.store_exact)
+    img = np.arange(14, 54)
+    cache = [(full_c[0]["K"][img], full_c[0]["V"][img])]
+    for k in (0, 120):
+        counts = orc.image_counts(req.segments, k=k)
+        h_prof = orc.profile_prefill(shape, W, smp["emb"], req, 0, counts, cache, orc.store_exact)
+        sel = orc.selective_prefill(shape, W, smp["emb"], req, [counts], cache, orc.store_exact)[0]
+        np.testing.assert_allclose(h_prof[sel["slots"]][-6:], sel["h"][-6:], atol=1e-12)

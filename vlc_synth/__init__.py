@@ -8,8 +8,8 @@ two sides see identical data without sharing any computation.
 """
 from .workloads import (Shape, Segment, Request, Workload, SHAPES, make_workload,
                         layer_weights, head_weights, grid_positions, embedding_rows, cached_kv,
-                        sensitivity_table, normal_f32, WEIGHT_NAMES)
+                        sensitivity_table, normal_f32, WEIGHT_NAMES, profile_sample)
 
 __all__ = ["Shape", "Segment", "Request", "Workload", "SHAPES", "make_workload",
            "layer_weights", "head_weights", "grid_positions", "embedding_rows", "cached_kv", "sensitivity_table",
-           "normal_f32", "WEIGHT_NAMES"]
+           "normal_f32", "WEIGHT_NAMES", "profile_sample"]

@@ -362,6 +362,23 @@ def embedding_rows(wl: Workload) -> np.ndarray:
     return emb
 
 
+def profile_sample(shape: Shape, seed: int, t_cache_text: int, t_text: int, t_image: int, t_answer: int) -> dict:
+    """One sample of the layer-wise sensitivity measurement: an image that was cached under a prompt
+    (t_cache_text text rows | image) and is evaluated under another one (t_text text rows | image |
+    t_answer answer rows).  Text rows: rows of a 1024-row N(0, text_scale^2) table at random ids
+    (different ids for the two prompts); image rows N(0, 1), the same under both prompts.  1-D positions."""
+    H = shape.H
+    rng = np.random.default_rng([seed, 70])
+    table = normal_f32([seed, 71], 1024 * H, shape.text_scale).reshape(1024, H)
+    image = normal_f32([seed, 72], t_image * H).reshape(t_image, H)
+    cache_emb = np.concatenate([table[rng.integers(0, 1024, size=t_cache_text)], image])
+    emb = np.concatenate([table[rng.integers(0, 1024, size=t_text)], image, table[rng.integers(0, 1024, size=t_answer)]])
+    cache_request = Request(_layout([("text", t_cache_text), ("image", t_image, t_cache_text, 0)]), 0)
+    request = Request(_layout([("text", t_text), ("image", t_image, t_cache_text, 0), ("text", t_answer)]), 0)
+    return {"cache_request": cache_request, "cache_emb": cache_emb, "request": request, "emb": emb,
+            "answer_rows": np.arange(t_text + t_image, t_text + t_image + t_answer)}
+
+
 def cached_kv(wl: Workload, layer: int):
     """Cached image K and V pools of one layer, float32 [cache_rows, Hkv, D], N(0, 1)."""
     sh = wl.shape
