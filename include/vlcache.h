@@ -71,6 +71,18 @@ int vlc_version(void);
 int vlc_plan_layer_rates(int L, int G, const double* sens, int64_t budget_steps, int32_t* k_out);
 
 /*
+ * The same problem (Eq. 6-9) with moves that raise a whole run of equal layers.  Sec. 3.2 notes that
+ * some layers gain nothing from recomputation, yet Eq. 8 keeps every deeper layer at or below them: with
+ * flat scores in the shallow layers (the first layer's always are - its cached keys/values do not depend
+ * on the prompt) the one-step greedy above stops at zero.  Here a move raises layers a..j by one step,
+ * a..j-1 being exactly the layers before j at j's level; it costs j-a+1 steps and gains the sum of their
+ * score drops (summed in layer order).  Among affordable moves with positive gain the largest gain per
+ * step wins (compared as gain * other_cost > other_gain * cost; equal: the smallest j).  Arguments,
+ * errors and uniqueness as vlc_plan_layer_rates.
+ */
+int vlc_plan_layer_rates_blocks(int L, int G, const double* sens, int64_t budget_steps, int32_t* k_out);
+
+/*
  * One run of consecutive slots of a request inside the packed K/V of a batch.
  *   start      first packed slot of the run
  *   length     number of tokens
@@ -215,7 +227,9 @@ typedef struct {
   int64_t n_in;                 /* rows of h_in (the previous layer's output rows) */
   int64_t n;                    /* rows recomputed by this layer */
   const int32_t* map;           /* device [n]: row of h_in each recomputed row comes from */
-  const int32_t* slot;          /* device [n]: packed K/V slot of each row (scatter target) */
+  const int32_t* slot;          /* device [n]: packed K/V slot of each row (scatter target); a negative entry:
+                                   the row is computed and attends, but its fresh k, v are not stored - what the
+                                   cache holds at its slot stays (used by the sensitivity measurement, Sec. 3.2) */
   const int32_t* pos;           /* device [n]: position id of each row */
   const int32_t* row_kv_start;  /* device [n] */
   const int32_t* row_kv_len;    /* device [n] */
@@ -308,6 +322,17 @@ int64_t vlc_first_token_workspace_bytes(int H, int64_t n_req, int dtype);
 int vlc_first_token(const void* h, const int32_t* rows, int64_t n_req, int H, int64_t vocab, float eps,
                     const void* w_norm, const void* w_out, float* logits, int32_t* token, void* workspace,
                     int64_t workspace_bytes, int dtype, void* stream);
+
+/*
+ * Mean squared difference of two float arrays, the error measure of the layer-wise sensitivity
+ * score S_i(r) = E MSE(z_orig, z_reuse) (Sec. 4.1, Eq. 5): out[0] = sum_i (a[i] - b[i])^2 / n,
+ * accumulated in double.  a, b: device float [n]; out: device double [1]; workspace: device, at
+ * least vlc_mean_squared_error_workspace_bytes() bytes, 8-byte aligned, caller-owned.
+ * Errors: VLC_ERR_SHAPE (n <= 0), VLC_ERR_NULL, VLC_ERR_WORKSPACE, VLC_ERR_HIP.  Enqueues two kernels.
+ */
+int64_t vlc_mean_squared_error_workspace_bytes(void);
+int vlc_mean_squared_error(const float* a, const float* b, int64_t n, double* out, void* workspace,
+                           int64_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

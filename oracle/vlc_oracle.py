@@ -103,6 +103,52 @@ def plan_layer_rates(sens, budget_steps, G=None):
     return np.asarray(k, dtype=np.int32)
 
 
+def plan_layer_rates_blocks(sens, budget_steps, G=None):
+    """Greedy allocation as plan_layer_rates, with moves that raise a whole run of equal layers at once.
+
+    reading: Sec. 3.2 observes that some layers gain nothing from recomputation, while Eq. 8 forces a
+    deeper layer's rate below every shallower one's.  When the shallow layers' scores are flat (the first
+    layer's always are: its cached keys/values do not depend on the prompt) the one-step greedy cannot
+    raise any deeper layer and stops at zero.  The paper does not say how its greedy handles this; taken
+    here as the smallest change that does: a move raises by one step the layers a..j, where a..j-1 are
+    exactly the layers before j that sit at j's level (they have to rise with it, Eq. 8); it costs
+    j-a+1 steps and gains the sum of the layers' score drops; among affordable moves with positive gain
+    the largest gain per step wins (equal: the smallest j).  With a = j this is the one-step move.
+    """
+    sens = np.asarray(sens, dtype=np.float64)
+    L = sens.shape[0]
+    if G is None:
+        G = sens.shape[1] - 1
+    S = [[float(v) for v in row] for row in sens]
+    k = [0] * L
+    used = 0
+    while used < budget_steps:
+        best_j, best_a, best_gain, best_cost = -1, 0, 0.0, 1
+        for j in range(L):
+            if k[j] >= G:
+                continue
+            a = j
+            while a > 0 and k[a - 1] == k[j]:
+                a -= 1
+            cost = j - a + 1
+            if used + cost > budget_steps:
+                continue
+            gain = 0.0
+            for i in range(a, j + 1):
+                gain = gain + (S[i][k[i]] - S[i][k[i] + 1])
+            if not gain > 0.0:
+                continue
+            # gain / cost > best_gain / best_cost, without dividing
+            if best_j < 0 or gain * best_cost > best_gain * cost:
+                best_j, best_a, best_gain, best_cost = j, a, gain, cost
+        if best_j < 0:
+            break
+        for i in range(best_a, best_j + 1):
+            k[i] += 1
+        used += best_cost
+    return np.asarray(k, dtype=np.int32)
+
+
 def budget_steps_from_mean_rate(mean_rate_bp, L):
     """reading: Eq. 7 bounds the *sum* of rates while the tables quote a *mean* rate; the budget
     is given as a mean rate in basis points and converted to a total number of grid steps:

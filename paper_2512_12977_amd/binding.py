@@ -60,6 +60,7 @@ def lib():
         L.vlc_layer_workspace_bytes.restype = C.c_int64
         L.vlc_layer_workspace_bytes.argtypes = [C.c_void_p, C.c_int64]
         L.vlc_plan_layer_rates.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
+        L.vlc_plan_layer_rates_blocks.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
         L.vlc_plan_token_indices.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int64] + [C.c_void_p] * 6
         L.vlc_plan_reuse_rows.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int64] + [C.c_void_p] * 4
         L.vlc_gather_rows.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_void_p]
@@ -69,6 +70,8 @@ def lib():
         L.vlc_sparse_q_attention.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_float,
                                                                 C.c_void_p, C.c_int, C.c_void_p]
         L.vlc_layer_workspace_layout.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
+        L.vlc_mean_squared_error_workspace_bytes.restype = C.c_int64
+        L.vlc_mean_squared_error.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.vlc_layer_forward.argtypes = [C.c_void_p] * 8 + [C.c_int64, C.c_void_p]
         L.vlc_layer_forward_timed.argtypes = [C.c_void_p] * 8 + [C.c_int64, C.c_void_p, C.c_void_p]
         L.vlc_first_token_workspace_bytes.restype = C.c_int64
@@ -128,6 +131,14 @@ def vlc_plan_layer_rates(sens: np.ndarray, budget_steps: int) -> np.ndarray:
     L, G1 = sens.shape
     k = np.zeros(L, dtype=np.int32)
     _check(lib().vlc_plan_layer_rates(L, G1 - 1, sens.ctypes.data, int(budget_steps), k.ctypes.data))
+    return k
+
+
+def vlc_plan_layer_rates_blocks(sens: np.ndarray, budget_steps: int) -> np.ndarray:
+    sens = np.ascontiguousarray(sens, dtype=np.float64)
+    L, G1 = sens.shape
+    k = np.zeros(L, dtype=np.int32)
+    _check(lib().vlc_plan_layer_rates_blocks(L, G1 - 1, sens.ctypes.data, int(budget_steps), k.ctypes.data))
     return k
 
 
@@ -255,3 +266,14 @@ def vlc_first_token(h, rows, eps: float, w_norm, w_out, logits, token, workspace
     _check(lib().vlc_first_token(_dev(h), _dev(rows), n_req, H, vocab, float(eps), _dev(w_norm), _dev(w_out),
                                  _dev(logits), _dev(token), _dev(workspace),
                                  workspace.numel() * workspace.element_size(), _dtype_code(h), _stream(stream)))
+
+
+def vlc_mean_squared_error(a, b, out, workspace, stream=None) -> None:
+    """a, b float32 device tensors of equal size; out float64 [1]; workspace >= vlc_mean_squared_error_workspace_bytes()."""
+    assert a.numel() == b.numel()
+    _check(lib().vlc_mean_squared_error(_dev(a), _dev(b), a.numel(), _dev(out), _dev(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def vlc_mean_squared_error_workspace_bytes() -> int:
+    return int(lib().vlc_mean_squared_error_workspace_bytes())

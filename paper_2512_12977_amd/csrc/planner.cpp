@@ -34,6 +34,45 @@ extern "C" int vlc_plan_layer_rates(int L, int G, const double* sens, int64_t bu
   return VLC_OK;
 }
 
+extern "C" int vlc_plan_layer_rates_blocks(int L, int G, const double* sens, int64_t budget_steps,
+                                           int32_t* k_out) {
+  if (!sens || !k_out) return fail(VLC_ERR_NULL, "vlc_plan_layer_rates_blocks: NULL pointer");
+  if (L <= 0 || G <= 0 || G > VLC_RATE_GRID)
+    return fail(VLC_ERR_SHAPE, "vlc_plan_layer_rates_blocks: L=%d G=%d out of range", L, G);
+  if (budget_steps < 0) return fail(VLC_ERR_SHAPE, "vlc_plan_layer_rates_blocks: negative budget");
+  const int64_t stride = (int64_t)G + 1;
+  for (int i = 0; i < L; ++i) k_out[i] = 0;
+  int64_t used = 0;
+  while (used < budget_steps) {
+    int best_j = -1, best_a = 0, best_cost = 1;
+    double best_gain = 0.0;
+    for (int j = 0; j < L; ++j) {
+      if (k_out[j] >= G) continue;                          // grid ceiling (Eq. 9)
+      int a = j;                                            // layers a..j-1 sit at j's level: they rise with it (Eq. 8)
+      while (a > 0 && k_out[a - 1] == k_out[j]) --a;
+      const int cost = j - a + 1;
+      if (used + cost > budget_steps) continue;             // Eq. 7
+      volatile double gain = 0.0;                           // every operation a plain IEEE one, in layer order
+      for (int i = a; i <= j; ++i) {
+        volatile double drop = sens[i * stride + k_out[i]] - sens[i * stride + k_out[i] + 1];
+        gain = gain + drop;
+      }
+      if (!(gain > 0.0)) continue;
+      volatile double lhs = gain * (double)best_cost, rhs = best_gain * (double)cost;
+      if (best_j < 0 || lhs > rhs) {                        // more gain per step; equal: the smaller j stays
+        best_j = j;
+        best_a = a;
+        best_gain = gain;
+        best_cost = cost;
+      }
+    }
+    if (best_j < 0) break;
+    for (int i = best_a; i <= best_j; ++i) k_out[i] += 1;
+    used += best_cost;
+  }
+  return VLC_OK;
+}
+
 namespace {
 
 int check_segments(int n_seg, const vlc_segment* seg, const char* who) {

@@ -237,7 +237,9 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
   }
   const float* r = qkv + row * ((int64_t)heads * D) + c * VEC;
   uint4* qo = q_out + row * ((int64_t)Hq * HEAD_CHUNKS) + c;
-  const int64_t dst = (int64_t)slot[row] * ((int64_t)Hkv * HEAD_CHUNKS) + c;
+  const int row_slot = slot[row];
+  const bool keep_kv = row_slot >= 0;      // a negative slot: the row is computed, its k and v are not stored
+  const int64_t dst = (int64_t)(keep_kv ? row_slot : 0) * ((int64_t)Hkv * HEAD_CHUNKS) + c;
 #pragma unroll
   for (int j = 0; j < HB; ++j) {
     const int h = hb * HB + j;
@@ -277,8 +279,10 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
       hi[i] = b.x; hi[i + 1] = b.y; hi[i + 2] = b.z; hi[i + 3] = b.w;
     }
     if (h >= Hq + Hkv) {
-      v_cache[dst + (h - Hq - Hkv) * HEAD_CHUNKS] = Chunk<T>::pack(lo);
-      v_cache[dst + (h - Hq - Hkv) * HEAD_CHUNKS + CH] = Chunk<T>::pack(hi);
+      if (keep_kv) {
+        v_cache[dst + (h - Hq - Hkv) * HEAD_CHUNKS] = Chunk<T>::pack(lo);
+        v_cache[dst + (h - Hq - Hkv) * HEAD_CHUNKS + CH] = Chunk<T>::pack(hi);
+      }
       continue;
     }
     if (w_qn) {   // RMSNorm over the head, float; every lane of the head's CH-lane group is here
@@ -306,8 +310,10 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
       qo[h * HEAD_CHUNKS] = plo;
       qo[h * HEAD_CHUNKS + CH] = phi;
     } else {
-      k_cache[dst + (h - Hq) * HEAD_CHUNKS] = plo;
-      k_cache[dst + (h - Hq) * HEAD_CHUNKS + CH] = phi;
+      if (keep_kv) {
+        k_cache[dst + (h - Hq) * HEAD_CHUNKS] = plo;
+        k_cache[dst + (h - Hq) * HEAD_CHUNKS + CH] = phi;
+      }
     }
   }
 }
@@ -709,7 +715,60 @@ int launch_argmax_rows(const float* x, int64_t rows, int64_t cols, int32_t* out,
   return VLC_OK;
 }
 
+// Mean squared difference of two float arrays: per-workgroup partial sums in double, then one workgroup.
+namespace {
+constexpr int kMseBlocks = 1024;
+__global__ __launch_bounds__(256) void sqdiff_partial_kernel(const float* __restrict__ a, const float* __restrict__ b,
+                                                             int64_t n, double* __restrict__ part) {
+  double s = 0.0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const double d = (double)a[i] - (double)b[i];
+    s += d * d;
+  }
+  __shared__ double sh[256];
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) part[blockIdx.x] = sh[0];
+}
+__global__ __launch_bounds__(256) void sqdiff_final_kernel(const double* __restrict__ part, int blocks, int64_t n,
+                                                           double* __restrict__ out) {
+  double s = 0.0;
+  for (int i = threadIdx.x; i < blocks; i += 256) s += part[i];
+  __shared__ double sh[256];
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[0] = sh[0] / (double)n;
+}
+}  // namespace
+
 }  // namespace vlc
+
+extern "C" int64_t vlc_mean_squared_error_workspace_bytes(void) { return vlc::kMseBlocks * 8; }
+
+extern "C" int vlc_mean_squared_error(const float* a, const float* b, int64_t n, double* out, void* workspace,
+                                      int64_t workspace_bytes, void* stream) {
+  if (n <= 0) return vlc::fail(VLC_ERR_SHAPE, "vlc_mean_squared_error: n=%lld", (long long)n);
+  if (!a || !b || !out || !workspace) return vlc::fail(VLC_ERR_NULL, "vlc_mean_squared_error: NULL pointer");
+  if (workspace_bytes < vlc::kMseBlocks * 8 || ((uintptr_t)workspace & 7))
+    return vlc::fail(VLC_ERR_WORKSPACE, "vlc_mean_squared_error: workspace of %lld bytes, %d needed (8-byte aligned)",
+                     (long long)workspace_bytes, vlc::kMseBlocks * 8);
+  const int blocks = (int)((n + 255) / 256 < vlc::kMseBlocks ? (n + 255) / 256 : vlc::kMseBlocks);
+  hipLaunchKernelGGL(vlc::sqdiff_partial_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, a, b, n,
+                     static_cast<double*>(workspace));
+  VLC_CHECK_LAUNCH("sqdiff_partial");
+  hipLaunchKernelGGL(vlc::sqdiff_final_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream,
+                     static_cast<const double*>(workspace), blocks, n, out);
+  VLC_CHECK_LAUNCH("sqdiff_final");
+  return VLC_OK;
+}
 
 // ---------------------------------------------------------------------------------------------
 // C ABI entry points of the streaming kernels

@@ -45,6 +45,29 @@ def test_planner_bit_exact_vs_oracle():
         np.testing.assert_array_equal(vlc.vlc_plan_layer_rates(sens, B), orc.plan_layer_rates(sens, B))
 
 
+def test_block_planner_bit_exact_vs_oracle():
+    rng = np.random.default_rng(3)
+    for trial in range(40):
+        L, G = int(rng.integers(1, 30)), int(rng.integers(1, 60))
+        if trial % 4 == 0:
+            sens = rng.random((L, G + 1))
+        elif trial % 4 == 1:
+            sens = syn.sensitivity_table(L, G, trial)
+        elif trial % 4 == 2:   # many exact ties
+            sens = np.round(rng.random((L, G + 1)) * 4) / 4
+        else:                  # flat first layers, the case the runs are for
+            sens = syn.sensitivity_table(L, G, trial)
+            sens[:max(1, L // 4)] = 1.0
+        B = int(rng.integers(0, L * G + 3))
+        np.testing.assert_array_equal(vlc.vlc_plan_layer_rates_blocks(sens, B), orc.plan_layer_rates_blocks(sens, B))
+    sens = syn.sensitivity_table(28, 150, 1)
+    sens[0] = sens[0, 0]
+    np.testing.assert_array_equal(vlc.vlc_plan_layer_rates_blocks(sens, 700), orc.plan_layer_rates_blocks(sens, 700))
+    assert vlc.vlc_plan_layer_rates(sens, 700).sum() == 0 and vlc.vlc_plan_layer_rates_blocks(sens, 700).sum() > 600
+    with pytest.raises(vlc.VlcError):
+        vlc.vlc_plan_layer_rates_blocks(sens, -1)
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
 def test_token_indices_bit_exact_vs_oracle(name):
     wl = syn.make_workload(name)

@@ -642,6 +642,72 @@ def test_planner_weights_early_layers_on_benchmark_table():
     assert k[0] > k[-1]
 
 
+def objective(sens, k):
+    return sum(sens[i][k[i]] for i in range(len(k)))
+
+
+def test_block_planner_feasible_and_never_worse_than_starting_point():
+    rng = np.random.default_rng(1)
+    for trial in range(30):
+        L, G = int(rng.integers(1, 12)), int(rng.integers(1, 20))
+        sens = rng.random((L, G + 1))
+        B = int(rng.integers(0, L * G + 5))
+        k = orc.plan_layer_rates_blocks(sens, B)
+        assert feasible(k, B, G)
+        assert objective(sens, k) <= objective(sens, [0] * L) + 1e-15      # every move has positive gain
+
+
+def test_block_planner_closed_forms():
+    L, G = 5, 8
+    row = 1.0 / (1.0 + np.arange(G + 1))
+    same = np.tile(row, (L, 1))
+    assert list(orc.plan_layer_rates_blocks(same, 0)) == [0] * L
+    assert list(orc.plan_layer_rates_blocks(same, L * G + 9)) == [G] * L
+    assert list(orc.plan_layer_rates_blocks(np.ones((L, G + 1)), 17)) == [0] * L
+    # identical convex rows: gain per step of a run equals that of its first layer alone, ties go to the
+    # smallest j, so steps are dealt exactly as by the one-step greedy
+    for B in (1, 4, 5, 6, 23, 39):
+        np.testing.assert_array_equal(orc.plan_layer_rates_blocks(same, B), orc.plan_layer_rates(same, B))
+    # A first layer that gains nothing (its cached keys/values are exact) blocks the one-step greedy at zero;
+    # runs carry it along.  Layers 1, 2 gain 1.0 and 0.6 per step, layer 0 nothing: the run 0..1 gains 0.5 per
+    # step, the run 0..2 gains 1.6 / 3 per step > 0.5, so all three rise together while the budget lasts.
+    flat0 = np.stack([np.zeros(G + 1), -1.0 * np.arange(G + 1), -0.6 * np.arange(G + 1)])
+    assert list(orc.plan_layer_rates(flat0, 12)) == [0, 0, 0]
+    assert list(orc.plan_layer_rates_blocks(flat0, 12)) == [4, 4, 4]
+    assert list(orc.plan_layer_rates_blocks(flat0, 14)) == [5, 5, 4]      # 2 steps left: the run 0..1
+    assert list(orc.plan_layer_rates_blocks(flat0, 13)) == [4, 4, 4]      # 1 step left: layer 0 alone gains nothing
+
+
+def test_block_planner_reaches_the_exhaustive_optimum_where_the_one_step_greedy_cannot():
+    """Tables whose first layer is flat and whose other layers are convex with gains ordered by depth: the
+    optimum raises layer 0 only as far as the layers behind it need; enumeration over every monotone sequence
+    (L <= 4, G <= 5) agrees with the run-based greedy whenever the budget is a multiple of what a full run costs."""
+    rng = np.random.default_rng(7)
+    hits = 0
+    for trial in range(10):
+        L, G = int(rng.integers(2, 5)), int(rng.integers(2, 6))
+        w = np.sort(rng.random(L - 1) + 0.1)[::-1] * 3.0
+        sens = np.concatenate([np.zeros((1, G + 1)), w[:, None] / (1.0 + np.arange(G + 1))[None, :]])
+        for B in range(0, L * G + 1):
+            k = orc.plan_layer_rates_blocks(sens, B)
+            assert feasible(k, B, G)
+            best = exhaustive_optimum(sens, B)
+            val = objective(sens, k)
+            assert val >= best - 1e-12
+            assert objective(sens, orc.plan_layer_rates(sens, B)) == objective(sens, [0] * L)   # stuck at zero
+            if B >= 2:
+                assert val < objective(sens, [0] * L)
+            hits += abs(val - best) < 1e-12
+    assert hits > 60           # optimal in most cases; the greedy is an approximation (Sec. 4.1)
+    # on convex tables ordered by depth (no flat layer) both greedies solve the problem exactly
+    for trial in range(8):
+        L, G = int(rng.integers(2, 5)), int(rng.integers(2, 6))
+        w = np.sort(rng.random(L) + 0.1)[::-1] * 3.0
+        sens = w[:, None] / (1.0 + np.arange(G + 1))[None, :]
+        for B in range(0, L * G + 1, 3):
+            assert abs(objective(sens, orc.plan_layer_rates_blocks(sens, B)) - exhaustive_optimum(sens, B)) < 1e-12
+
+
 # ---- mixture-of-experts MLP (Qwen3-VL-30B-A3B-shaped layer) -----------------------------------
 
 def test_route_top_k_by_hand():
