@@ -78,10 +78,13 @@ __device__ __forceinline__ int fswz(int row) { return (row & 7) ^ ((row >> 3) & 
 // each k-step; issued this way the loads are tracked only by the explicit vmcnt waits below (the
 // loop contains no other vector-memory instruction).  M0 holds the LDS address; the compiler never
 // keeps a live value in M0 across statements (it is reserved and written right before each use).
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_byte_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+// The global address is a wavefront-uniform base (scalar registers) plus a 32-bit byte offset per lane: the lane
+// offsets never change, the base moves along k with scalar adds, so the k-loop holds no vector address arithmetic
+// (a vector instruction of a wavefront does not overlap with its own MFMAs).
+__device__ __forceinline__ void dma16(const void* uniform_base, uint32_t lane_byte_off, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
-               : "s"(lds_byte_addr), "v"(gptr)
+               : "s"(lds_byte_addr), "v"(lane_byte_off), "s"(uniform_base)
                : "memory");
 }
 
@@ -148,19 +151,23 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   const int kt_end = (EPI == EPI_PARTIAL || tail_block >= 0) ? min(K / BK, kt_begin + kt_per_split) : K / BK;
   const int KT = kt_end - kt_begin;
 
-  // ---- per-lane global source of each of this wavefront's loads (k-tile kt_begin) ---------------
-  const uint16_t* a_src[A_INSTR];
-  const uint16_t* w_src[W_INSTR];
+  // ---- global source of each of this wavefront's loads: a uniform base (first row of the tile, k-tile
+  // kt_begin) and a per-lane byte offset.  Rows fetched through amap are offsets from A itself.
+  uint32_t a_lane[A_INSTR], w_lane[W_INSTR];
+  const bool mapped = GROUPED && amap != nullptr;
+  const uint16_t* a_base = A + (mapped ? (int64_t)0 : (int64_t)m0 * lda) + (int64_t)kt_begin * BK;
+  const uint16_t* w_base = W + (int64_t)n0 * K + (int64_t)kt_begin * BK;
 #pragma unroll
   for (int i = 0; i < A_INSTR; ++i) {
     const int p = (wave * A_INSTR + i) * 64 + lane;        // LDS chunk this lane fills
     const int r = p >> 3, c = (p & 7) ^ fswz(r);
     int gr = m0 + r;
     gr = gr < M ? gr : M - 1;                              // ragged tail: re-read the last row
+    int64_t rel = gr - m0;
     if constexpr (GROUPED) {
-      if (amap) gr = amap[gr];
+      if (mapped) rel = amap[gr];
     }
-    a_src[i] = A + (int64_t)gr * lda + (int64_t)kt_begin * BK + c * 8;
+    a_lane[i] = (uint32_t)((rel * lda + c * 8) * 2);
   }
 #pragma unroll
   for (int i = 0; i < W_INSTR; ++i) {
@@ -171,7 +178,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
     else gr = n0 + r;
     const int limit = (EPI == EPI_SWIGLU) ? 2 * N : N;
     gr = gr < limit ? gr : limit - 1;
-    w_src[i] = W + (int64_t)gr * K + (int64_t)kt_begin * BK + c * 8;
+    w_lane[i] = (uint32_t)(((int64_t)(gr - n0) * K + c * 8) * 2);
   }
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
   // LDS byte address of this wavefront's i-th load of a stage (A part first, then W)
@@ -185,10 +192,11 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   int k_rot = 0;
   if constexpr (GROUPED) k_rot = (tn * 5 + tm * 3) % KT;
 #define VLC_KT(kt_) (GROUPED ? ((kt_) + k_rot < KT ? (kt_) + k_rot : (kt_) + k_rot - KT) : (kt_))
-#define VLC_SRC(kt_, i_) ((i_) < A_INSTR ? a_src[(i_) < A_INSTR ? (i_) : 0] + VLC_KT(kt_) * BK                \
-                                         : w_src[(i_) >= A_INSTR ? (i_) - A_INSTR : 0] + VLC_KT(kt_) * BK)
-#define VLC_ISSUE(kt_, stage_)                                                                               \
-  _Pragma("unroll") for (int i = 0; i < LOADS; ++i) dma16(VLC_SRC(kt_, i), VLC_LDS_DST(stage_, i));
+#define VLC_DMA(kt_, i_, stage_)                                                                              \
+  dma16(((i_) < A_INSTR ? a_base : w_base) + VLC_KT(kt_) * BK,                                                \
+        (i_) < A_INSTR ? a_lane[(i_) < A_INSTR ? (i_) : 0] : w_lane[(i_) >= A_INSTR ? (i_) - A_INSTR : 0],     \
+        VLC_LDS_DST(stage_, i_))
+#define VLC_ISSUE(kt_, stage_) _Pragma("unroll") for (int i = 0; i < LOADS; ++i) VLC_DMA(kt_, i, stage_);
 
   // fragment positions inside a stage (chunk units) for every 16-wide k-step
   int w_off[NT][KS], a_off[MT][KS];
@@ -224,9 +232,9 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   constexpr int TG = KS * G;                   // groups per k-tile
   constexpr int NF = NT + MT;                  // fragments per k-step
   static_assert(NT * MT % MPG == 0, "wavefront tile must hold whole groups of MFMA tiles");
-#define VLC_COMPUTE_TILE(kt_, WITH_LOADS, nkt_, nst_)                                                         \
+#define VLC_COMPUTE_TILE(cst_, WITH_LOADS, nkt_, nst_)                                                        \
   {                                                                                                           \
-    const u32x4* st_ = lds + ((kt_) % STAGES) * STAGE_CHUNKS;                                                 \
+    const u32x4* st_ = lds + (cst_) * STAGE_CHUNKS;                                                           \
     bf16x8 wf[2][NT], af[2][MT];                                                                              \
     _Pragma("unroll") for (int nt = 0; nt < NT; ++nt) wf[0][nt] = __builtin_bit_cast(bf16x8, st_[w_off[nt][0]]); \
     _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) af[0][mt] = __builtin_bit_cast(bf16x8, st_[a_off[mt][0]]); \
@@ -234,7 +242,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
       _Pragma("unroll") for (int g = 0; g < G; ++g) {                                                         \
         if (WITH_LOADS) {                                                                                     \
           _Pragma("unroll") for (int i = 0; i < LOADS; ++i)                                                   \
-            if (i * (TG / 2) / LOADS == ks * G + g) dma16(VLC_SRC(nkt_, i), VLC_LDS_DST(nst_, i));            \
+            if (i * (TG / 2) / LOADS == ks * G + g) VLC_DMA(nkt_, i, nst_);                                    \
         }                                                                                                     \
         if (ks + 1 < KS) {                                                                                    \
           _Pragma("unroll") for (int f = 0; f < NF; ++f) {                                                    \
@@ -260,19 +268,31 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   for (int s = 0; s < STAGES - 1; ++s)
     if (s < KT) { VLC_ISSUE(s, s) }
   int kt = 0;
+  if constexpr (STAGES == 2) {
+    // two k-tiles per trip, so that the stage every fragment address refers to is a constant of the code
+    // and the addresses of both stages stay in registers (no address arithmetic inside the loop)
+    for (; kt + 2 < KT; kt += 2) {
+      VLC_WAITCNT_VM(0);
+      __syncthreads();
+      VLC_COMPUTE_TILE(0, true, kt + 1, 1)
+      VLC_WAITCNT_VM(0);
+      __syncthreads();
+      VLC_COMPUTE_TILE(1, true, kt + 2, 0)
+    }
+  }
   for (; kt + STAGES - 1 < KT; ++kt) {   // steady state: k-tile kt+STAGES-1 is fetched while kt is consumed
     VLC_WAITCNT_VM((STAGES - 2) * LOADS);          // this wavefront's part of k-tile kt has landed
     __syncthreads();                               // everyone's part has; stage (kt-1)%STAGES is free
-    VLC_COMPUTE_TILE(kt, true, kt + STAGES - 1, (kt + STAGES - 1) % STAGES)
+    VLC_COMPUTE_TILE(kt % STAGES, true, kt + STAGES - 1, (kt + STAGES - 1) % STAGES)
   }
   for (; kt < KT; ++kt) {                // drain
     const int later = KT - 1 - kt;
     if (later >= 2) { VLC_WAITCNT_VM(2 * LOADS); } else if (later == 1) { VLC_WAITCNT_VM(LOADS); } else { VLC_WAITCNT_VM(0); }
     __syncthreads();
-    VLC_COMPUTE_TILE(kt, false, 0, 0)
+    VLC_COMPUTE_TILE(kt % STAGES, false, 0, 0)
   }
 #undef VLC_ISSUE
-#undef VLC_SRC
+#undef VLC_DMA
 #undef VLC_KT
 #undef VLC_LDS_DST
 #undef VLC_COMPUTE_TILE
