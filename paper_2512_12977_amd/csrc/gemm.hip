@@ -739,6 +739,9 @@ int launch_gemm_grouped(const void* A, int64_t lda, const int32_t* amap, const v
   if (dtype == VLC_BF16) {
     if (K % BK || N % 4 || lda % 8 || ldc % 4)
       return fail(VLC_ERR_SHAPE, "grouped gemm(bf16): K=%lld must be a multiple of %d, N, lda, ldc aligned", (long long)K, BK);
+    // 32-bit lane offsets: rows fetched through amap are offsets from A itself (amap values are below `rows`)
+    if ((amap ? rows : 256) * lda * 2 >= ((int64_t)1 << 31) || ((epilogue == EPI_SWIGLU ? N : 0) + 256) * K * 2 >= ((int64_t)1 << 31))
+      return fail(VLC_ERR_SHAPE, "grouped gemm(bf16): operand rows span more than 2 GiB");
     if (tile_rows == 256) {
       if (epilogue == EPI_SWIGLU)
         return launch_bf16_grouped<256, 256, 2, 2, 2, 1, EPI_SWIGLU>(A, lda, amap, W, w_stride, C, ldc, N, K, tiles, n_tiles, max_tiles, st);
@@ -774,6 +777,10 @@ int launch_gemm(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
     if (K % BK) return fail(VLC_ERR_SHAPE, "gemm(bf16): K=%lld must be a multiple of %d", (long long)K, BK);
     if (N % 4 || lda % 8 || ldc % 4 || (epilogue == EPI_RESIDUAL && ldr % 4))
       return fail(VLC_ERR_SHAPE, "gemm(bf16): N, lda, ldc, ldr must keep 8-byte (A: 16-byte) alignment");
+    // lane offsets of the loads are 32-bit byte offsets from the tile's first row (SwiGLU: up rows sit N rows on)
+    if (256 * lda * 2 >= ((int64_t)1 << 31) || ((epilogue == EPI_SWIGLU ? N : 0) + 256) * K * 2 >= ((int64_t)1 << 31))
+      return fail(VLC_ERR_SHAPE, "gemm(bf16): a tile's rows span more than 2 GiB (lda=%lld N=%lld K=%lld)",
+                  (long long)lda, (long long)N, (long long)K);
     switch (epilogue) {
       case EPI_BIAS: return dispatch_bf16<EPI_BIAS>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, deferred, st);
       case EPI_BIAS_F32: return dispatch_bf16<EPI_BIAS_F32>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, splitk_ws, splitk_ws_bytes, deferred, st);
