@@ -19,6 +19,13 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) {   // round to nearest
   u += 0x7fffu + ((u >> 16) & 1u);
   return u >> 16;
 }
+// two floats -> packed bf16 pair with the hardware conversion (round to nearest even), one instruction
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
 // ---------------------------------------------------------------------------------------------
@@ -366,8 +373,8 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
               make_float4(v[0], v[1], v[2], v[3]);
         } else {
           uint2 o;
-          o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-          o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+          o.x = pack_bf16x2(v[0], v[1]);
+          o.y = pack_bf16x2(v[2], v[3]);
           *reinterpret_cast<uint2*>(C + (int64_t)m * ldc + n) = o;
         }
       }
@@ -412,8 +419,8 @@ __global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float* __res
     *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + m * ldc + n) = s;
   } else {
     uint2 o;
-    o.x = f32_to_bf16(s.x) | (f32_to_bf16(s.y) << 16);
-    o.y = f32_to_bf16(s.z) | (f32_to_bf16(s.w) << 16);
+    o.x = pack_bf16x2(s.x, s.y);
+    o.y = pack_bf16x2(s.z, s.w);
     *reinterpret_cast<uint2*>(C + m * ldc + n) = o;
   }
 }
@@ -463,8 +470,8 @@ __global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restric
     *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + (int64_t)m * ldc + n) = s;
   } else {
     uint2 o;
-    o.x = f32_to_bf16(s.x) | (f32_to_bf16(s.y) << 16);
-    o.y = f32_to_bf16(s.z) | (f32_to_bf16(s.w) << 16);
+    o.x = pack_bf16x2(s.x, s.y);
+    o.y = pack_bf16x2(s.z, s.w);
     *reinterpret_cast<uint2*>(C + (int64_t)m * ldc + n) = o;
   }
 }
