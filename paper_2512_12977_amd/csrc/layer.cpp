@@ -223,11 +223,13 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
     ms.pair_pos = reinterpret_cast<int32_t*>(base + ws.moe_pos);
     void* y = base + ws.moe_y;
     const int tile_rows = vlc::gemm_group_tile_rows(pairs, E, s.dtype);
+    int r_splits = 0;    // > 0: the scores are still split-K partials, summed by the choice kernel
     rc = vlc::launch_gemm(n2, H, w->w_router, logits, E, n, E, H,
                           s.dtype == VLC_BF16 ? vlc::EPI_BIAS_F32 : vlc::EPI_BIAS, nullptr, nullptr, 0, nullptr,
-                          s.dtype, skw, ws.splitk_bytes, st);
+                          s.dtype, skw, ws.splitk_bytes, st, &r_splits);
     if (rc) return rc;
-    rc = vlc::launch_moe_route(logits, n, E, K, tile_rows, ms, st);
+    rc = vlc::launch_moe_route(r_splits > 0 ? static_cast<const float*>(skw) : logits, r_splits > 0 ? r_splits : 1,
+                               n * E, r_splits > 0 ? logits : nullptr, n, E, K, tile_rows, ms, st);
     if (rc) return rc;
     rc = vlc::launch_gemm_grouped(n2, H, ms.pair_row, w->w_gate_up, 2 * I * H, act, I, pairs, E, I, H,
                                   vlc::EPI_SWIGLU, ms.tiles, ms.n_tiles, tile_rows, s.dtype, st);

@@ -23,6 +23,7 @@ namespace {
 
 constexpr int kMaxExperts = 256;   // four scores per lane
 constexpr int kMaxTopK = 16;
+constexpr int64_t kSmallPlanPairs = 65536;   // up to here one workgroup groups the pairs
 
 __global__ __launch_bounds__(256) void zero_i32_kernel(int32_t* p, int n) {
   const int i = blockIdx.x * 256 + threadIdx.x;
@@ -37,7 +38,11 @@ __device__ __forceinline__ void better(float& bv, int& be, float v, int e) {
 }
 
 // one wavefront per row
-__global__ __launch_bounds__(256) void moe_route_kernel(const float* __restrict__ logits, int64_t n, int E, int K,
+// logits: `splits` float partial matrices [n, E] (split_stride floats apart) whose sum are the scores
+// (1: the scores themselves).  count == NULL: no ranks are taken (the single-workgroup plan does that).
+__global__ __launch_bounds__(256) void moe_route_kernel(const float* __restrict__ logits, int splits,
+                                                        int64_t split_stride, float* __restrict__ sum_out,
+                                                        int64_t n, int E, int K,
                                                         int32_t* __restrict__ idx, float* __restrict__ wts,
                                                         int32_t* __restrict__ rank, int32_t* __restrict__ count) {
   const int lane = threadIdx.x & 63;
@@ -47,7 +52,12 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const float* __restrict_
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int e = lane + 64 * j;
-    float z = e < E ? logits[row * E + e] : -INFINITY;
+    float z = -INFINITY;
+    if (e < E) {
+      z = logits[row * E + e];
+      for (int s = 1; s < splits; ++s) z += logits[s * split_stride + row * E + e];   // in split order
+      if (sum_out) sum_out[row * E + e] = z;             // the scores the choice is taken from, for inspection
+    }
     if (e < E && !(z >= -FLT_MAX)) z = -FLT_MAX;        // NaN or -inf scores rank last but stay selectable
     v[j] = z;
   }
@@ -77,7 +87,68 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const float* __restrict_
     const int e = my_e < E ? my_e : E - 1;
     idx[row * K + lane] = e;
     wts[row * K + lane] = ex / sum;
-    rank[row * K + lane] = atomicAdd(&count[e], 1);
+    if (count) rank[row * K + lane] = atomicAdd(&count[e], 1);
+  }
+}
+
+// Few pairs: counting, scan, tile table, positions and the inverse list in ONE workgroup (LDS atomics),
+// instead of the zero / plan / fill kernels around the counting in moe_route_kernel.
+__global__ __launch_bounds__(1024) void moe_plan_small_kernel(const int32_t* __restrict__ idx, int64_t pairs, int K,
+                                                              int E, int tile_rows, int32_t* __restrict__ offset,
+                                                              GroupTile* __restrict__ tiles,
+                                                              int32_t* __restrict__ n_tiles,
+                                                              int32_t* __restrict__ pair_row,
+                                                              int32_t* __restrict__ pair_pos) {
+  __shared__ int cnt[256], sc[256], stl[256], cur[256];
+  const int t = threadIdx.x;
+  if (t < 256) cnt[t] = 0;
+  __syncthreads();
+  for (int64_t i = t; i < pairs; i += 1024) atomicAdd(&cnt[idx[i]], 1);
+  __syncthreads();
+  const int c = t < 256 ? cnt[t] : 0;
+  const int nt = (c + tile_rows - 1) / tile_rows;
+  if (t < 256) {
+    sc[t] = c;
+    stl[t] = nt;
+  }
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {      // inclusive scans over the 256 expert slots
+    int a = 0, b = 0;
+    if (t < 256 && t >= o) {
+      a = sc[t - o];
+      b = stl[t - o];
+    }
+    __syncthreads();
+    if (t < 256) {
+      sc[t] += a;
+      stl[t] += b;
+    }
+    __syncthreads();
+  }
+  if (t < 256) {
+    const int off = sc[t] - c, toff = stl[t] - nt;
+    cur[t] = off;
+    if (t < E) {
+      offset[t] = off;
+      for (int k = 0; k < nt; ++k) {
+        GroupTile g;
+        g.expert = t;
+        g.m0 = off + k * tile_rows;
+        g.m_end = off + c;
+        g.pad = 0;
+        tiles[toff + k] = g;
+      }
+    }
+    if (t == 255) {
+      offset[E] = sc[255];
+      *n_tiles = stl[255];
+    }
+  }
+  __syncthreads();
+  for (int64_t i = t; i < pairs; i += 1024) {
+    const int pos = atomicAdd(&cur[idx[i]], 1);
+    pair_pos[i] = pos;
+    pair_row[pos] = (int32_t)(i / K);
   }
 }
 
@@ -173,18 +244,29 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const T* __restrict__ 
 
 }  // namespace
 
-int launch_moe_route(const float* logits, int64_t n, int n_experts, int top_k, int tile_rows, const MoeScratch& s,
-                     hipStream_t st) {
+int launch_moe_route(const float* logits, int splits, int64_t split_stride, float* sum_out, int64_t n,
+                     int n_experts, int top_k, int tile_rows, const MoeScratch& s, hipStream_t st) {
   if (n <= 0) return VLC_OK;
+  if (splits < 1) return fail(VLC_ERR_SHAPE, "moe: splits=%d", splits);
   if (n_experts < 1 || n_experts > kMaxExperts || top_k < 1 || top_k > kMaxTopK || top_k > n_experts)
     return fail(VLC_ERR_SHAPE, "moe: n_experts=%d (<= %d), top_k=%d (<= %d, <= n_experts)", n_experts, kMaxExperts,
                 top_k, kMaxTopK);
   if (n * top_k > INT32_MAX) return fail(VLC_ERR_SHAPE, "moe: too many (row, expert) pairs");
   const int64_t pairs = n * top_k;
+  if (pairs <= kSmallPlanPairs) {
+    hipLaunchKernelGGL(moe_route_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, logits, splits,
+                       split_stride, sum_out, n, n_experts, top_k, s.idx, s.wts, (int32_t*)nullptr,
+                       (int32_t*)nullptr);
+    VLC_CHECK_LAUNCH("moe_route");
+    hipLaunchKernelGGL(moe_plan_small_kernel, dim3(1), dim3(1024), 0, st, (const int32_t*)s.idx, pairs, top_k,
+                       n_experts, tile_rows, s.offset, s.tiles, s.n_tiles, s.pair_row, s.pair_pos);
+    VLC_CHECK_LAUNCH("moe_plan_small");
+    return VLC_OK;
+  }
   hipLaunchKernelGGL(zero_i32_kernel, dim3(1), dim3(256), 0, st, s.count, n_experts);
   VLC_CHECK_LAUNCH("moe_zero");
-  hipLaunchKernelGGL(moe_route_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, logits, n, n_experts, top_k,
-                     s.idx, s.wts, s.rank, s.count);
+  hipLaunchKernelGGL(moe_route_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, logits, splits, split_stride,
+                     sum_out, n, n_experts, top_k, s.idx, s.wts, s.rank, s.count);
   VLC_CHECK_LAUNCH("moe_route");
   hipLaunchKernelGGL(moe_plan_kernel, dim3(1), dim3(256), 0, st, (const int32_t*)s.count, n_experts, tile_rows,
                      s.offset, s.tiles, s.n_tiles);

@@ -139,8 +139,10 @@ struct MoeScratch {
   int32_t* pair_row;
   int32_t* pair_pos;
 };
-int launch_moe_route(const float* logits, int64_t n, int n_experts, int top_k, int tile_rows, const MoeScratch& s,
-                     hipStream_t st);
+// logits: `splits` partial matrices [n, E] to sum, split_stride floats apart; sum_out (optional): where the summed
+// scores are left
+int launch_moe_route(const float* logits, int splits, int64_t split_stride, float* sum_out, int64_t n,
+                     int n_experts, int top_k, int tile_rows, const MoeScratch& s, hipStream_t st);
 int launch_moe_combine(const void* h1, const void* y, const float* wts, const int32_t* pair_pos, int64_t n,
                        int top_k, int H, void* out, int dtype, hipStream_t st);
 
