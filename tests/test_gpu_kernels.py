@@ -185,6 +185,18 @@ def test_attention_long_context_bf16():
     attention_case("bf16", 28, 4, 128, [(S, slots)], seed=21)
 
 
+@pytest.mark.parametrize("Hq,Hkv,reqs", [
+    # one query head per kv head, 256 rows per tile: runs of three requests share tiles, a zero-length row,
+    # single-key rows, rows out of order
+    (64, 64, [(700, [-1, 0, 0] + list(range(0, 700, 1)) + [5, 699, 3]), (300, list(range(300))), (1000, list(range(1000)))]),
+    # two query heads per kv head, 128 rows per tile, ragged tail
+    (32, 16, [(2500, list(range(2500))), (1723, list(range(0, 1723)))]),
+])
+def test_attention_many_rows(Hq, Hkv, reqs):
+    """Thousands of rows, several requests, more than 512 workgroups."""
+    attention_case("bf16", Hq, Hkv, 128, reqs, seed=31)
+
+
 def test_attention_errors():
     q = torch.zeros((2, 4, 128), device=DEV, dtype=torch.bfloat16)
     kv = torch.zeros((8, 3, 128), device=DEV, dtype=torch.bfloat16)
