@@ -201,10 +201,35 @@ def test_workspace_size_is_monotone_in_rows():
     """A workspace sized for n_max rows must serve every call with fewer rows (the scratch areas for
     split-K GEMMs and key-split attention only exist for small row counts)."""
     from paper_2512_12977_amd.runner import make_shape
-    for name in ("7b", "72b", "tiny_bf16", "tiny", "q3vl_8b", "tiny_q3"):
+    for name in ("7b", "72b", "tiny_bf16", "tiny", "q3vl_8b", "tiny_q3", "q3vl_30b_a3b", "tiny_moe"):
         rec = make_shape(syn.SHAPES[name])
         prev = 0
         for n in list(range(0, 3000, 13)) + [5000, 18944, 147456]:
             b = vlc.vlc_layer_workspace_bytes(rec, n)
             assert b >= prev, (name, n, b, prev)
             prev = b
+
+
+def test_expert_fields_of_the_shape_and_layout():
+    from paper_2512_12977_amd.runner import make_shape
+    dense = make_shape(syn.SHAPES["7b"])
+    off = vlc.vlc_layer_workspace_layout(dense, 100)
+    assert all(off[name] == -1 for name in ("moe_idx", "moe_w", "moe_pos", "moe_y", "moe_logits", "moe_offset"))
+    moe = make_shape(syn.SHAPES["q3vl_30b_a3b"])
+    off = vlc.vlc_layer_workspace_layout(moe, 100)
+    vals = [off[name] for name in ("act", "moe_idx", "moe_w", "moe_pos", "moe_y", "moe_logits", "moe_offset")]
+    assert all(v >= 0 and v % 256 == 0 for v in vals) and vals == sorted(vals) and len(set(vals)) == len(vals)
+    assert off["moe_idx"] - off["act"] >= 100 * 8 * 768 * 2          # the SwiGLU product holds one row per (row, expert) pair
+    assert vlc.vlc_layer_workspace_bytes(moe, 100) > vlc.vlc_layer_workspace_bytes(make_shape(syn.SHAPES["q3vl_8b"]), 100) - (1 << 26)
+    for n_experts, top_k in ((257, 8), (8, 9), (8, 0), (8, 17), (-1, 0)):
+        bad = vlc.LayerShape(2048, 32, 4, 128, 768, vlc.VLC_BF16, 1e-6, 5e6, 24, 20, 20, n_experts, top_k)
+        with pytest.raises(vlc.VlcError):
+            vlc.vlc_layer_workspace_bytes(bad, 10)
+        assert "n_experts" in vlc.last_error()
+
+
+def test_mean_squared_error_argument_checks():
+    L = vlc.lib()
+    assert L.vlc_mean_squared_error_workspace_bytes() >= 8
+    assert L.vlc_mean_squared_error(None, None, 0, None, None, 0, None) == 2      # n <= 0
+    assert L.vlc_mean_squared_error(None, None, 5, None, None, 0, None) == 1      # NULL pointers
