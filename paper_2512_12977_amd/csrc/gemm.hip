@@ -193,14 +193,8 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   (lds_base + (uint32_t)(((stage_) * STAGE_CHUNKS +                                                           \
                           ((i_) < A_INSTR ? wave * A_INSTR * 64 + (i_) * 64                                  \
                                           : BM * 8 + wave * W_INSTR * 64 + ((i_) - A_INSTR) * 64)) * 16))
-  // GROUPED: the k-tiles are walked from a tile-dependent start, wrapping round.  Every matrix of a group is
-  // read once, cold, by workgroups that start together; with a row pitch that is a power of two they would
-  // all ask the same memory channels for the same k at the same time.
-  int k_rot = 0;
-  if constexpr (GROUPED) k_rot = (tn * 5 + tm * 3) % KT;
-#define VLC_KT(kt_) (GROUPED ? ((kt_) + k_rot < KT ? (kt_) + k_rot : (kt_) + k_rot - KT) : (kt_))
 #define VLC_DMA(kt_, i_, stage_)                                                                              \
-  dma16(((i_) < A_INSTR ? a_base : w_base) + VLC_KT(kt_) * BK,                                                \
+  dma16(((i_) < A_INSTR ? a_base : w_base) + (kt_) * BK,                                                \
         (i_) < A_INSTR ? a_lane[(i_) < A_INSTR ? (i_) : 0] : w_lane[(i_) >= A_INSTR ? (i_) - A_INSTR : 0],     \
         VLC_LDS_DST(stage_, i_))
 #define VLC_ISSUE(kt_, stage_) _Pragma("unroll") for (int i = 0; i < LOADS; ++i) VLC_DMA(kt_, i, stage_);
@@ -300,7 +294,6 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   }
 #undef VLC_ISSUE
 #undef VLC_DMA
-#undef VLC_KT
 #undef VLC_LDS_DST
 #undef VLC_COMPUTE_TILE
 

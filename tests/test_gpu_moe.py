@@ -109,3 +109,13 @@ def test_moe_30b_a3b_shape_layer_stage_by_stage():
     g = check_moe_layer(syn.make_workload("c2_moe"), 0)
     counts = np.bincount(g["moe_idx"].ravel(), minlength=128)
     print("pairs per expert: min %d median %d max %d" % (counts.min(), np.median(counts), counts.max()))
+
+
+def test_moe_many_pairs_grouped_with_atomic_ranks():
+    """More than 65536 (row, expert) pairs: ranks come from atomic counters in the choice kernel and the plan / fill
+    kernels, and with 10000 rows per expert the grouped GEMMs run on 256-row tiles.  330 short text-only requests."""
+    sh = syn.SHAPES["tiny_moe_bf16"]
+    reqs = [syn.Request([syn.Segment(0, 124, False)], 124 * i, 0, syn.grid_positions([("text", 124)])) for i in range(330)]
+    wl = syn.Workload("moe_many", sh, reqs, 1, "static", static_k=0, seed=14)
+    g = check_moe_layer(wl, 0)
+    assert g["moe_idx"].shape == (330 * 124, 2)
