@@ -219,7 +219,9 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
       const bool in_seg = vr_ok[rt] && r_local[rt] >= seg_begin && r_local[rt] < seg_end;
       len[rt] = in_seg ? my_len[rt] : 0;
       w_max = max(w_max, len[rt]);
-      w_min = min(w_min, len[rt]);
+      // padding lanes (no row behind them) are left out: nothing of theirs is stored, so they need no
+      // masking - otherwise the wavefront that holds the tile's padding would mask every block
+      w_min = min(w_min, vr_ok[rt] ? len[rt] : 0x7fffffff);
     }
     // longest / shortest visible range among this wavefront's rows (uniform per wavefront)
 #pragma unroll
