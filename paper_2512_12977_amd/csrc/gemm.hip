@@ -605,20 +605,44 @@ int launch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
   return VLC_OK;
 }
 
-// Tile choice.  Many rows: 256 x 256 tiles, 4 wavefronts of 128 x 128.  Few rows: 128 x 128 tiles, 4 wavefronts, two
-// workgroups per CU; if that still leaves most of the 256 CUs idle, the k range is split as well.
+// Tile choice.  Many rows: 256 x 256 tiles, 4 wavefronts of 128 x 128.  Few rows: two workgroups per CU, on
+// 128 x 192 tiles (4 wavefronts of 32 x 192: 96 output columns) for gate|up, and on 128 x 128 tiles (4 wavefronts of
+// 64 x 64) for the others, whose k range is split as well if the tiles still leave most of the 256 CUs idle.
 template <int EPI>
 int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
                   int64_t K, const void* bias, const void* resid, int64_t ldr, const int32_t* rmap,
                   void* splitk_ws, int64_t splitk_ws_bytes, int* deferred, hipStream_t st) {
   const int KT = (int)(K / BK);
-  if (M >= 1536)
+  // 256 x 256 tiles (one workgroup per CU) against the small tiles (two per CU).
+  bool big;
+  if constexpr (EPI == EPI_SWIGLU) {
+    // Both in rounds of resident workgroups, the last round shortened by the tail split as launch_bf16 does it;
+    // a round of 256 x 256 tiles takes 1.09 rounds of 128 x 192 tiles (measured rates 1.26 and 1.03 PFLOP/s).
+    auto rounds = [KT](int64_t tiles, int slots) {
+      const int64_t full = tiles / slots, tail = tiles % slots;
+      float r = (float)full;
+      if (tail > 0) {
+        const int64_t tsp = full > 0 ? (slots / tail < KT / 8 ? slots / tail : KT / 8) : 1;
+        r += tsp >= 2 ? 1.0f / (float)tsp + 0.1f : 1.0f;
+      }
+      return r;
+    };
+    const int64_t tiles_big = ((M + 255) / 256) * ((N + 127) / 128), tiles_small = ((M + 127) / 128) * ((N + 95) / 96);
+    big = 1.09f * rounds(tiles_big, 256) < rounds(tiles_small, 512);
+  } else {
+    // with few output columns (the o, down and qkv products) there are not enough 256 x 256 tiles for the 256 CUs
+    // until several thousand rows: the small tiles with a split k range stay ahead
+    big = M >= 1536 && ((M + 255) / 256) * ((N + 255) / 256) >= 200;
+  }
+  if (big)
     return launch_bf16<256, 256, 2, 2, 2, 1, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT,
                                                   splitk_ws, splitk_ws_bytes, st);
-  constexpr int CN = (EPI == EPI_SWIGLU) ? 64 : 128;
-  const int64_t tiles = ((M + 127) / 128) * ((N + CN - 1) / CN);
-  int splits = 1;
-  if constexpr (EPI != EPI_SWIGLU) {
+  if constexpr (EPI == EPI_SWIGLU) {
+    return launch_bf16<128, 192, 4, 1, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, splitk_ws,
+                                                  splitk_ws_bytes, st);
+  } else {
+    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    int splits = 1;
     if (splitk_ws && tiles < 384) {
       // 512 workgroups are resident at once (two per CU).  Cost of a split count, in units of one
       // workgroup's k-tile (~1.2 us): (rounds of resident workgroups) x (k-tiles per workgroup), plus
@@ -635,15 +659,13 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
         }
       }
     }
-  }
-  if (splits <= 1)
-    return launch_bf16<128, 128, 2, 2, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT,
-                                                  splitk_ws, splitk_ws_bytes, st);
-  if constexpr (EPI != EPI_SWIGLU) {
+    if (splits <= 1)
+      return launch_bf16<128, 128, 2, 2, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT,
+                                                   splitk_ws, splitk_ws_bytes, st);
     const int per = (KT + splits - 1) / splits;
     splits = (KT + per - 1) / per;
     int rc = launch_bf16<128, 128, 2, 2, 2, 2, EPI_PARTIAL>(A, lda, W, splitk_ws, N, M, N, K, nullptr, nullptr, 0,
-                                                            nullptr, splits, per, nullptr, 0, st);
+                                                           nullptr, splits, per, nullptr, 0, st);
     if (rc) return rc;
     if (deferred) {   // the caller's next kernel sums the partials and applies the epilogue
       *deferred = splits;
@@ -654,8 +676,8 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
                        (const float*)splitk_ws, splits, (uint16_t*)C, ldc, (int)M, (int)N, (const uint16_t*)bias,
                        (const uint16_t*)resid, ldr, rmap);
     VLC_CHECK_LAUNCH("splitk_epilogue");
+    return VLC_OK;
   }
-  return VLC_OK;
 }
 
 template <int EPI>

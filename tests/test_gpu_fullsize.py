@@ -99,11 +99,12 @@ def test_c4_layer_sampled_rows():
         assert_close(back(h_out[torch.from_numpy(rows).to(DEV)]), r["h2"], sh.dtype, "h_out")
 
 
-@pytest.mark.parametrize("n_text,n_image,all_rows", [(200, 5000, True), (720, 2000, False), (1600, 0, True)])
+@pytest.mark.parametrize("n_text,n_image,all_rows", [(200, 5000, True), (720, 2000, False), (1184, 0, True), (1600, 0, True)])
 def test_7b_layer_rows_that_leave_a_partial_round_of_gemm_tiles(n_text, n_image, all_rows):
     """Row counts at which the output tiles of the GEMMs do not fill the chip a whole number of times
-    (5200 rows: all four GEMMs; 720 and 1600 rows: the gate|up GEMM with the 128- and the 256-row tile):
-    the tiles of the last round are then split along k and summed by a second kernel.  Every 13th row
+    (5200 rows: all four GEMMs on 256-row tiles; 720 rows: the gate|up GEMM on 128 x 192 tiles, whose last column
+    tile is ragged; 1184 and 1600 rows: gate|up on 256-row tiles next to o, down and qkv on 128-row tiles with a
+    split k range): the tiles of the last round are then split along k and summed by a second kernel.  Every 13th row
     (so every tile of every GEMM is sampled) is compared stage by stage with the oracle."""
     sh = syn.SHAPES["7b"]
     st = orc.STORE[sh.dtype]
