@@ -641,31 +641,50 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
     return launch_bf16<128, 192, 4, 1, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, splitk_ws,
                                                   splitk_ws_bytes, st);
   } else {
-    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
-    int splits = 1;
-    if (splitk_ws && tiles < 384) {
-      // 512 workgroups are resident at once (two per CU).  Cost of a split count, in units of one
-      // workgroup's k-tile (~1.2 us): (rounds of resident workgroups) x (k-tiles per workgroup), plus
-      // a second kernel and, per split, one float matrix written and read back (8 bytes per element
-      // at ~4 TB/s = 1.7e-6 units per element).  At least 8 k-tiles per split.
-      float best = (float)((tiles + 511) / 512) * (float)KT;
+    // Tile width (128 or 192 columns) and number of k ranges, by cost in units of one 128 x 128 workgroup's
+    // k-tile (~1.2 us; 1.35 of them for a 128 x 192 k-tile): (rounds of the 512 resident workgroups) x (k-tiles
+    // per workgroup), plus, when the k range is split, a second kernel (2 units) and per split one float
+    // matrix written and read back (8 bytes per element at ~4 TB/s = 1.7e-6 units per element).  At least
+    // 8 k-tiles per split; no split from 384 tiles on.
+    int splits = 1, width = 128;
+    float best = 0.f;
+    for (int tn = 128; tn <= 192; tn += 64) {
+      const int64_t tiles = ((M + 127) / 128) * ((N + tn - 1) / tn);
+      const float unit = tn == 128 ? 1.0f : 1.35f;
+      const float whole = (float)((tiles + 511) / 512) * (float)KT * unit;
+      if (tn == 128 || whole < best) {
+        best = whole;
+        splits = 1;
+        width = tn;
+      }
+      if (!splitk_ws || tiles >= 384) continue;
       for (int sp = 2; sp <= 8; ++sp) {
         if (KT / sp < 8 || (int64_t)sp * M * N * 4 > splitk_ws_bytes) break;
-        const float cost = (float)(((tiles * sp + 511) / 512) * ((KT + sp - 1) / sp)) + 2.0f +
+        const float cost = (float)(((tiles * sp + 511) / 512) * ((KT + sp - 1) / sp)) * unit + 2.0f +
                            (float)sp * (float)(M * N) * 1.7e-6f;
         if (cost < best) {
           best = cost;
           splits = sp;
+          width = tn;
         }
       }
     }
-    if (splits <= 1)
+    if (splits <= 1) {
+      if (width == 192)
+        return launch_bf16<128, 192, 4, 1, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT,
+                                                      splitk_ws, splitk_ws_bytes, st);
       return launch_bf16<128, 128, 2, 2, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT,
-                                                   splitk_ws, splitk_ws_bytes, st);
+                                                    splitk_ws, splitk_ws_bytes, st);
+    }
     const int per = (KT + splits - 1) / splits;
     splits = (KT + per - 1) / per;
-    int rc = launch_bf16<128, 128, 2, 2, 2, 2, EPI_PARTIAL>(A, lda, W, splitk_ws, N, M, N, K, nullptr, nullptr, 0,
-                                                           nullptr, splits, per, nullptr, 0, st);
+    int rc;
+    if (width == 192)
+      rc = launch_bf16<128, 192, 4, 1, 2, 2, EPI_PARTIAL>(A, lda, W, splitk_ws, N, M, N, K, nullptr, nullptr, 0,
+                                                          nullptr, splits, per, nullptr, 0, st);
+    else
+      rc = launch_bf16<128, 128, 2, 2, 2, 2, EPI_PARTIAL>(A, lda, W, splitk_ws, N, M, N, K, nullptr, nullptr, 0,
+                                                          nullptr, splits, per, nullptr, 0, st);
     if (rc) return rc;
     if (deferred) {   // the caller's next kernel sums the partials and applies the epilogue
       *deferred = splits;
