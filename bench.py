@@ -144,6 +144,9 @@ def main() -> int:
     ap.add_argument("--no-full", action="store_true", help="skip the full-recompute comparison")
     ap.add_argument("--no-first-token", action="store_true", help="skip the first-token head timing")
     ap.add_argument("--cpu-layers", type=int, default=None, help="layers of the oracle sample")
+    ap.add_argument("--per-layer-shift", action="store_true",
+                    help="re-rotate the reused keys inside every layer call instead of in one launch for all "
+                         "layers ahead of the layer loop")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain row copy of 1 GiB through vlc_gather_rows "
                          "(identity index) so a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -211,10 +214,20 @@ def main() -> int:
             n_prev = p.n_rows[l]
         return out
 
-    sel_recs = recs(plans)
+    # Reused keys/values: by default one launch moves those of all layers before the layer loop (they depend
+    # on nothing the layers compute) and the layers run with n_reuse = 0; --per-layer-shift leaves them to
+    # the layer calls.  Either way the work is inside every timed step.
+    shift_all = None if args.per_layer_shift else R.ShiftJobs(plans, kpool, vpool, kcache, vcache)
+    sel_recs = recs(plans, reuse=shift_all is None)
     full_recs = recs(full, reuse=False) if full else None
 
-    def run_step(records, events=None):
+    def run_step(records, events=None, shift_events=None):
+        if records is sel_recs and shift_all is not None:
+            if shift_events is not None:
+                hev.record(shift_events[0], stream)
+            shift_all.run(sh.rope_base)
+            if shift_events is not None:
+                hev.record(shift_events[1], stream)
         h_in = emb
         for l in range(L):
             h_out = hbuf[l & 1]
@@ -252,9 +265,15 @@ def main() -> int:
                                                   "max": round(max(peak), 2)}, "experts": sh.n_experts}
     psteps = 3
     pev = [[hev.create(NS + 1) for _ in range(L)] for _ in range(psteps)]
+    sev = [hev.create(2) for _ in range(psteps)]
     for s in range(psteps):
-        run_step(sel_recs, pev[s])
+        run_step(sel_recs, pev[s], sev[s])
     torch.cuda.synchronize()
+    shift_all_us = None
+    if shift_all is not None and shift_all.n_jobs:
+        shift_all_us = float(np.mean([hev.elapsed_ms(e[0], e[1]) for e in sev])) * 1e3
+    for e in sev:
+        hev.destroy(e)
     stage_ms = np.zeros((psteps, L, NS))
     layer_ms = np.zeros((psteps, L))
     for s in range(psteps):
@@ -306,10 +325,17 @@ def main() -> int:
         by = np.mean([stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])[name][1] for l in range(L)])
         us = float(stage_avg_us[i])
         stages[name] = {"avg_us": round(us, 2), "share": round(float(stage_avg_us[i] / stage_avg_us.sum()), 4)}
-        if fl > 0:
+        if name == "rope_shift" and shift_all_us is not None:
+            stages[name]["note"] = "empty: the reused keys of all layers are moved by one launch per step"
+        elif fl > 0:
             stages[name]["tflops"] = round(fl / (us * 1e-6) / 1e12, 2)
         elif by > 0:
             stages[name]["gbs"] = round(by / (us * 1e-6) / 1e9, 1)
+    if shift_all_us is not None:
+        # one launch per step for all layers (the per-layer rope_shift stage above is then empty)
+        by = float(sum(stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])["rope_shift"][1] for l in range(L)))
+        stages["rope_shift_all_layers"] = {"avg_us": round(shift_all_us, 2), "per_step": True,
+                                           "gbs": round(by / (shift_all_us * 1e-6) / 1e9, 1)}
     dom_name = vlc.LAYER_STAGES[dom]
     fl = np.mean([stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])[dom_name][0] for l in range(L)])
     by = np.mean([stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])[dom_name][1] for l in range(L)])

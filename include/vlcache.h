@@ -165,6 +165,32 @@ int vlc_rope_shift_kv(const void* k_src, const void* v_src, void* k_dst, void* v
                       int64_t n_tok, int Hkv, int D, double rope_base, int dtype, void* stream);
 
 /*
+ * The same for several independent jobs in one launch - the reused keys of all layers of a prompt (Sec. 4.2):
+ * the cached K/V of every layer and the position shifts are known before the first layer runs and depend
+ * on nothing the layers compute, so the per-layer calls can be replaced by one call ahead of the layer
+ * loop; the layers are then run with n_reuse = 0.
+ *   jobs: DEVICE array [n_jobs] of vlc_shift_job records, 8-byte aligned (all its pointers device, same meaning,
+ *         layouts and aliasing rules as the arguments of vlc_rope_shift_kv; v_src/v_dst NULL: keys only).
+ *         Jobs must not write rows another job reads or writes.  The table must stay valid until the
+ *         kernel has run.
+ *   max_n_tok: host-side upper bound of every job's n_tok (sizes the grid; a job with a larger n_tok
+ *         is processed only up to max_n_tok tokens).  Jobs with n_tok = 0 are skipped.
+ * The library cannot check a device table: row indices and pointers in it are the caller's responsibility.
+ */
+typedef struct {
+  const void* k_src;
+  const void* v_src;
+  void* k_dst;
+  void* v_dst;
+  const int32_t* src_row;
+  const int32_t* dst_row;
+  const int32_t* delta;
+  int64_t n_tok;
+} vlc_shift_job;
+int vlc_rope_shift_kv_layers(const vlc_shift_job* jobs, int n_jobs, int64_t max_n_tok, int Hkv, int D,
+                             double rope_base, int dtype, void* stream);
+
+/*
  * KV blend (Sec. 4.2 "fine-grained KV cache reuse"): fresh K/V rows of the recomputed tokens
  * overwrite their slots.  k_cache[dst_row[i]] = k_new[i], v_cache[dst_row[i]] = v_new[i].
  *   k_new, v_new [n, Hkv, D]; k_cache, v_cache [cache_rows, Hkv, D]; dst_row entries unique.

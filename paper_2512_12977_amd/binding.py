@@ -35,6 +35,11 @@ class LayerWeights(C.Structure):
                                           "w_qnorm", "w_knorm", "w_router")]
 
 
+class ShiftJob(C.Structure):
+    _fields_ = [("k_src", C.c_void_p), ("v_src", C.c_void_p), ("k_dst", C.c_void_p), ("v_dst", C.c_void_p),
+                ("src_row", C.c_void_p), ("dst_row", C.c_void_p), ("delta", C.c_void_p), ("n_tok", C.c_int64)]
+
+
 class LayerPlan(C.Structure):
     _fields_ = [("n_in", C.c_int64), ("n", C.c_int64), ("map", C.c_void_p), ("slot", C.c_void_p),
                 ("pos", C.c_void_p), ("row_kv_start", C.c_void_p), ("row_kv_len", C.c_void_p),
@@ -65,6 +70,8 @@ def lib():
         L.vlc_plan_reuse_rows.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int64] + [C.c_void_p] * 4
         L.vlc_gather_rows.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_void_p]
         L.vlc_rope_shift_kv.argtypes = [C.c_void_p] * 7 + [C.c_int64, C.c_int, C.c_int, C.c_double, C.c_int, C.c_void_p]
+        L.vlc_rope_shift_kv_layers.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_double, C.c_int,
+                                               C.c_void_p]
         L.vlc_scatter_kv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.vlc_sparse_q_attention.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_float,
@@ -198,6 +205,28 @@ def vlc_rope_shift_kv(k_src, v_src, k_dst, v_dst, src_row, dst_row, delta, rope_
     _check(lib().vlc_rope_shift_kv(_dev(k_src), _dev(v_src), _dev(k_dst), _dev(v_dst), _dev(src_row),
                                    _dev(dst_row), _dev(delta), src_row.numel(), Hkv, D, float(rope_base),
                                    _dtype_code(k_src), _stream(stream)))
+
+
+def shift_job_table(jobs) -> np.ndarray:
+    """Host bytes of a vlc_shift_job table.  jobs: sequences (k_src, v_src, k_dst, v_dst, src_row, dst_row, delta)
+    of GPU tensors (v_src, v_dst may be None); n_tok = src_row.numel().  Copy the result to the GPU
+    (torch.from_numpy(table).cuda()) and pass that tensor to vlc_rope_shift_kv_layers; the tensors named here
+    must outlive its use."""
+    arr = (ShiftJob * max(len(jobs), 1))()
+    for i, (ks, vs, kd, vd, src, dst, dl) in enumerate(jobs):
+        if not (src.numel() == dst.numel() == dl.numel()):
+            raise ValueError("job %d: index arrays differ in length" % i)
+        arr[i] = ShiftJob(_dev(ks), _dev(vs), _dev(kd), _dev(vd), _dev(src), _dev(dst), _dev(dl), src.numel())
+    return np.frombuffer(bytes(arr), dtype=np.uint8)[:len(jobs) * C.sizeof(ShiftJob)].copy()
+
+
+def vlc_rope_shift_kv_layers(job_table, n_jobs: int, max_n_tok: int, Hkv: int, D: int, rope_base: float, dtype: int,
+                             stream=None) -> None:
+    """job_table: GPU uint8 tensor holding n_jobs vlc_shift_job records (see shift_job_table)."""
+    if n_jobs and job_table.numel() < n_jobs * C.sizeof(ShiftJob):
+        raise ValueError("job table holds fewer than %d jobs" % n_jobs)
+    _check(lib().vlc_rope_shift_kv_layers(_dev(job_table), int(n_jobs), int(max_n_tok), int(Hkv), int(D),
+                                          float(rope_base), int(dtype), _stream(stream)))
 
 
 def vlc_scatter_kv(k_new, v_new, dst_row, k_cache, v_cache, stream=None) -> None:

@@ -144,14 +144,13 @@ int copy_rows(const void* src0, const void* src1, int64_t src_stride_bytes, cons
 // matching chunk of the high half) and walks over the Hkv heads, so each sine/cosine is computed
 // once per token and reused for every head.  Consecutive lanes cover consecutive chunks of a row.
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void rope_shift_kernel(
-    const uint4* k_src, const uint4* v_src, uint4* k_dst, uint4* v_dst,   // may alias (in-place use)
+__device__ __forceinline__ void rope_shift_thread(
+    int64_t gid, const uint4* k_src, const uint4* v_src, uint4* k_dst, uint4* v_dst,   // may alias (in-place use)
     const int32_t* __restrict__ src_row, const int32_t* __restrict__ dst_row,
-    const int32_t* __restrict__ delta, int64_t n_tok, int Hkv, int head_parts, RopeFreq freq) {
+    const int32_t* __restrict__ delta, int64_t n_tok, int Hkv, int head_parts, const RopeFreq& freq) {
   constexpr int VEC = Chunk<T>::VEC;
   constexpr int CH = (D / 2) / VEC;                  // chunks per half head
   constexpr int HEAD_CHUNKS = 2 * CH;                // chunks per head
-  const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const int64_t t = gid / CH;
   const int c = (int)(gid - t * CH);
   const int64_t tok = t / head_parts;                // head_parts > 1: the heads of a token are shared out
@@ -193,6 +192,25 @@ __global__ __launch_bounds__(kThreads) void rope_shift_kernel(
       vd[h * HEAD_CHUNKS + CH] = v_hi;
     }
   }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void rope_shift_kernel(
+    const uint4* k_src, const uint4* v_src, uint4* k_dst, uint4* v_dst,
+    const int32_t* __restrict__ src_row, const int32_t* __restrict__ dst_row,
+    const int32_t* __restrict__ delta, int64_t n_tok, int Hkv, int head_parts, RopeFreq freq) {
+  rope_shift_thread<T, D>((int64_t)blockIdx.x * kThreads + threadIdx.x, k_src, v_src, k_dst, v_dst, src_row, dst_row,
+                          delta, n_tok, Hkv, head_parts, freq);
+}
+
+// The same for a table of jobs (one per layer): blockIdx.y picks the job, blocks beyond its token count leave.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void rope_shift_jobs_kernel(const vlc_shift_job* __restrict__ jobs, int Hkv,
+                                                                   int head_parts, RopeFreq freq) {
+  const vlc_shift_job j = jobs[blockIdx.y];
+  rope_shift_thread<T, D>((int64_t)blockIdx.x * kThreads + threadIdx.x, (const uint4*)j.k_src, (const uint4*)j.v_src,
+                          (uint4*)j.k_dst, (uint4*)j.v_dst, j.src_row, j.dst_row, j.delta, j.n_tok, Hkv, head_parts,
+                          freq);
 }
 
 constexpr int kMaxSplits = 8;   // the GEMM never splits the k range into more parts
@@ -586,6 +604,25 @@ int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v
   return VLC_OK;
 }
 
+int launch_rope_shift_jobs(const vlc_shift_job* jobs, int n_jobs, int64_t max_n_tok, int Hkv, int D,
+                           const RopeFreq& f, int dtype, hipStream_t st) {
+  if (n_jobs <= 0 || max_n_tok <= 0) return VLC_OK;
+  const int vec = dtype == VLC_BF16 ? 8 : 4;
+  const int head_parts = max_n_tok * n_jobs * ((D / 2) / vec) < (int64_t)kThreads * 1024 ? Hkv : 1;
+  const int64_t threads = max_n_tok * head_parts * ((D / 2) / vec);
+  const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads), (unsigned)n_jobs);
+#define VLC_LAUNCH_SHIFT(T, DD) \
+  hipLaunchKernelGGL((rope_shift_jobs_kernel<T, DD>), grid, dim3(kThreads), 0, st, jobs, Hkv, head_parts, f)
+  if (dtype == VLC_BF16 && D == 128) VLC_LAUNCH_SHIFT(uint16_t, 128);
+  else if (dtype == VLC_BF16 && D == 64) VLC_LAUNCH_SHIFT(uint16_t, 64);
+  else if (dtype == VLC_F32 && D == 128) VLC_LAUNCH_SHIFT(float, 128);
+  else if (dtype == VLC_F32 && D == 64) VLC_LAUNCH_SHIFT(float, 64);
+  else return fail(VLC_ERR_SHAPE, "rope shift: unsupported D=%d", D);
+#undef VLC_LAUNCH_SHIFT
+  VLC_CHECK_LAUNCH("rope_shift_kv_layers");
+  return VLC_OK;
+}
+
 int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t* slot, int64_t n, int Hq,
                            int Hkv, int D, const RopeFreq& f, void* q_out, void* k_cache, void* v_cache,
                            int dtype, hipStream_t st, const float* partials, int splits, const void* bias,
@@ -810,6 +847,22 @@ extern "C" int vlc_rope_shift_kv(const void* k_src, const void* v_src, void* k_d
     return fail(VLC_ERR_SHAPE, "vlc_rope_shift_kv: pointers must be 16-byte aligned");
   return vlc::launch_rope_shift(k_src, v_src, k_dst, v_dst, src_row, dst_row, delta, n_tok, Hkv, D,
                                 vlc::make_rope_freq(rope_base, D), dtype, (hipStream_t)stream);
+}
+
+extern "C" int vlc_rope_shift_kv_layers(const vlc_shift_job* jobs, int n_jobs, int64_t max_n_tok, int Hkv, int D,
+                                       double rope_base, int dtype, void* stream) {
+  int rc = check_kv("vlc_rope_shift_kv_layers", Hkv, D, dtype);
+  if (rc) return rc;
+  if (n_jobs < 0 || n_jobs > 65535)
+    return fail(VLC_ERR_SHAPE, "vlc_rope_shift_kv_layers: n_jobs=%d (0 ... 65535)", n_jobs);
+  if (max_n_tok < 0 || max_n_tok > ((int64_t)1 << 31))
+    return fail(VLC_ERR_SHAPE, "vlc_rope_shift_kv_layers: max_n_tok=%lld", (long long)max_n_tok);
+  if (!(rope_base > 0.0)) return fail(VLC_ERR_SHAPE, "vlc_rope_shift_kv_layers: rope_base must be positive");
+  if (n_jobs == 0 || max_n_tok == 0) return VLC_OK;
+  if (!jobs) return fail(VLC_ERR_NULL, "vlc_rope_shift_kv_layers: jobs is NULL");
+  if ((uintptr_t)jobs & 7) return fail(VLC_ERR_SHAPE, "vlc_rope_shift_kv_layers: jobs must be 8-byte aligned");
+  return vlc::launch_rope_shift_jobs(jobs, n_jobs, max_n_tok, Hkv, D, vlc::make_rope_freq(rope_base, D), dtype,
+                                     (hipStream_t)stream);
 }
 
 extern "C" int vlc_scatter_kv(const void* k_new, const void* v_new, const int32_t* dst_row, int64_t n,

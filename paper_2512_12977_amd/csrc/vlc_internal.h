@@ -65,6 +65,10 @@ int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v
                       const int32_t* src_row, const int32_t* dst_row, const int32_t* delta,
                       int64_t n_tok, int Hkv, int D, const RopeFreq& f, int dtype, hipStream_t st);
 
+// The same for n_jobs independent jobs (device table) in one launch; max_n_tok bounds every job's n_tok.
+int launch_rope_shift_jobs(const vlc_shift_job* jobs, int n_jobs, int64_t max_n_tok, int Hkv, int D,
+                           const RopeFreq& f, int dtype, hipStream_t st);
+
 // Strided scatter of K/V rows: cache[dst_row[i]] = src[i * src_stride_elems ...]
 int launch_scatter_kv(const void* k_new, const void* v_new, int64_t src_stride_elems,
                       const int32_t* dst_row, int64_t n, void* k_cache, void* v_cache, int Hkv, int D,

@@ -116,6 +116,29 @@ class DevicePlans:
                            p(d["pos3"]))
 
 
+class ShiftJobs:
+    """The reused keys/values of all layers as one job table for vlc_rope_shift_kv_layers: layer l moves the
+    rows plans.reuse lists for it from k_pool[l] / v_pool[l] into k_cache[l] / v_cache[l].  The layers are then
+    run with records made with k_pool=None (n_reuse = 0)."""
+
+    def __init__(self, plans: DevicePlans, k_pool, v_pool, k_cache, v_cache):
+        jobs = []
+        for l, d in enumerate(plans.dev):
+            if plans.n_reuse[l] > 0:
+                jobs.append((k_pool[l], v_pool[l], k_cache[l], v_cache[l], d["src_row"], d["dst_slot"], d["delta"]))
+        self.keep = jobs
+        self.n_jobs = len(jobs)
+        self.max_n_tok = max([j[4].numel() for j in jobs] + [0])
+        self.table = torch.from_numpy(B.shift_job_table(jobs)).to(k_cache[0].device) if jobs else None
+        self.Hkv, self.D = k_cache[0].shape[-2], k_cache[0].shape[-1]
+        self.dtype = B._dtype_code(k_cache[0])
+
+    def run(self, rope_base: float, stream=None) -> None:
+        if self.n_jobs:
+            B.vlc_rope_shift_kv_layers(self.table, self.n_jobs, self.max_n_tok, self.Hkv, self.D, rope_base,
+                                       self.dtype, stream)
+
+
 class Workspace:
     def __init__(self, shape_rec: B.LayerShape, n_rows_max: int, device="cuda"):
         nbytes = B.vlc_layer_workspace_bytes(shape_rec, n_rows_max)

@@ -101,6 +101,65 @@ def test_rope_shift_in_place_and_inverse(dtype):
         assert np.max(np.abs(back(d_k) - k0)) < 5e-6
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("Hkv,D,base,counts", [(2, 64, 1e4, (211, 0, 37, 1)), (4, 128, 1e6, (20, 517, 300, 64, 3)),
+                                               (8, 128, 1e6, (4000, 2500))])
+def test_rope_shift_kv_layers_vs_oracle(dtype, Hkv, D, base, counts):
+    """Several layers' reused keys in one launch (job table), token counts differing per job (one
+    table entry has n_tok = 0): against the oracle, and bit for
+    bit against the per-layer entry point."""
+    rng = np.random.default_rng(Hkv * D + len(counts))
+    pool, S = max(counts) + 90, max(counts) + 301
+    jobs, keep, want, single = [], [], [], []
+    for n in counts:
+        ks = rng.standard_normal((pool, Hkv, D)).astype(np.float32)
+        vs = rng.standard_normal((pool, Hkv, D)).astype(np.float32)
+        src, dst = rng.permutation(pool)[:n], rng.permutation(S)[:n]
+        delta = rng.integers(-20000, 20000, size=n)
+        d_ks, d_vs = to_dev(ks, dtype), to_dev(vs, dtype)
+        d_k = torch.zeros((S, Hkv, D), device=DEV, dtype=TD[dtype])
+        d_v = torch.zeros((S, Hkv, D), device=DEV, dtype=TD[dtype])
+        idx = (i32(src), i32(dst), i32(delta))
+        jobs.append((d_ks, d_vs, d_k, d_v) + idx)
+        want_k, want_v = np.zeros((S, Hkv, D)), np.zeros((S, Hkv, D))
+        want_k[dst] = orc.STORE[dtype](orc.rope_rotate(stored(ks, dtype)[src], delta, base))
+        want_v[dst] = stored(vs, dtype)[src]
+        want.append((want_k, want_v))
+        s_k, s_v = torch.zeros_like(d_k), torch.zeros_like(d_v)
+        if n:
+            vlc.vlc_rope_shift_kv(d_ks, d_vs, s_k, s_v, *idx, base)
+        single.append((s_k, s_v))
+    table = torch.from_numpy(vlc.shift_job_table(jobs)).to(DEV)
+    assert table.numel() == 64 * len(counts)
+    vlc.vlc_rope_shift_kv_layers(table, len(jobs), max(counts), Hkv, D, base, vlc.VLC_BF16 if dtype == "bf16" else vlc.VLC_F32)
+    torch.cuda.synchronize()
+    for j, (wk, wv) in zip(jobs, want):
+        assert_close(back(j[2]), wk, dtype, "shifted K")
+        np.testing.assert_array_equal(back(j[3]), wv)
+    for j, (s_k, s_v) in zip(jobs, single):
+        assert torch.equal(j[2], s_k) and torch.equal(j[3], s_v)
+
+
+def test_rope_shift_kv_layers_bound_and_keys_only():
+    """max_n_tok below a job's n_tok: only the first max_n_tok tokens move; v pointers NULL: keys only."""
+    rng = np.random.default_rng(77)
+    Hkv, D, base, n = 4, 128, 1e6, 100
+    ks = rng.standard_normal((n, Hkv, D)).astype(np.float32)
+    d_k = torch.zeros((n, Hkv, D), device=DEV, dtype=torch.float32)
+    rows, delta = np.arange(n), rng.integers(-500, 500, size=n)
+    job = (to_dev(ks, "f32"), None, d_k, None, i32(rows), i32(rows), i32(delta))
+    table = torch.from_numpy(vlc.shift_job_table([job])).to(DEV)
+    vlc.vlc_rope_shift_kv_layers(table, 1, 40, Hkv, D, base, vlc.VLC_F32)
+    torch.cuda.synchronize()
+    got = back(d_k)
+    assert_close(got[:40], orc.rope_rotate(ks[:40].astype(np.float64), delta[:40], base), "f32", "first 40")
+    assert not got[40:].any()
+    vlc.vlc_rope_shift_kv_layers(table, 0, 40, Hkv, D, base, vlc.VLC_F32)      # no jobs: nothing launched
+    vlc.vlc_rope_shift_kv_layers(table, 1, 0, Hkv, D, base, vlc.VLC_F32)       # no tokens: nothing launched
+    with pytest.raises(vlc.VlcError):
+        vlc.vlc_rope_shift_kv_layers(table, 1, 40, Hkv, 96, base, vlc.VLC_F32)
+
+
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_scatter_kv_bit_exact(dtype):

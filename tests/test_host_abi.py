@@ -233,3 +233,21 @@ def test_mean_squared_error_argument_checks():
     assert L.vlc_mean_squared_error_workspace_bytes() >= 8
     assert L.vlc_mean_squared_error(None, None, 0, None, None, 0, None) == 2      # n <= 0
     assert L.vlc_mean_squared_error(None, None, 5, None, None, 0, None) == 1      # NULL pointers
+
+
+def test_rope_shift_kv_layers_argument_checks():
+    """Everything the host can check is refused before any launch (no GPU needed)."""
+    L = vlc.lib()
+    assert ctypes.sizeof(vlc.ShiftJob) == 64                                     # 7 pointers + int64
+    f = L.vlc_rope_shift_kv_layers
+    assert f(None, 0, 0, 4, 128, 1e6, vlc.VLC_BF16, None) == 0                   # nothing to do
+    assert f(None, 3, 0, 4, 128, 1e6, vlc.VLC_BF16, None) == 0                   # no tokens: jobs not read
+    assert f(None, 3, 10, 4, 128, 1e6, vlc.VLC_BF16, None) == 1                  # NULL table
+    assert f(None, -1, 10, 4, 128, 1e6, vlc.VLC_BF16, None) == 2
+    assert f(None, 70000, 10, 4, 128, 1e6, vlc.VLC_BF16, None) == 2              # more jobs than grid rows
+    assert f(None, 3, -1, 4, 128, 1e6, vlc.VLC_BF16, None) == 2
+    assert f(None, 3, 10, 4, 96, 1e6, vlc.VLC_BF16, None) == 2                   # head size
+    assert f(None, 3, 10, 4, 128, 0.0, vlc.VLC_BF16, None) == 2                  # rope base
+    assert f(None, 3, 10, 4, 128, 1e6, 7, None) == 3                             # dtype
+    assert f(ctypes.c_void_p(0x1004), 3, 10, 4, 128, 1e6, vlc.VLC_BF16, None) == 2   # misaligned table
+    assert "aligned" in vlc.last_error()
