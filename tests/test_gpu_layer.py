@@ -39,9 +39,12 @@ def oracle_stack(wl, weights, emb, caches, k, explicit, layers, store=None):
     return res
 
 
-def run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher=None, all_rows=False, keep_ws=False):
+def run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher=None, all_rows=False, keep_ws=False,
+                  shift_ahead=False):
     """Runs `layers` layers on the GPU.  teacher: optional per-layer input rows (oracle outputs of the
-    previous layer) to feed instead of the GPU's own previous output.  Returns per-layer (h, K, V[, ws])."""
+    previous layer) to feed instead of the GPU's own previous output.  shift_ahead: the reused keys/values of all
+    layers are placed by one vlc_rope_shift_kv_layers call before the first layer and the layers get no reuse
+    list.  Returns per-layer (h, K, V[, ws])."""
     sh = wl.shape
     dt = R.torch_dtype(sh.dtype)
     rec = R.make_shape(sh)
@@ -52,17 +55,26 @@ def run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher=None, a
     h_prev = torch.from_numpy(emb).to(DEV).to(dt)
     n_prev = total
     out = []
+    kps = [torch.from_numpy(caches[l][0]).to(DEV).to(dt) for l in range(layers)]
+    vps = [torch.from_numpy(caches[l][1]).to(DEV).to(dt) for l in range(layers)]
+    kcs = [torch.zeros((total, sh.Hkv, sh.D), device=DEV, dtype=dt) for l in range(layers)]
+    vcs = [torch.zeros((total, sh.Hkv, sh.D), device=DEV, dtype=dt) for l in range(layers)]
+    if shift_ahead:
+        assert not all_rows
+        jobs = R.ShiftJobs(plans, kps, vps, kcs, vcs)
+        assert jobs.n_jobs == sum(1 for m in plans.n_reuse if m > 0)
+        jobs.run(sh.rope_base)
     for l in range(layers):
         W = R.DeviceWeights(weights[l], dt)
-        kp = torch.from_numpy(caches[l][0]).to(DEV).to(dt)
-        vp = torch.from_numpy(caches[l][1]).to(DEV).to(dt)
-        kc = torch.zeros((total, sh.Hkv, sh.D), device=DEV, dtype=dt)
-        vc = torch.zeros((total, sh.Hkv, sh.D), device=DEV, dtype=dt)
+        kp, vp, kc, vc = kps[l], vps[l], kcs[l], vcs[l]
+        if shift_ahead:
+            kp = vp = None
         if teacher is not None and l > 0:
             h_prev = torch.from_numpy(teacher[l - 1].astype(np.float32)).to(DEV).to(dt)
         n = plans.n_rows[l]
         h_out = torch.empty((n, sh.H), device=DEV, dtype=dt)
         prec = plans.record(l, n_prev, total, None if all_rows else kp, None if all_rows else vp)
+        assert not shift_ahead or prec.n_reuse == 0
         R.run_layer(rec, W, prec, h_prev, h_out, kc, vc, ws)
         torch.cuda.synchronize()
         item = [back(h_out), back(kc), back(vc)]
@@ -88,7 +100,7 @@ def read_workspace(sh, rec, ws, n):
     return res
 
 
-def check_against_oracle(wl, layers, teacher_forced, all_rows=False):
+def check_against_oracle(wl, layers, teacher_forced, all_rows=False, shift_ahead=False):
     sh = wl.shape
     k, explicit = plan_steps(wl)
     if all_rows:
@@ -100,7 +112,7 @@ def check_against_oracle(wl, layers, teacher_forced, all_rows=False):
     teacher = None
     if teacher_forced:
         teacher = [np.concatenate([ref[r][l]["h"] for r in range(len(wl.requests))]) for l in range(layers)]
-    got, plans = run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher, all_rows)
+    got, plans = run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher, all_rows, shift_ahead=shift_ahead)
     worst = 0.0
     for l in range(layers):
         want_h = np.concatenate([ref[r][l]["h"] for r in range(len(wl.requests))])
@@ -188,6 +200,22 @@ def test_two_packed_requests_fp32():
                       syn.Segment(107, 5, False)], 129, pos_start=11)
     wl = syn.Workload("two", sh, [r0, r1], 200, "static", static_k=40, seed=12)
     check_against_oracle(wl, layers=2, teacher_forced=False)
+
+
+def test_reused_keys_of_all_layers_placed_ahead_of_the_layer_loop():
+    """vlc_rope_shift_kv_layers + layers without a reuse list give the oracle's stack: two packed requests in
+    fp32, the bf16 tiny stack, and rates that fall with depth (a different reuse list in every layer)."""
+    sh = syn.SHAPES["tiny_bias"]
+    r0 = syn.Request([syn.Segment(0, 20, False), syn.Segment(20, 100, True, 3, 0), syn.Segment(120, 9, False)], 0)
+    r1 = syn.Request([syn.Segment(0, 7, False), syn.Segment(7, 60, True, 50, 100), syn.Segment(67, 40, True, 0, 160),
+                      syn.Segment(107, 5, False)], 129, pos_start=11)
+    check_against_oracle(syn.Workload("two", sh, [r0, r1], 200, "static", static_k=40, seed=12), layers=2,
+                         teacher_forced=False, shift_ahead=True)
+    check_against_oracle(syn.make_workload("c1_bf16"), layers=2, teacher_forced=True, shift_ahead=True)
+    wl = syn.Workload("falling", sh, [r0, r1], 200, "dynamic", budget_bp=2000, seed=13)
+    k, _ = plan_steps(wl)
+    assert len(set(k.tolist())) > 1
+    check_against_oracle(wl, layers=sh.L, teacher_forced=False, shift_ahead=True)
 
 
 def test_7b_shape_layer_stage_by_stage():
