@@ -1,7 +1,7 @@
 """Full-size parity on sampled outputs: one layer of the long-context batch (8 requests x 18432
-slots, 18944 packed recomputed rows, 7B shape) runs on the GPU exactly as bench.py launches it; for
-a few sampled rows of two requests every stage is compared with the oracle evaluated on the GPU's
-own input to that stage (element-wise, 2e-2 + 1e-2*|o|), and K/V rows are compared end to end."""
+slots, 18944 packed recomputed rows, 7B shape) and of the 72B-shaped workload runs on the GPU exactly
+as bench.py launches it; for a few sampled rows every stage is compared with the oracle evaluated on
+the GPU's own input to that stage (element-wise, 2e-2 + 1e-2*|o|), and K/V rows are compared end to end."""
 import numpy as np
 import pytest
 import torch
@@ -20,21 +20,28 @@ def back(t):
     return t.float().cpu().numpy().astype(np.float64)
 
 
-def test_c4_layer_sampled_rows():
-    wl = syn.make_workload("c4")
+@pytest.mark.parametrize("name,layer,req_ids,n_rows", [("c4", 0, (0, 5), 18944), ("c5", 0, (0,), None),
+                                                       ("c5", 79, (0,), None)])
+def test_full_size_layer_sampled_rows(name, layer, req_ids, n_rows):
+    """c4: the long-context batch at the 7B shape.  c5: the 72B shape (64 query / 8 kv heads, MLP width 29568) at
+    its first layer (the highest rate of the layer-aware plan) and its last (text rows only: every GEMM splits k).
+    The layer reads the embeddings as its input rows, whatever its depth."""
+    wl = syn.make_workload(name)
     sh = wl.shape
     st = orc.STORE[sh.dtype]
     dt = R.torch_dtype(sh.dtype)
     rec = R.make_shape(sh)
     k, explicit = plan_steps(wl)
-    W = syn.layer_weights(sh, wl.seed, 0)
+    k = k[layer:layer + 1]
+    W = syn.layer_weights(sh, wl.seed, layer)
     emb = syn.embedding_rows(wl)
-    Kc, Vc = syn.cached_kv(wl, 0)
+    Kc, Vc = syn.cached_kv(wl, layer)
     total = wl.total_slots
 
-    plans = R.DevicePlans(wl.requests, 1, k=k[:1])
+    plans = R.DevicePlans(wl.requests, 1, k=k)
     n = plans.n_rows[0]
-    assert n == 18944
+    assert n_rows is None or n == n_rows
+    print("%s layer %d: %d rows (k = %d)" % (name, layer, n, int(k[0])), flush=True)
     ws = R.Workspace(rec, n)
     dW = R.DeviceWeights(W, dt)
     kp, vp = torch.from_numpy(Kc).to(DEV).to(dt), torch.from_numpy(Vc).to(DEV).to(dt)
@@ -58,7 +65,7 @@ def test_c4_layer_sampled_rows():
 
     slot_all = plans.host["slot"][0, :n].astype(np.int64)
     rng = np.random.default_rng(0)
-    for r_i in (0, 5):
+    for r_i in req_ids:
         req = wl.requests[r_i]
         counts = counts_for(req, k, explicit, 0)
         slots = orc.select_slots(req.segments, counts)               # relative to the request
@@ -66,7 +73,8 @@ def test_c4_layer_sampled_rows():
         assert np.array_equal(slot_all[first:first + len(slots)], req.kv_start + slots)
         # sampled rows: first and last text rows, leading rows of an early and a late image, random ones
         cand = np.concatenate([[0, 1, len(slots) - 1, len(slots) - 2],
-                               np.searchsorted(slots, [s.start for s in req.segments if s.is_image][::5]),
+                               np.minimum(np.searchsorted(slots, [s.start for s in req.segments if s.is_image][::5]),
+                                          len(slots) - 1),
                                rng.integers(0, len(slots), size=6)])
         sel = np.unique(cand)
         rows = first + sel
