@@ -38,10 +38,14 @@ __device__ __forceinline__ float silu_f(float x) { return x * __builtin_amdgcn_r
 constexpr int kXcds = 8;
 constexpr int kGroupM = 8;
 
-__device__ __forceinline__ void tile_coords(int pid, int total, int tiles_m, int tiles_n, int* tm, int* tn) {
+__device__ __forceinline__ int xcd_contiguous(int pid, int total) {
   const int per = total / kXcds;
-  int vid = pid;
-  if (pid < per * kXcds) vid = (pid % kXcds) * per + pid / kXcds;
+  return pid < per * kXcds ? (pid % kXcds) * per + pid / kXcds : pid;
+}
+
+template <bool REMAP = true>
+__device__ __forceinline__ void tile_coords(int pid, int total, int tiles_m, int tiles_n, int* tm, int* tn) {
+  const int vid = REMAP ? xcd_contiguous(pid, total) : pid;
   const int in_group = kGroupM * tiles_n;
   const int group = vid / in_group;
   const int first_m = group * kGroupM;
@@ -131,8 +135,11 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   const int tiles = tiles_m * tiles_n;
   int split = 0, pid = blockIdx.x, tail_block = -1;   // tail_block >= 0: this workgroup owns one k-range of a tail tile
   if constexpr (EPI == EPI_PARTIAL) {
-    split = blockIdx.x / tiles;
-    pid = blockIdx.x - split * tiles;
+    // the whole grid (k range major) is dealt to the XCDs in contiguous pieces: an XCD then works on one or two
+    // k ranges and its L2 holds only their slices of A, instead of every XCD streaming all of A
+    const int b = xcd_contiguous(blockIdx.x, gridDim.x);
+    split = b / tiles;
+    pid = b - split * tiles;
   } else if ((int)blockIdx.x >= full_tiles) {
     tail_block = blockIdx.x - full_tiles;
     const int t = tail_block / tail_splits;
@@ -140,7 +147,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
     pid = full_tiles + t;
   }
   int tm, tn;
-  tile_coords(pid, tiles, tiles_m, tiles_n, &tm, &tn);
+  tile_coords<EPI != EPI_PARTIAL>(pid, tiles, tiles_m, tiles_n, &tm, &tn);
   int m0 = tm * BM;
   const int n0 = tn * CN;
   if constexpr (GROUPED) {
