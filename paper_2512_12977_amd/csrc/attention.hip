@@ -364,6 +364,11 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
   }
     // One key block j (S^T already in CUR): fetch ahead, start the next block's S^T into NXT (its MFMAs
     // are independent of this block's softmax arithmetic, so the two interleave), finish this block.
+    // The PV product runs at a raised wave priority: two wavefronts share a SIMD, and a wavefront's own vector
+    // instructions do not overlap with its MFMAs, so the matrix pipe is only kept busy when one wavefront
+    // multiplies while the other does its softmax arithmetic.  With equal priorities two wavefronts that reach
+    // their MFMA phases together alternate instruction by instruction and stay in step; the priority lets the
+    // one already in its pure-MFMA phase run ahead, which puts the pair out of step (-6 % kernel time).
 #define VLC_ATT_BLOCK(j_, PAR, CUR, NXT)                                                                       \
   {                                                                                                            \
     if ((j_) + 2 < n_blocks) VLC_ATT_ISSUE_K(kb_first + (j_) + 2, PAR)                                         \
@@ -374,7 +379,9 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
       VLC_ATT_QK(NXT, (PAR) ^ 1)   /* past the last block this reads a stale tile; the result is unused */     \
       VLC_ATT_SOFTMAX(CUR)                                                                                     \
       VLC_ATT_INTERLEAVE()                                                                                     \
+      __builtin_amdgcn_s_setprio(1);   /* see below */                                                         \
       VLC_ATT_RESCALE_PV(CUR, PAR)                                                                             \
+      __builtin_amdgcn_s_setprio(0);                                                                           \
     }                                                                                                          \
     VLC_ATT_WAIT_VM0();   /* this wavefront's shares of the tiles fetched above have landed */                 \
     __syncthreads();                                                                                           \
