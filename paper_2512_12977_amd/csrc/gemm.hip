@@ -783,7 +783,8 @@ int gemm_group_tile_rows(int64_t rows, int n_groups, int dtype) {
 
 int launch_gemm_grouped(const void* A, int64_t lda, const int32_t* amap, const void* W, int64_t w_stride, void* C,
                         int64_t ldc, int64_t rows, int n_groups, int64_t N, int64_t K, int epilogue,
-                        const GroupTile* tiles, const int32_t* n_tiles, int tile_rows, int dtype, hipStream_t st) {
+                        const GroupTile* tiles, const int32_t* n_tiles, int tile_rows, int dtype, hipStream_t st,
+                        int64_t a_rows) {
   if (rows <= 0 || N <= 0) return VLC_OK;
   if (K <= 0 || n_groups <= 0) return fail(VLC_ERR_SHAPE, "grouped gemm: K=%lld groups=%d", (long long)K, n_groups);
   if (rows > INT32_MAX || N > INT32_MAX / 2 || K > INT32_MAX)
@@ -796,8 +797,8 @@ int launch_gemm_grouped(const void* A, int64_t lda, const int32_t* amap, const v
   if (dtype == VLC_BF16) {
     if (K % BK || N % 4 || lda % 8 || ldc % 4)
       return fail(VLC_ERR_SHAPE, "grouped gemm(bf16): K=%lld must be a multiple of %d, N, lda, ldc aligned", (long long)K, BK);
-    // 32-bit lane offsets: rows fetched through amap are offsets from A itself (amap values are below `rows`)
-    if ((amap ? rows : 256) * lda * 2 >= ((int64_t)1 << 31) || ((epilogue == EPI_SWIGLU ? N : 0) + 256) * K * 2 >= ((int64_t)1 << 31))
+    // 32-bit lane offsets: rows fetched through amap are offsets from A itself (amap values are below a_rows)
+    if ((amap ? a_rows : 256) * lda * 2 >= ((int64_t)1 << 31) || ((epilogue == EPI_SWIGLU ? N : 0) + 256) * K * 2 >= ((int64_t)1 << 31))
       return fail(VLC_ERR_SHAPE, "grouped gemm(bf16): operand rows span more than 2 GiB");
     if (tile_rows == 256) {
       if (epilogue == EPI_SWIGLU)

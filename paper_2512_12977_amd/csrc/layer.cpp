@@ -232,11 +232,11 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
                                n * E, r_splits > 0 ? logits : nullptr, n, E, K, tile_rows, ms, st);
     if (rc) return rc;
     rc = vlc::launch_gemm_grouped(n2, H, ms.pair_row, w->w_gate_up, 2 * I * H, act, I, pairs, E, I, H,
-                                  vlc::EPI_SWIGLU, ms.tiles, ms.n_tiles, tile_rows, s.dtype, st);
+                                  vlc::EPI_SWIGLU, ms.tiles, ms.n_tiles, tile_rows, s.dtype, st, n);
     if (rc) return rc;
     VLC_MARK(8);
     rc = vlc::launch_gemm_grouped(act, I, nullptr, w->w_down, H * I, y, H, pairs, E, H, I, vlc::EPI_BIAS, ms.tiles,
-                                  ms.n_tiles, tile_rows, s.dtype, st);
+                                  ms.n_tiles, tile_rows, s.dtype, st, pairs);
     if (rc) return rc;
     rc = vlc::launch_moe_combine(h1, y, ms.wts, ms.pair_pos, n, K, s.H, h_out, s.dtype, st);
     if (rc) return rc;

@@ -117,15 +117,16 @@ int64_t gemm_splitk_ws_bytes(int64_t n_rows, int64_t max_n);
 // Grouped GEMM (mixture-of-experts): C[m, :] = epilogue(A[amap ? amap[m] : m, :] * W[g]^T) for the rows m
 // of group g; the rows of a group are contiguous in C.  `tiles` (device) lists (group, first row, end row)
 // with at most tile_rows rows each, *n_tiles (device) says how many entries count; both are written by
-// launch_moe_plan.  rows: total number of rows over all groups; w_stride: elements between two groups'
-// matrices.  Epilogues: EPI_BIAS without a bias (plain product) and EPI_SWIGLU.
+// launch_moe_plan.  rows: total number of rows over all groups; a_rows: rows of A (bound of the amap values, or
+// = rows without a map); w_stride: elements between two groups' matrices.  Epilogues: EPI_BIAS without a bias (plain product) and EPI_SWIGLU.
 struct GroupTile {
   int32_t expert, m0, m_end, pad;
 };
 int gemm_group_tile_rows(int64_t rows, int n_groups, int dtype);
 int launch_gemm_grouped(const void* A, int64_t lda, const int32_t* amap, const void* W, int64_t w_stride, void* C,
                         int64_t ldc, int64_t rows, int n_groups, int64_t N, int64_t K, int epilogue,
-                        const GroupTile* tiles, const int32_t* n_tiles, int tile_rows, int dtype, hipStream_t st);
+                        const GroupTile* tiles, const int32_t* n_tiles, int tile_rows, int dtype, hipStream_t st,
+                        int64_t a_rows);
 
 // Mixture-of-experts routing.  All pointers device.  launch_moe_route: from router scores [n, E] (float)
 // writes the chosen experts idx [n, K], weights wts [n, K], the grouped order (offset [E + 1]: first pair

@@ -119,3 +119,61 @@ def test_moe_many_pairs_grouped_with_atomic_ranks():
     wl = syn.Workload("moe_many", sh, reqs, 1, "static", static_k=0, seed=14)
     g = check_moe_layer(wl, 0)
     assert g["moe_idx"].shape == (330 * 124, 2)
+
+
+def test_moe_more_pairs_than_2_gib_of_input_rows():
+    """66000 rows at the 30B-A3B shape: 528000 (row, expert) pairs, so pairs x row bytes (2.2 GB) passes the 2 GiB
+    that the grouped GEMM's 32-bit row offsets cover while the rows themselves (270 MB) do not - the bound that
+    counts is the rows'.  Grouping invariants on everything; the experts' arithmetic on 48 sampled rows."""
+    sh = syn.SHAPES["q3vl_30b_a3b"]
+    st = orc.STORE[sh.dtype]
+    dt = R.torch_dtype(sh.dtype)
+    T, B = 1000, 66
+    reqs = [syn.Request([syn.Segment(0, T, False)], T * i, 0, syn.grid_positions([("text", T)])) for i in range(B)]
+    wl = syn.Workload("moe_wide", sh, reqs, 1, "static", static_k=0, seed=15)
+    W = syn.layer_weights(sh, wl.seed, 0)
+    emb = syn.embedding_rows(wl)
+    rec = R.make_shape(sh)
+    plans = R.DevicePlans(wl.requests, 1, k=np.zeros(1, dtype=np.int32))
+    n, total = plans.n_rows[0], wl.total_slots
+    assert n == T * B and n * sh.top_k * sh.H * 2 >= 2 ** 31 > n * sh.H * 2
+    ws = R.Workspace(rec, n)
+    dW = R.DeviceWeights(W, dt)
+    kc = torch.zeros((total, sh.Hkv, sh.D), device=DEV, dtype=dt)
+    vc = torch.zeros_like(kc)
+    h_in = torch.from_numpy(emb).to(DEV).to(dt)
+    h_out = torch.empty((n, sh.H), device=DEV, dtype=dt)
+    R.run_layer(rec, dW, plans.record(0, total, total, None, None), h_in, h_out, kc, vc, ws)
+    torch.cuda.synchronize()
+
+    off = vlc.vlc_layer_workspace_layout(rec, n)
+    K, E, P = sh.top_k, sh.n_experts, n * sh.top_k
+
+    def take(name, tdt, shape, size):
+        return ws.t[off[name]:off[name] + int(np.prod(shape)) * size].view(tdt).reshape(shape)
+
+    idx = take("moe_idx", torch.int32, (n, K), 4).cpu().numpy().astype(np.int64)
+    pos = take("moe_pos", torch.int32, (n, K), 4).cpu().numpy().astype(np.int64)
+    offset = take("moe_offset", torch.int32, (E + 1,), 4).cpu().numpy().astype(np.int64)
+    counts = np.bincount(idx.ravel(), minlength=E)
+    np.testing.assert_array_equal(offset, np.concatenate([[0], np.cumsum(counts)]))
+    assert np.array_equal(np.sort(pos.ravel()), np.arange(P))
+    assert np.all(pos >= offset[idx]) and np.all(pos < offset[idx + 1])
+
+    sel = np.unique(np.concatenate([[0, 1, n - 1], np.random.default_rng(0).integers(0, n, size=45)]))
+    sel_t = torch.from_numpy(sel).to(DEV)
+    pos_t = torch.from_numpy(pos[sel]).to(DEV)
+    n2 = back(take("n2", dt, (n, sh.H), 2)[sel_t])
+    h1 = back(take("h1", dt, (n, sh.H), 2)[sel_t])
+    logits = back(take("moe_logits", torch.float32, (n, E), 4)[sel_t])
+    wts = back(take("moe_w", torch.float32, (n, K), 4)[sel_t])
+    act = back(take("act", dt, (P, sh.I), 2)[pos_t])
+    y = back(take("moe_y", dt, (P, sh.H), 2)[pos_t])
+    Ws = {name: (None if w is None else st(w)) for name, w in W.items()}
+    want_idx, want_w = orc.route_top_k(logits, K)
+    np.testing.assert_array_equal(idx[sel], want_idx)
+    np.testing.assert_allclose(wts, want_w, rtol=2e-6, atol=1e-7)
+    r = orc.moe_mlp(sh, Ws, n2, st, {"moe_idx": idx[sel], "moe_w": wts, "act": act, "y": y})
+    assert_close(act, r["act"], sh.dtype, "SwiGLU product of the chosen experts")
+    assert_close(y, r["y"], sh.dtype, "expert outputs")
+    assert_close(back(h_out[sel_t]), st(h1 + r["mlp"]), sh.dtype, "weighted sum + residual")
