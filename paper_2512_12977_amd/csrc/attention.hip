@@ -89,9 +89,11 @@ __device__ __forceinline__ float pair_sum(float v) {
 
 #define VLC_ATT_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8) | (0 << 14))
 
-// SPLIT: blockIdx.z handles every nsplit-th share of each run's key blocks and leaves an
-// un-normalised partial (O as float, running max, running sum) for attention_merge_kernel; used when
-// there are too few (row tile, kv head) pairs to occupy the chip and the key loop is the critical path.
+// SPLIT: blockIdx.z handles the z-th share of split_blocks key blocks of each run (the last share also what
+// lies beyond) and leaves an un-normalised partial (O as float, running max, running sum) for
+// attention_merge_kernel; a workgroup whose share starts beyond the tile's longest row leaves at once and writes
+// nothing.  Used when there are too few (row tile, kv head) pairs to occupy the chip and the key loop is the
+// critical path: rows with few keys then stay whole and only the long ones are shared out.
 // RT: 32-row tiles of virtual rows per wavefront.  RT = 1: 128 virtual rows per workgroup, two
 // workgroups per CU.  RT = 2: 256 virtual rows, one workgroup per CU; every K and V fragment read
 // from LDS then feeds two MFMAs, which halves the LDS traffic per flop (with one row tile the
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
     const uint16_t* __restrict__ q, int64_t q_stride, const uint16_t* __restrict__ kc,
     const uint16_t* __restrict__ vc, const int32_t* __restrict__ row_kv_start,
     const int32_t* __restrict__ row_kv_len, int n, int Hq, int Hkv, int g, int rows_per_tile,
-    float scale_log2, uint16_t* __restrict__ out, int nsplit, float* __restrict__ part_o,
+    float scale_log2, uint16_t* __restrict__ out, int split_blocks, float* __restrict__ part_o,
     float* __restrict__ part_ml) {
   __shared__ u32x4 lds[2 * ATT_STAGE_CHUNKS];     // 64 KB: K ring (2 tiles), then V ring (2 tiles)
   __shared__ int s_start[VR * RT];
@@ -125,6 +127,11 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
     s_len[tid] = ok ? row_kv_len[row0 + tid] : 0;
   }
   __syncthreads();
+  if (SPLIT) {   // nothing of this tile reaches this share's first key: attention_merge_kernel will not read it
+    int tile_max = 0;
+    for (int r = 0; r < rows_here; ++r) tile_max = max(tile_max, s_len[r]);
+    if ((int64_t)blockIdx.z * split_blocks * KB >= tile_max) return;
+  }
 
   // this lane's virtual rows (one per row tile)
   int r_local[RT], head[RT], my_len[RT];
@@ -235,9 +242,8 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
     const int all_blocks = (seg_max + KB - 1) / KB;
     int kb_first = 0, n_blocks = all_blocks;        // this workgroup's share of the run's key blocks
     if (SPLIT) {
-      const int per = (all_blocks + nsplit - 1) / nsplit;
-      kb_first = min(all_blocks, (int)blockIdx.z * per);
-      n_blocks = min(all_blocks, kb_first + per) - kb_first;
+      kb_first = min(all_blocks, (int)blockIdx.z * split_blocks);
+      n_blocks = (blockIdx.z + 1 == gridDim.z ? all_blocks : min(all_blocks, kb_first + split_blocks)) - kb_first;
     }
     const int last_key = seg_max - 1;               // loads never leave the run's key range
 
@@ -451,15 +457,19 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
   }
 }
 
-// Merge of the split partials: out = sum_z O_z 2^(m_z - m) / sum_z l_z 2^(m_z - m), m = max_z m_z.
+// Merge of the split partials: out = sum_z O_z 2^(m_z - m) / sum_z l_z 2^(m_z - m), m = max_z m_z, over the
+// shares that hold keys of the row (share z starts at key block z * split_blocks; the others were not written).
 // One thread per 8 output elements.
 __global__ __launch_bounds__(256) void attention_merge_kernel(const float* __restrict__ part_o,
-                                                              const float* __restrict__ part_ml, int nsplit,
-                                                              int64_t rows_heads, uint16_t* __restrict__ out) {
+                                                              const float* __restrict__ part_ml, int max_split,
+                                                              int split_blocks, const int32_t* __restrict__ row_kv_len,
+                                                              int Hq, int64_t rows_heads, uint16_t* __restrict__ out) {
   const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t rh = id / (ATT_D / 8);
   const int c = (int)(id - rh * (ATT_D / 8));
   if (rh >= rows_heads) return;
+  const int blocks = (row_kv_len[rh / Hq] + KB - 1) / KB;
+  const int nsplit = min(max_split, (blocks + split_blocks - 1) / split_blocks);
   float m = -INFINITY;
   for (int z = 0; z < nsplit; ++z) m = fmaxf(m, part_ml[2 * (z * rows_heads + rh)]);
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -580,17 +590,21 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
     const int rows_per_tile = (wide ? 2 * VR : VR) / g;
     const int64_t tiles = (n + rows_per_tile - 1) / rows_per_tile;
     // Few workgroups (512 are resident at once, two per CU): the key loop of the longest rows is the
-    // critical path, so split the key range over up to 1024 workgroups, keeping at least 8 key blocks
-    // per share (shorter shares cost more in partials and merging than they save).
-    int nsplit = 1;
+    // critical path, so their key range is shared out in pieces of split_blocks key blocks: as few blocks as
+    // keep the grid within 1024 workgroups and 8 shares (the workspace), but at least 4 (shorter shares cost
+    // more in partials and merging than they save).  Without a bound on the lengths: 8 blocks per share, the
+    // last share takes the rest.
+    int nsplit = 1, split_blocks = 8;
     if (!wide && ws && tiles * Hkv < 512) {
       nsplit = (int)(1024 / (tiles * Hkv));
       if (nsplit > 8) nsplit = 8;
-      if (max_kv_len > 0) {
-        const int64_t by_len = max_kv_len / (8 * KB);
-        if (nsplit > by_len) nsplit = by_len > 1 ? (int)by_len : 1;
-      }
       while (nsplit > 1 && (int64_t)nsplit * n * Hq * (ATT_D + 2) * 4 > ws_bytes) --nsplit;
+      if (max_kv_len > 0) {
+        const int64_t blocks = (max_kv_len + KB - 1) / KB;
+        split_blocks = (int)((blocks + nsplit - 1) / nsplit);
+        if (split_blocks < 4) split_blocks = 4;
+        nsplit = (int)((blocks + split_blocks - 1) / split_blocks);
+      }
     }
     if (nsplit > 1) {
       float* part_o = static_cast<float*>(ws);
@@ -598,12 +612,12 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
       const dim3 grid((unsigned)tiles, (unsigned)Hkv, (unsigned)nsplit);
       hipLaunchKernelGGL((attention_bf16_kernel<true, 1>), grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
                          (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
-                         Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, nsplit, part_o,
+                         Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, split_blocks, part_o,
                          part_ml);
       VLC_CHECK_LAUNCH("attention_bf16(split)");
       const int64_t threads = n * Hq * (ATT_D / 8);
       hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, part_o,
-                         part_ml, nsplit, n * Hq, (uint16_t*)out);
+                         part_ml, nsplit, split_blocks, row_kv_len, Hq, n * Hq, (uint16_t*)out);
       VLC_CHECK_LAUNCH("attention_merge");
       return VLC_OK;
     }
