@@ -202,6 +202,20 @@ def test_two_packed_requests_fp32():
     check_against_oracle(wl, layers=2, teacher_forced=False)
 
 
+def test_three_packed_requests_bf16_keys_shared_out_over_workgroups():
+    """Few rows, so the bf16 attention shares the keys out in pieces of 4 blocks (1220 slots: 5 pieces): rows of three
+    requests of 700, 130 and 390 slots share row tiles, the short request's rows fit one piece, the long one's
+    need up to three, and the pieces beyond a tile's longest row are never written."""
+    sh = syn.SHAPES["tiny_bf16"]
+    r0 = syn.Request([syn.Segment(0, 40, False), syn.Segment(40, 600, True, 7, 0), syn.Segment(640, 60, False)], 0)
+    r1 = syn.Request([syn.Segment(0, 30, False), syn.Segment(30, 80, True, 200, 600), syn.Segment(110, 20, False)], 700,
+                     pos_start=5)
+    r2 = syn.Request([syn.Segment(0, 90, False), syn.Segment(90, 300, True, 0, 680)], 830)
+    wl = syn.Workload("three", sh, [r0, r1, r2], 980, "static", static_k=40, seed=17)
+    check_against_oracle(wl, layers=2, teacher_forced=True)
+    check_against_oracle(wl, layers=2, teacher_forced=False, shift_ahead=True)
+
+
 def test_reused_keys_of_all_layers_placed_ahead_of_the_layer_loop():
     """vlc_rope_shift_kv_layers + layers without a reuse list give the oracle's stack: two packed requests in
     fp32, the bf16 tiny stack, and rates that fall with depth (a different reuse list in every layer)."""
