@@ -584,10 +584,10 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
     if (D != ATT_D) return fail(VLC_ERR_SHAPE, "attention(bf16): D=%d unsupported (128 only)", D);
     if (g > VR) return fail(VLC_ERR_SHAPE, "attention(bf16): Hq/Hkv=%d exceeds %d", g, VR);
     if (q_stride % 8) return fail(VLC_ERR_SHAPE, "attention(bf16): q row stride must be a multiple of 8");
-    // Many rows: 256 virtual rows per workgroup (two row tiles per wavefront, one workgroup per
-    // CU).  Few rows: 128 virtual rows, two workgroups per CU, so that more workgroups exist.
-    const bool wide = false;   // (two row tiles per wavefront: register allocation not yet clean)
-    const int rows_per_tile = (wide ? 2 * VR : VR) / g;
+    // 128 virtual rows per workgroup, two workgroups per CU (RT = 1).  The kernel is also written for two row
+    // tiles per wavefront (RT = 2: 256 virtual rows, one workgroup per CU), which is not launched: it needs
+    // more registers than a wavefront has (147 spilled) and one wavefront per SIMD overlaps nothing.
+    const int rows_per_tile = VR / g;
     const int64_t tiles = (n + rows_per_tile - 1) / rows_per_tile;
     // Few workgroups (512 are resident at once, two per CU): the key loop of the longest rows is the
     // critical path, so their key range is shared out in pieces of split_blocks key blocks: as few blocks as
@@ -595,7 +595,7 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
     // more in partials and merging than they save).  Without a bound on the lengths: 8 blocks per share, the
     // last share takes the rest.
     int nsplit = 1, split_blocks = 8;
-    if (!wide && ws && tiles * Hkv < 512) {
+    if (ws && tiles * Hkv < 512) {
       nsplit = (int)(1024 / (tiles * Hkv));
       if (nsplit > 8) nsplit = 8;
       while (nsplit > 1 && (int64_t)nsplit * n * Hq * (ATT_D + 2) * 4 > ws_bytes) --nsplit;
@@ -622,16 +622,10 @@ int launch_attention(const void* q, int64_t q_stride, const void* k_cache, const
       return VLC_OK;
     }
     const dim3 grid((unsigned)tiles, (unsigned)Hkv);
-    if (wide)
-      hipLaunchKernelGGL((attention_bf16_kernel<false, 2>), grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
-                         (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
-                         Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, 1, nullptr,
-                         nullptr);
-    else
-      hipLaunchKernelGGL((attention_bf16_kernel<false, 1>), grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
-                         (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
-                         Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, 1, nullptr,
-                         nullptr);
+    hipLaunchKernelGGL((attention_bf16_kernel<false, 1>), grid, dim3(256), 0, st, (const uint16_t*)q, q_stride,
+                       (const uint16_t*)k_cache, (const uint16_t*)v_cache, row_kv_start, row_kv_len, (int)n,
+                       Hq, Hkv, g, rows_per_tile, scale * 1.4426950408889634f, (uint16_t*)out, 1, nullptr,
+                       nullptr);
     VLC_CHECK_LAUNCH("attention_bf16");
     return VLC_OK;
   }
