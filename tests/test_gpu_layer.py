@@ -202,6 +202,18 @@ def test_two_packed_requests_fp32():
     check_against_oracle(wl, layers=2, teacher_forced=False)
 
 
+@pytest.mark.parametrize("rows", [1, 2, 31, 33, 64, 65, 127, 129, 191, 193, 255, 257, 383, 385, 513, 641])
+def test_bf16_layer_row_counts_around_tile_edges(rows):
+    """One bf16 layer over `rows` text tokens (every row computed): row counts just below, at and above the 32-row
+    MFMA tiles and the 128-row workgroup tiles, so that the clamped loads of a ragged last tile, its guarded
+    stores, the ragged last column tile of the 96-column gate|up tiles and the key split of the attention (from
+    257 rows on there are more than 4 key blocks) are all hit."""
+    sh = syn.SHAPES["tiny_bf16"]
+    req = syn.Request([syn.Segment(0, rows, False)], 0)
+    wl = syn.Workload("rows_%d" % rows, sh, [req], 1, "static", static_k=0, seed=100 + rows)
+    check_against_oracle(wl, layers=1, teacher_forced=False, all_rows=True)
+
+
 def test_three_packed_requests_bf16_keys_shared_out_over_workgroups():
     """Few rows, so the bf16 attention shares the keys out in pieces of 4 blocks (1220 slots: 5 pieces): rows of three
     requests of 700, 130 and 390 slots share row tiles, the short request's rows fit one piece, the long one's
