@@ -251,3 +251,27 @@ def test_rope_shift_kv_layers_argument_checks():
     assert f(None, 3, 10, 4, 128, 1e6, 7, None) == 3                             # dtype
     assert f(ctypes.c_void_p(0x1004), 3, 10, 4, 128, 1e6, vlc.VLC_BF16, None) == 2   # misaligned table
     assert "aligned" in vlc.last_error()
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """include/vlcache.h compiles as C99 (-pedantic, warnings as errors) and a C program linked against the library
+    gets the planner's result (host entry points only: no GPU needed)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "abi.c"
+    src.write_text('#include "vlcache.h"\n#include <stdio.h>\n'
+                   "int main(void) {\n"
+                   "  double sens[8] = {4, 3, 2, 1, 8, 4, 2, 1};\n"
+                   "  int32_t k[2];\n"
+                   "  int rc = vlc_plan_layer_rates(2, 3, sens, 3, k);\n"
+                   '  printf("%d %d %d %d\\n", vlc_version(), rc, (int)k[0], (int)k[1]);\n'
+                   "  return rc;\n}\n")
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(vlc.lib_path())
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-l:libvlcache.so", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    want = orc.plan_layer_rates(np.array([[4, 3, 2, 1], [8, 4, 2, 1]], dtype=np.float64), 3)
+    assert [int(v) for v in out] == [vlc.lib().vlc_version(), 0, int(want[0]), int(want[1])]
