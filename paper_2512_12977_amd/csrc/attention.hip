@@ -470,19 +470,41 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(const float* __res
   if (rh >= rows_heads) return;
   const int blocks = (row_kv_len[rh / Hq] + KB - 1) / KB;
   const int nsplit = min(max_split, (blocks + split_blocks - 1) / split_blocks);
+  // all loads of a pass are issued together (max_split <= 8): running maxima and sums first, then the outputs
+  constexpr int MAXZ = 8;
+  float mz[MAXZ], lz[MAXZ];
+#pragma unroll
+  for (int z = 0; z < MAXZ; ++z) {
+    mz[z] = -INFINITY;
+    lz[z] = 0.f;
+    if (z < nsplit) {
+      const float2 ml = *reinterpret_cast<const float2*>(part_ml + 2 * (z * rows_heads + rh));
+      mz[z] = ml.x;
+      lz[z] = ml.y;
+    }
+  }
   float m = -INFINITY;
-  for (int z = 0; z < nsplit; ++z) m = fmaxf(m, part_ml[2 * (z * rows_heads + rh)]);
+#pragma unroll
+  for (int z = 0; z < MAXZ; ++z) m = fmaxf(m, mz[z]);
+  float4 pa[MAXZ], pb[MAXZ];
+  float wz[MAXZ];
+#pragma unroll
+  for (int z = 0; z < MAXZ; ++z) {
+    wz[z] = mz[z] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mz[z] - m);   // -inf: this share saw no visible key
+    pa[z] = pb[z] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (z < nsplit && mz[z] != -INFINITY) {
+      const float4* po = reinterpret_cast<const float4*>(part_o + (z * rows_heads + rh) * ATT_D + 8 * c);
+      pa[z] = po[0];
+      pb[z] = po[1];
+    }
+  }
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float l = 0.f;
-  for (int z = 0; z < nsplit; ++z) {
-    const float mz = part_ml[2 * (z * rows_heads + rh)];
-    if (mz == -INFINITY) continue;                     // this share saw no visible key
-    const float w = __builtin_amdgcn_exp2f(mz - m);
-    l += part_ml[2 * (z * rows_heads + rh) + 1] * w;
-    const float4* po = reinterpret_cast<const float4*>(part_o + (z * rows_heads + rh) * ATT_D + 8 * c);
-    const float4 a = po[0], b = po[1];
-    acc[0] += a.x * w; acc[1] += a.y * w; acc[2] += a.z * w; acc[3] += a.w * w;
-    acc[4] += b.x * w; acc[5] += b.y * w; acc[6] += b.z * w; acc[7] += b.w * w;
+#pragma unroll
+  for (int z = 0; z < MAXZ; ++z) {      // in share order, as before
+    l += lz[z] * wz[z];
+    acc[0] += pa[z].x * wz[z]; acc[1] += pa[z].y * wz[z]; acc[2] += pa[z].z * wz[z]; acc[3] += pa[z].w * wz[z];
+    acc[4] += pb[z].x * wz[z]; acc[5] += pb[z].y * wz[z]; acc[6] += pb[z].z * wz[z]; acc[7] += pb[z].w * wz[z];
   }
   const float inv = l > 0.f ? 1.0f / l : 0.f;
   u32x4 w4;
