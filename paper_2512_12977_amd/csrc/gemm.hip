@@ -613,8 +613,9 @@ int launch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
 }
 
 // Tile choice.  Many rows: 256 x 256 tiles, 4 wavefronts of 128 x 128 or 8 of 64 x 128.  Few rows: two workgroups per CU, on
-// 128 x 192 tiles (4 wavefronts of 32 x 192: 96 output columns) for gate|up, and on 128 x 128 tiles (4 wavefronts of
-// 64 x 64) for the others, whose k range is split as well if the tiles still leave most of the 256 CUs idle.
+// 128 x 192 tiles for gate|up (4 wavefronts of 32 x 192, so that each holds the gate and the up columns of its 96
+// outputs), and on 128 x 128 (4 wavefronts of 64 x 64) or 128 x 192 tiles (4 of 64 x 96: fewer fragment reads per
+// MFMA than 32 x 192) for the others, whose k range is split as well if the tiles still leave most of the 256 CUs idle.
 template <int EPI>
 int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
                   int64_t K, const void* bias, const void* resid, int64_t ldr, const int32_t* rmap,
@@ -685,7 +686,7 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
     }
     if (splits <= 1) {
       if (width == 192)
-        return launch_bf16<128, 192, 4, 1, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT,
+        return launch_bf16<128, 192, 2, 2, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT,
                                                       splitk_ws, splitk_ws_bytes, st);
       return launch_bf16<128, 128, 2, 2, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT,
                                                     splitk_ws, splitk_ws_bytes, st);
@@ -694,7 +695,7 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
     splits = (KT + per - 1) / per;
     int rc;
     if (width == 192)
-      rc = launch_bf16<128, 192, 4, 1, 2, 2, EPI_PARTIAL>(A, lda, W, splitk_ws, N, M, N, K, nullptr, nullptr, 0,
+      rc = launch_bf16<128, 192, 2, 2, 2, 2, EPI_PARTIAL>(A, lda, W, splitk_ws, N, M, N, K, nullptr, nullptr, 0,
                                                           nullptr, splits, per, nullptr, 0, st);
     else
       rc = launch_bf16<128, 128, 2, 2, 2, 2, EPI_PARTIAL>(A, lda, W, splitk_ws, N, M, N, K, nullptr, nullptr, 0,
