@@ -127,7 +127,26 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   // columns of C covered by this tile: SwiGLU consumes a gate and an up row per output column
   constexpr int CN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   static_assert(STAGES >= 2 && STAGES <= 4, "ring depth");
-  static_assert(EPI != EPI_SWIGLU || NT % 2 == 0, "SwiGLU pairs tiles inside a wavefront");
+  // SwiGLU pairs a gate and an up column inside a lane.  Even NT: the wavefront's first NT/2 tiles are gate columns,
+  // the others the up columns of the same outputs.  Odd NT (MIXED): FT = NT/2 such pairs of tiles, then one tile
+  // whose columns 0-15 are gate and 16-31 up columns of 16 more outputs (registers j and j + 8 of a lane).
+  constexpr bool MIXED = EPI == EPI_SWIGLU && NT % 2 == 1;
+  constexpr int FT = NT / 2;
+  static_assert(!MIXED || WN == 64 * FT + 32, "mixed SwiGLU tile: wavefront columns");
+  // W row of the tile (= LDS row) -> row of the weight matrix relative to n0; the up rows lie N rows further
+  auto swiglu_row = [&](int r, bool* up) {
+    if constexpr (MIXED) {
+      const int wv = r / WN, lr = r - wv * WN;
+      int c;
+      if (lr < 32 * FT) { *up = false; c = lr; }
+      else if (lr < 64 * FT) { *up = true; c = lr - 32 * FT; }
+      else { const int m = lr - 64 * FT; *up = m >= 16; c = 32 * FT + (m & 15); }
+      return wv * (WN / 2) + c;
+    } else {
+      *up = r >= BN / 2;
+      return *up ? r - BN / 2 : r;
+    }
+  };
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4* lds = reinterpret_cast<u32x4*>(smem);
@@ -190,8 +209,13 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
     const int p = (wave * W_INSTR + i) * 64 + lane;
     const int r = p >> 3, c = (p & 7) ^ fswz(r);
     int gr;
-    if constexpr (EPI == EPI_SWIGLU) gr = r < BN / 2 ? n0 + r : N + n0 + (r - BN / 2);   // gate | up rows
-    else gr = n0 + r;
+    if constexpr (EPI == EPI_SWIGLU) {
+      bool up;
+      const int c = swiglu_row(r, &up);
+      gr = (up ? N : 0) + n0 + c;
+    } else {
+      gr = n0 + r;
+    }
     const int limit = (EPI == EPI_SWIGLU) ? 2 * N : N;
     gr = gr < limit ? gr : limit - 1;
     w_lane[i] = (uint32_t)(((int64_t)(gr - n0) * K + c * 8) * 2);
@@ -213,7 +237,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     int r;
-    if constexpr (EPI == EPI_SWIGLU)
+    if constexpr (EPI == EPI_SWIGLU && !MIXED)
       r = (nt < NT / 2 ? wn * (WN / 2) + nt * 32 : BN / 2 + wn * (WN / 2) + (nt - NT / 2) * 32) + l32;
     else
       r = wn * WN + nt * 32 + l32;
@@ -315,14 +339,17 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
         const int ml = wm * WM + mt * 32 + l32;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-          int j0;   // row of the W tile this accumulator tile starts at
+          int j0;   // gate | up position (gate columns of the tile first, then its up columns) this tile starts at
           if constexpr (EPI == EPI_SWIGLU)
-            j0 = nt < NT / 2 ? wn * (WN / 2) + nt * 32 : BN / 2 + wn * (WN / 2) + (nt - NT / 2) * 32;
+            j0 = nt < FT ? wn * (WN / 2) + nt * 32 : BN / 2 + wn * (WN / 2) + (nt - FT) * 32;
           else
             j0 = wn * WN + nt * 32;
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const int j = j0 + 4 * x + 8 * q;
+            int j = j0 + 4 * x + 8 * q;
+            if constexpr (MIXED) {
+              if (nt == NT - 1) j = (q < 2 ? 0 : BN / 2) + wn * (WN / 2) + 32 * FT + 4 * x + 8 * (q & 1);
+            }
             *reinterpret_cast<float4*>(P + ((int64_t)(j >> 2) * BM + ml) * 4) =
                 make_float4(acc[nt][mt][4 * q], acc[nt][mt][4 * q + 1], acc[nt][mt][4 * q + 2], acc[nt][mt][4 * q + 3]);
           }
@@ -379,6 +406,20 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
           o.y = pack_bf16x2(v[2], v[3]);
           *reinterpret_cast<uint2*>(C + (int64_t)m * ldc + n) = o;
         }
+      }
+    }
+    if constexpr (MIXED) {   // the last tile: gate columns in registers 0-7, the up columns of the same outputs in 8-15
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int n = n0 + wn * OWN + 32 * FT + 4 * x + 8 * q;
+        if (n >= N) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = silu_f(acc[NT - 1][mt][4 * q + e]) * acc[NT - 1][mt][4 * (q + 2) + e];
+        uint2 o;
+        o.x = pack_bf16x2(v[0], v[1]);
+        o.y = pack_bf16x2(v[2], v[3]);
+        *reinterpret_cast<uint2*>(C + (int64_t)m * ldc + n) = o;
       }
     }
   }
@@ -613,9 +654,9 @@ int launch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
 }
 
 // Tile choice.  Many rows: 256 x 256 tiles, 4 wavefronts of 128 x 128 or 8 of 64 x 128.  Few rows: two workgroups per CU, on
-// 128 x 192 tiles for gate|up (4 wavefronts of 32 x 192, so that each holds the gate and the up columns of its 96
-// outputs), and on 128 x 128 (4 wavefronts of 64 x 64) or 128 x 192 tiles (4 of 64 x 96: fewer fragment reads per
-// MFMA than 32 x 192) for the others, whose k range is split as well if the tiles still leave most of the 256 CUs idle.
+// 128 x 192 tiles for gate|up (4 wavefronts of 64 x 96: 32 gate, 32 up and a mixed tile of 16 + 16 columns, so that
+// each holds the gate and the up columns of its 48 outputs), and on 128 x 128 (4 wavefronts of 64 x 64) or 128 x 192
+// tiles (4 of 64 x 96) for the others, whose k range is split as well if the tiles still leave most of the 256 CUs idle.
 template <int EPI>
 int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int64_t M, int64_t N,
                   int64_t K, const void* bias, const void* resid, int64_t ldr, const int32_t* rmap,
@@ -653,7 +694,7 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
                                                     splitk_ws, splitk_ws_bytes, st);
   }
   if constexpr (EPI == EPI_SWIGLU) {
-    return launch_bf16<128, 192, 4, 1, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, splitk_ws,
+    return launch_bf16<128, 192, 2, 2, 2, 2, EPI>(A, lda, W, C, ldc, M, N, K, bias, resid, ldr, rmap, 1, KT, splitk_ws,
                                                   splitk_ws_bytes, st);
   } else {
     // Tile width (128 or 192 columns) and number of k ranges, by cost in units of one 128 x 128 workgroup's
