@@ -147,6 +147,9 @@ def main() -> int:
     ap.add_argument("--per-layer-shift", action="store_true",
                     help="re-rotate the reused keys inside every layer call instead of in one launch for all "
                          "layers ahead of the layer loop")
+    ap.add_argument("--no-chain", action="store_true",
+                    help="every layer takes its own input norm (default: a layer whose successor recomputes the "
+                         "same rows leaves that norm behind, vlc_layer_forward_chained)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain row copy of 1 GiB through vlc_gather_rows "
                          "(identity index) so a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -228,15 +231,8 @@ def main() -> int:
             shift_all.run(sh.rope_base)
             if shift_events is not None:
                 hev.record(shift_events[1], stream)
-        h_in = emb
-        for l in range(L):
-            h_out = hbuf[l & 1]
-            if events is None:
-                vlc.vlc_layer_forward(rec, weights[l].rec, records[l], h_in, h_out, kcache[l], vcache[l], ws.t)
-            else:
-                vlc.vlc_layer_forward_timed(rec, weights[l].rec, records[l], h_in, h_out, kcache[l], vcache[l],
-                                            ws.t, events[l])
-            h_in = h_out
+        R.run_layers(rec, weights, plans if records is sel_recs else full, records, emb, hbuf, kcache, vcache, ws,
+                     events=events, chain=not args.no_chain)
 
     # ---- selective recompute: warmup, an untimed pass with every stage event (the stage table and
     # the choice of the dominant stage), then exactly `steps` timed steps in which only the dominant
@@ -320,6 +316,7 @@ def main() -> int:
     pairs = np.asarray([float(plans.host["kv_len"][l, :plans.n_rows[l]].astype(np.float64).sum()) for l in range(L)])
     stage_avg_us = stage_ms.mean(axis=(0, 1)) * 1e3
     stages = {}
+    n_chained = 0 if args.no_chain else sum(R.keeps_every_row(plans, l) for l in range(L))
     for i, name in enumerate(vlc.LAYER_STAGES):
         fl = np.mean([stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])[name][0] for l in range(L)])
         by = np.mean([stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])[name][1] for l in range(L)])
@@ -327,6 +324,9 @@ def main() -> int:
         stages[name] = {"avg_us": round(us, 2), "share": round(float(stage_avg_us[i] / stage_avg_us.sum()), 4)}
         if name == "rope_shift" and shift_all_us is not None:
             stages[name]["note"] = "empty: the reused keys of all layers are moved by one launch per step"
+        elif name == "rmsnorm1" and n_chained:
+            stages[name]["note"] = ("%d of %d layers find their input norm in the workspace: the layer above took it in "
+                                    "the kernel that sums its down projection (counted under down_gemm)" % (n_chained, L))
         elif fl > 0:
             stages[name]["tflops"] = round(fl / (us * 1e-6) / 1e12, 2)
         elif by > 0:

@@ -112,7 +112,7 @@ extern "C" int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t 
 static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weights* w,
                               const vlc_layer_plan* p, const void* h_in, void* h_out, void* k_cache,
                               void* v_cache, void* workspace, int64_t workspace_bytes, void* stream,
-                              void* const* ev) {
+                              void* const* ev, int xn_ready = 0, const void* next_w_ln1 = nullptr) {
   const char* who = "vlc_layer_forward";
   // optional stage timing: ev[i] is recorded before stage i, ev[VLC_LAYER_STAGES] after the last
 #define VLC_MARK(i)                                                                     \
@@ -173,9 +173,12 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
   const int64_t H = s.H, nqkv = (int64_t)(s.Hq + 2 * s.Hkv) * s.D, hqd = (int64_t)s.Hq * s.D, I = s.I;
 
   // x = h_in[map] is never materialised: the norm reads through the map, and so does the residual.
+  // (a chained call finds the normed rows in the workspace: the layer above wrote them with its last kernel)
   VLC_MARK(1);
-  rc = vlc::launch_rmsnorm(h_in, p->map, w->w_ln1, xn, n, s.H, s.eps, s.dtype, st);
-  if (rc) return rc;
+  if (!xn_ready) {
+    rc = vlc::launch_rmsnorm(h_in, p->map, w->w_ln1, xn, n, s.H, s.eps, s.dtype, st);
+    if (rc) return rc;
+  }
   VLC_MARK(2);
   int qkv_splits = 0;   // > 0: the projection is still split-K partials, summed by the next kernel
   rc = vlc::launch_gemm(xn, H, w->w_qkv, qkv32, nqkv, n, nqkv, H, vlc::EPI_BIAS_F32, w->b_qkv, nullptr, 0,
@@ -240,6 +243,10 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
     if (rc) return rc;
     rc = vlc::launch_moe_combine(h1, y, ms.wts, ms.pair_pos, n, K, s.H, h_out, s.dtype, st);
     if (rc) return rc;
+    if (next_w_ln1) {
+      rc = vlc::launch_rmsnorm(h_out, nullptr, next_w_ln1, xn, n, s.H, s.eps, s.dtype, st);
+      if (rc) return rc;
+    }
     VLC_MARK(9);
     return VLC_OK;
   }
@@ -247,9 +254,20 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
                         s.dtype, skw, ws.splitk_bytes, st);
   if (rc) return rc;
   VLC_MARK(8);
+  // Chained: the input norm of the layer below is taken here, where the rows of h_out are at hand - with a
+  // split k range in the kernel that sums the partials, so h_out is not read back and one launch goes.
+  int down_splits = 0;
   rc = vlc::launch_gemm(act, I, w->w_down, h_out, H, n, H, I, vlc::EPI_RESIDUAL, nullptr, h1, H, nullptr,
-                        s.dtype, skw, ws.splitk_bytes, st);
+                        s.dtype, skw, ws.splitk_bytes, st, next_w_ln1 ? &down_splits : nullptr);
   if (rc) return rc;
+  if (next_w_ln1) {
+    if (down_splits > 0)
+      rc = vlc::launch_sum_residual_rmsnorm(static_cast<const float*>(skw), down_splits, h1, nullptr, next_w_ln1,
+                                            h_out, xn, n, s.H, s.eps, st);
+    else
+      rc = vlc::launch_rmsnorm(h_out, nullptr, next_w_ln1, xn, n, s.H, s.eps, s.dtype, st);
+    if (rc) return rc;
+  }
   VLC_MARK(9);
   return VLC_OK;
 #undef VLC_MARK
@@ -269,6 +287,16 @@ extern "C" int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_l
   if (!stage_events) return fail(VLC_ERR_NULL, "vlc_layer_forward_timed: stage_events is NULL");
   return layer_forward_impl(shape, w, p, h_in, h_out, k_cache, v_cache, workspace, workspace_bytes, stream,
                             stage_events);
+}
+
+extern "C" int vlc_layer_forward_chained(const vlc_layer_shape* shape, const vlc_layer_weights* w,
+                                         const vlc_layer_plan* p, const void* h_in, void* h_out, void* k_cache,
+                                         void* v_cache, void* workspace, int64_t workspace_bytes, void* stream,
+                                         int input_norm_ready, const void* next_w_ln1, void* const* stage_events) {
+  if (input_norm_ready != 0 && input_norm_ready != 1)
+    return fail(VLC_ERR_SHAPE, "vlc_layer_forward_chained: input_norm_ready=%d (0 or 1)", input_norm_ready);
+  return layer_forward_impl(shape, w, p, h_in, h_out, k_cache, v_cache, workspace, workspace_bytes, stream,
+                            stage_events, input_norm_ready, next_w_ln1);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -151,6 +151,31 @@ def run_layer(shape_rec, weights: DeviceWeights, plan_rec, h_in, h_out, k_cache,
     B.vlc_layer_forward(shape_rec, weights.rec, plan_rec, h_in, h_out, k_cache, v_cache, ws.t, stream)
 
 
+def keeps_every_row(plans: DevicePlans, l: int) -> bool:
+    """True if layer l + 1 recomputes exactly the rows layer l did (its map is then 0..n-1: the planner's maps
+    are strictly increasing), so that layer l may leave the input norm of layer l + 1 behind."""
+    if l + 1 >= plans.L or plans.n_rows[l] == 0 or plans.n_rows[l + 1] != plans.n_rows[l]:
+        return False
+    n = plans.n_rows[l]
+    return bool(np.array_equal(plans.host["map"][l + 1, :n], np.arange(n, dtype=plans.host["map"].dtype)))
+
+
+def run_layers(shape_rec, weights: Sequence[DeviceWeights], plans: DevicePlans, records: Sequence, h0, hbuf,
+               k_cache, v_cache, ws: Workspace, stream=None, events=None, chain: bool = True):
+    """All layers in order through vlc_layer_forward_chained: a layer whose successor keeps every row hands it
+    the input norm (chain=False: every layer norms its own input).  h0 [n_in, H] is the first layer's input,
+    hbuf two [n_max, H] buffers the layers alternate between; events: per-layer stage-event arrays or None.
+    Returns the buffer that holds the last layer's output rows."""
+    h_in, ready = h0, False
+    for l in range(plans.L):
+        h_out = hbuf[l & 1]
+        nxt = weights[l + 1].t["w_ln1"] if chain and keeps_every_row(plans, l) else None
+        B.vlc_layer_forward_chained(shape_rec, weights[l].rec, records[l], h_in, h_out, k_cache[l], v_cache[l], ws.t,
+                                    ready, nxt, None if events is None else events[l], stream)
+        h_in, ready = h_out, nxt is not None
+    return h_in
+
+
 def plan_for(wl):
     """(k per layer | None, explicit leading-token count per layer | None) of a workload description,
     through the library's planner.  A mean-rate budget of bp basis points over L layers is

@@ -174,3 +174,78 @@ def test_layer_rows_that_leave_a_partial_round_of_gemm_tiles(shape, n_text, n_im
     assert_close(forced["n2"], r["n2"], sh.dtype, "n2")
     assert_close(forced["act"], r["act"], sh.dtype, "act (gate|up + SwiGLU)")
     assert_close(back(h_out[sel_t]), r["h2"], sh.dtype, "h_out (down-proj + residual)")
+
+
+def test_chained_layers_at_the_7b_shape():
+    """Three layers of the 7B-shaped single-image workload (596 recomputed rows in each: the down projection splits
+    its k range) through vlc_layer_forward_chained.  (1) Every layer's h_out and K/V equal, bit for bit, what
+    vlc_layer_forward gives layer by layer.  (2) After a layer that was given its successor's norm weight, every 13th
+    row of h_out and of the normed rows left in the workspace is compared with the oracle evaluated on the GPU's own
+    h1 and SwiGLU product of that layer."""
+    wl = syn.make_workload("c2")
+    sh = wl.shape
+    st = orc.STORE[sh.dtype]
+    dt = R.torch_dtype(sh.dtype)
+    rec = R.make_shape(sh)
+    L = 3
+    k, _ = plan_steps(wl)
+    plans = R.DevicePlans(wl.requests, L, k=k[:L])
+    n, total = plans.n_rows[0], wl.total_slots
+    assert plans.n_rows == [n] * L and R.keeps_every_row(plans, 0) and R.keeps_every_row(plans, 1)
+    assert not R.keeps_every_row(plans, 2)
+    Ws = [syn.layer_weights(sh, wl.seed, l) for l in range(L)]
+    dWs = [R.DeviceWeights(W, dt) for W in Ws]
+    pools = [[torch.from_numpy(a).to(DEV).to(dt) for a in syn.cached_kv(wl, l)] for l in range(L)]
+    emb = torch.from_numpy(syn.embedding_rows(wl)).to(DEV).to(dt)
+    ws = R.Workspace(rec, n)
+    recs = [plans.record(l, total if l == 0 else n, total, pools[l][0], pools[l][1]) for l in range(L)]
+
+    def caches():
+        return ([torch.zeros((total, sh.Hkv, sh.D), device=DEV, dtype=dt) for _ in range(L)],
+                [torch.zeros((total, sh.Hkv, sh.D), device=DEV, dtype=dt) for _ in range(L)])
+
+    # layer by layer, every layer norming its own input
+    kc0, vc0 = caches()
+    hs0, h_in = [], emb
+    for l in range(L):
+        h_out = torch.empty((n, sh.H), device=DEV, dtype=dt)
+        R.run_layer(rec, dWs[l], recs[l], h_in, h_out, kc0[l], vc0[l], ws)
+        hs0.append(h_out)
+        h_in = h_out
+    torch.cuda.synchronize()
+
+    # chained, stopping after layer 1 to look at what it left behind
+    kc1, vc1 = caches()
+    hs1 = [torch.empty((n, sh.H), device=DEV, dtype=dt) for _ in range(L)]
+    print("chained layer 0", flush=True)
+    vlc.vlc_layer_forward_chained(rec, dWs[0].rec, recs[0], emb, hs1[0], kc1[0], vc1[0], ws.t, False, dWs[1].t["w_ln1"])
+    print("chained layer 1", flush=True)
+    vlc.vlc_layer_forward_chained(rec, dWs[1].rec, recs[1], hs1[0], hs1[1], kc1[1], vc1[1], ws.t, True, dWs[2].t["w_ln1"])
+    torch.cuda.synchronize()
+    off = vlc.vlc_layer_workspace_layout(rec, n)
+    sel = np.unique(np.concatenate([np.arange(0, n, 13), [n - 1]]))
+    sel_t = torch.from_numpy(sel).to(DEV)
+
+    def ws_rows(name, cols):
+        return back(ws.t[off[name]:off[name] + n * cols * 2].view(dt).reshape(n, cols)[sel_t])
+
+    h1, act, xn_next = ws_rows("h1", sh.H), ws_rows("act", sh.I), ws_rows("xn", sh.H)
+    g_h = back(hs1[1][sel_t])
+    assert_close(g_h, st(h1 + orc.linear(act, st(Ws[1]["w_down"]))), sh.dtype, "h_out of a chained layer")
+    assert_close(xn_next, st(orc.rmsnorm(g_h, st(Ws[2]["w_ln1"]), sh.eps)), sh.dtype, "input norm left for the next layer")
+    print("chained layer 2", flush=True)
+    vlc.vlc_layer_forward_chained(rec, dWs[2].rec, recs[2], hs1[1], hs1[2], kc1[2], vc1[2], ws.t, True, None)
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert torch.equal(hs1[l], hs0[l]), "h_out of layer %d" % l
+        assert torch.equal(kc1[l], kc0[l]) and torch.equal(vc1[l], vc0[l]), "K/V of layer %d" % l
+
+    # the runner's loop over all layers, chained and not
+    kc2, vc2 = caches()
+    hbuf = [torch.empty((n, sh.H), device=DEV, dtype=dt) for _ in range(2)]
+    out = R.run_layers(rec, dWs, plans, recs, emb, hbuf, kc2, vc2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out[:n], hs0[L - 1]) and all(torch.equal(kc2[l], kc0[l]) for l in range(L))
+    out = R.run_layers(rec, dWs, plans, recs, emb, hbuf, kc2, vc2, ws, chain=False)
+    torch.cuda.synchronize()
+    assert torch.equal(out[:n], hs0[L - 1])

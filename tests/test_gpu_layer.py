@@ -40,11 +40,12 @@ def oracle_stack(wl, weights, emb, caches, k, explicit, layers, store=None):
 
 
 def run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher=None, all_rows=False, keep_ws=False,
-                  shift_ahead=False):
+                  shift_ahead=False, chain=False):
     """Runs `layers` layers on the GPU.  teacher: optional per-layer input rows (oracle outputs of the
     previous layer) to feed instead of the GPU's own previous output.  shift_ahead: the reused keys/values of all
     layers are placed by one vlc_rope_shift_kv_layers call before the first layer and the layers get no reuse
-    list.  Returns per-layer (h, K, V[, ws])."""
+    list.  chain: layers go through vlc_layer_forward_chained, and a layer whose successor keeps every row leaves
+    that layer's input norm in the workspace.  Returns per-layer (h, K, V[, ws])."""
     sh = wl.shape
     dt = R.torch_dtype(sh.dtype)
     rec = R.make_shape(sh)
@@ -64,8 +65,11 @@ def run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher=None, a
         jobs = R.ShiftJobs(plans, kps, vps, kcs, vcs)
         assert jobs.n_jobs == sum(1 for m in plans.n_reuse if m > 0)
         jobs.run(sh.rope_base)
+    assert not (chain and teacher is not None)
+    ready, chained = False, 0
+    dws = [R.DeviceWeights(weights[l], dt) for l in range(layers)]
     for l in range(layers):
-        W = R.DeviceWeights(weights[l], dt)
+        W = dws[l]
         kp, vp, kc, vc = kps[l], vps[l], kcs[l], vcs[l]
         if shift_ahead:
             kp = vp = None
@@ -75,13 +79,21 @@ def run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher=None, a
         h_out = torch.empty((n, sh.H), device=DEV, dtype=dt)
         prec = plans.record(l, n_prev, total, None if all_rows else kp, None if all_rows else vp)
         assert not shift_ahead or prec.n_reuse == 0
-        R.run_layer(rec, W, prec, h_prev, h_out, kc, vc, ws)
+        if chain:
+            nxt = dws[l + 1].t["w_ln1"] if R.keeps_every_row(plans, l) else None
+            vlc.vlc_layer_forward_chained(rec, W.rec, prec, h_prev, h_out, kc, vc, ws.t, ready, nxt)
+            ready = nxt is not None
+            chained += int(ready)
+        else:
+            R.run_layer(rec, W, prec, h_prev, h_out, kc, vc, ws)
         torch.cuda.synchronize()
         item = [back(h_out), back(kc), back(vc)]
         if keep_ws:
             item.append(read_workspace(sh, rec, ws, n))
         out.append(item)
         h_prev, n_prev = h_out, n
+    if chain:
+        plans.chained = chained
     return out, plans
 
 
@@ -100,7 +112,7 @@ def read_workspace(sh, rec, ws, n):
     return res
 
 
-def check_against_oracle(wl, layers, teacher_forced, all_rows=False, shift_ahead=False):
+def check_against_oracle(wl, layers, teacher_forced, all_rows=False, shift_ahead=False, chain=False):
     sh = wl.shape
     k, explicit = plan_steps(wl)
     if all_rows:
@@ -112,7 +124,10 @@ def check_against_oracle(wl, layers, teacher_forced, all_rows=False, shift_ahead
     teacher = None
     if teacher_forced:
         teacher = [np.concatenate([ref[r][l]["h"] for r in range(len(wl.requests))]) for l in range(layers)]
-    got, plans = run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher, all_rows, shift_ahead=shift_ahead)
+    got, plans = run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher, all_rows, shift_ahead=shift_ahead,
+                               chain=chain)
+    if chain:
+        check_against_oracle.chained = plans.chained
     worst = 0.0
     for l in range(layers):
         want_h = np.concatenate([ref[r][l]["h"] for r in range(len(wl.requests))])
@@ -242,6 +257,29 @@ def test_reused_keys_of_all_layers_placed_ahead_of_the_layer_loop():
     k, _ = plan_steps(wl)
     assert len(set(k.tolist())) > 1
     check_against_oracle(wl, layers=sh.L, teacher_forced=False, shift_ahead=True)
+
+
+def test_chained_layers_small_shapes():
+    """vlc_layer_forward_chained over whole stacks against the oracle: the fp32 and bf16 tiny stacks and the packed
+    pair with a uniform rate (every layer hands its successor the input norm), full recompute, and rates that fall
+    with depth (only runs of equal rates chain; a layer whose successor drops rows norms for itself)."""
+    for name in ("c1", "c1_bf16", "c1_q3"):
+        check_against_oracle(syn.make_workload(name), layers=2, teacher_forced=False, chain=True)
+        assert check_against_oracle.chained == 1
+    check_against_oracle(syn.make_workload("c1"), layers=2, teacher_forced=False, all_rows=True, chain=True)
+    assert check_against_oracle.chained == 1
+    sh = syn.SHAPES["tiny_bias"]
+    r0 = syn.Request([syn.Segment(0, 20, False), syn.Segment(20, 100, True, 3, 0), syn.Segment(120, 9, False)], 0)
+    r1 = syn.Request([syn.Segment(0, 7, False), syn.Segment(7, 60, True, 50, 100), syn.Segment(67, 40, True, 0, 160),
+                      syn.Segment(107, 5, False)], 129, pos_start=11)
+    check_against_oracle(syn.Workload("two", sh, [r0, r1], 200, "static", static_k=40, seed=12), layers=2,
+                         teacher_forced=False, shift_ahead=True, chain=True)
+    assert check_against_oracle.chained == 1
+    wl = syn.Workload("falling", sh, [r0, r1], 200, "dynamic", budget_bp=2000, seed=13)
+    k, _ = plan_steps(wl)
+    assert k[0] != k[1]
+    check_against_oracle(wl, layers=sh.L, teacher_forced=False, chain=True)
+    assert check_against_oracle.chained == 0
 
 
 def test_7b_shape_layer_stage_by_stage():

@@ -94,6 +94,8 @@ def check_moe_layer(wl, layer=0):
 def test_moe_tiny_fp32_stack_end_to_end():
     """2-layer fp32 decoder with 8 experts, 2 per token: every output against the free-running oracle."""
     check_against_oracle(syn.make_workload("c1_moe"), layers=2, teacher_forced=False)
+    check_against_oracle(syn.make_workload("c1_moe"), layers=2, teacher_forced=False, chain=True)
+    assert check_against_oracle.chained == 1
 
 
 @pytest.mark.parametrize("name", ["c1_moe", "c1_moe_bf16"])
