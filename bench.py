@@ -148,8 +148,8 @@ def main() -> int:
                     help="re-rotate the reused keys inside every layer call instead of in one launch for all "
                          "layers ahead of the layer loop")
     ap.add_argument("--no-chain", action="store_true",
-                    help="every layer takes its own input norm (default: a layer whose successor recomputes the "
-                         "same rows leaves that norm behind, vlc_layer_forward_chained)")
+                    help="every layer takes its own input norm (default: each layer leaves the norm of the rows its "
+                         "successor recomputes behind, vlc_layer_forward_chained)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain row copy of 1 GiB through vlc_gather_rows "
                          "(identity index) so a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -316,7 +316,7 @@ def main() -> int:
     pairs = np.asarray([float(plans.host["kv_len"][l, :plans.n_rows[l]].astype(np.float64).sum()) for l in range(L)])
     stage_avg_us = stage_ms.mean(axis=(0, 1)) * 1e3
     stages = {}
-    n_chained = 0 if args.no_chain else sum(R.keeps_every_row(plans, l) for l in range(L))
+    n_chained = 0 if args.no_chain else sum(R.chain_link(plans, l)[0] for l in range(L))
     for i, name in enumerate(vlc.LAYER_STAGES):
         fl = np.mean([stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])[name][0] for l in range(L)])
         by = np.mean([stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])[name][1] for l in range(L)])

@@ -329,16 +329,19 @@ int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_layer_weight
                             void* const* stage_events);
 
 /*
- * vlc_layer_forward for a run of layers that recompute the same rows (equal rates in Algorithm 1's
- * allocation, or a uniform rate): the input RMSNorm of the layer below is produced by this layer's last
- * kernel - the one that sums the down projection's partial products when its k range is split - instead
- * of a kernel of its own at the head of the next call.  Results equal vlc_layer_forward's (h_out bit for
- * bit; the normed rows to the rounding of one float sum taken in another order).
+ * vlc_layer_forward for consecutive layers of one prefill (Algorithm 1's allocation makes the rows of a
+ * layer a subset of those of the layer above): the input RMSNorm of the layer below is produced by this
+ * layer's last kernel - the one that sums the down projection's partial products when its k range is
+ * split - instead of a kernel of its own at the head of the next call.  Results equal vlc_layer_forward's
+ * bit for bit.
  *   next_w_ln1 (device [H], or NULL): input-norm weight of the layer below.  Non-NULL: after h_out, the
- *     rows RMSNorm(h_out) * next_w_ln1 are left in the workspace (its first field, see
- *     vlc_layer_workspace_layout).  The caller may pass it only if the layer below keeps every row of this
- *     one - its plan has n_in == n == this plan's n and map[i] == i - and runs next on the same
- *     workspace and stream with input_norm_ready = 1.
+ *     rows RMSNorm(h_out) * next_w_ln1 that the layer below recomputes are left in the workspace (its first
+ *     field, see vlc_layer_workspace_layout), in that layer's row order.  The layer below must run next on
+ *     the same workspace and stream, with a plan whose n_in equals this plan's n, and input_norm_ready = 1.
+ *   next_row (device [n] int32, or NULL; read only with next_w_ln1): for every row of this layer its index
+ *     among the rows of the layer below, negative if that layer drops it - the inverse of that layer's
+ *     `map`: next_row[map_below[j]] == j for all j < n_below.  NULL: the layer below keeps every row
+ *     (n_below == n, map_below[i] == i).
  *   input_norm_ready (0 or 1): 1 = the workspace already holds this layer's input-normed rows, left by the
  *     call for the layer above as described; h_in is then read only for the residual.
  *   stage_events: NULL, or as in vlc_layer_forward_timed (stage 1 is empty when input_norm_ready is 1,
@@ -349,7 +352,8 @@ int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_layer_weight
 int vlc_layer_forward_chained(const vlc_layer_shape* shape, const vlc_layer_weights* weights,
                               const vlc_layer_plan* plan, const void* h_in, void* h_out, void* k_cache,
                               void* v_cache, void* workspace, int64_t workspace_bytes, void* stream,
-                              int input_norm_ready, const void* next_w_ln1, void* const* stage_events);
+                              int input_norm_ready, const void* next_w_ln1, const int32_t* next_row,
+                              void* const* stage_events);
 
 /*
  * First output token of each request - where the paper's time-to-first-token ends (Sec. 5.1; Tables

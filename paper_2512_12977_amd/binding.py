@@ -81,7 +81,7 @@ def lib():
         L.vlc_mean_squared_error.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.vlc_layer_forward.argtypes = [C.c_void_p] * 8 + [C.c_int64, C.c_void_p]
         L.vlc_layer_forward_timed.argtypes = [C.c_void_p] * 8 + [C.c_int64, C.c_void_p, C.c_void_p]
-        L.vlc_layer_forward_chained.argtypes = [C.c_void_p] * 8 + [C.c_int64, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        L.vlc_layer_forward_chained.argtypes = [C.c_void_p] * 8 + [C.c_int64, C.c_void_p, C.c_int] + [C.c_void_p] * 3
         L.vlc_first_token_workspace_bytes.restype = C.c_int64
         L.vlc_first_token_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int]
         L.vlc_first_token.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int64, C.c_float] + \
@@ -282,15 +282,19 @@ def vlc_layer_forward_timed(shape: LayerShape, weights: LayerWeights, plan: Laye
 
 
 def vlc_layer_forward_chained(shape: LayerShape, weights: LayerWeights, plan: LayerPlan, h_in, h_out, k_cache,
-                              v_cache, workspace, input_norm_ready: bool, next_w_ln1=None, stage_events=None,
-                              stream=None) -> None:
-    """next_w_ln1: the input-norm weight of the layer below (device tensor) when that layer keeps every row of
-    this one, else None; input_norm_ready: the previous call on this workspace was given this layer's weight."""
+                              v_cache, workspace, input_norm_ready: bool, next_w_ln1=None, next_row=None,
+                              stage_events=None, stream=None) -> None:
+    """next_w_ln1: the input-norm weight of the layer below (device tensor) or None; next_row: int32 [n], the index
+    of each row among the rows of the layer below (negative: dropped), None if that layer keeps every row;
+    input_norm_ready: the previous call on this workspace was given this layer's weight."""
+    if next_row is not None and (next_row.element_size() != 4 or next_row.numel() != plan.n):
+        raise ValueError("next_row: int32 tensor with one entry per recomputed row")
     _check(lib().vlc_layer_forward_chained(C.addressof(shape), C.addressof(weights), C.addressof(plan),
                                            _dev(h_in), _dev(h_out), _dev(k_cache), _dev(v_cache), _dev(workspace),
                                            workspace.numel() * workspace.element_size(), _stream(stream),
                                            1 if input_norm_ready else 0,
                                            None if next_w_ln1 is None else _dev(next_w_ln1),
+                                           None if next_row is None else _dev(next_row),
                                            None if stage_events is None else C.addressof(stage_events)))
 
 

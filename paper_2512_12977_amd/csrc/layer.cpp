@@ -112,7 +112,8 @@ extern "C" int vlc_layer_workspace_layout(const vlc_layer_shape* shape, int64_t 
 static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weights* w,
                               const vlc_layer_plan* p, const void* h_in, void* h_out, void* k_cache,
                               void* v_cache, void* workspace, int64_t workspace_bytes, void* stream,
-                              void* const* ev, int xn_ready = 0, const void* next_w_ln1 = nullptr) {
+                              void* const* ev, int xn_ready = 0, const void* next_w_ln1 = nullptr,
+                              const int32_t* next_row = nullptr) {
   const char* who = "vlc_layer_forward";
   // optional stage timing: ev[i] is recorded before stage i, ev[VLC_LAYER_STAGES] after the last
 #define VLC_MARK(i)                                                                     \
@@ -244,7 +245,7 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
     rc = vlc::launch_moe_combine(h1, y, ms.wts, ms.pair_pos, n, K, s.H, h_out, s.dtype, st);
     if (rc) return rc;
     if (next_w_ln1) {
-      rc = vlc::launch_rmsnorm(h_out, nullptr, next_w_ln1, xn, n, s.H, s.eps, s.dtype, st);
+      rc = vlc::launch_rmsnorm(h_out, nullptr, next_w_ln1, xn, n, s.H, s.eps, s.dtype, st, next_row);
       if (rc) return rc;
     }
     VLC_MARK(9);
@@ -263,9 +264,9 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
   if (next_w_ln1) {
     if (down_splits > 0)
       rc = vlc::launch_sum_residual_rmsnorm(static_cast<const float*>(skw), down_splits, h1, nullptr, next_w_ln1,
-                                            h_out, xn, n, s.H, s.eps, st);
+                                            h_out, xn, n, s.H, s.eps, st, next_row);
     else
-      rc = vlc::launch_rmsnorm(h_out, nullptr, next_w_ln1, xn, n, s.H, s.eps, s.dtype, st);
+      rc = vlc::launch_rmsnorm(h_out, nullptr, next_w_ln1, xn, n, s.H, s.eps, s.dtype, st, next_row);
     if (rc) return rc;
   }
   VLC_MARK(9);
@@ -292,11 +293,12 @@ extern "C" int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_l
 extern "C" int vlc_layer_forward_chained(const vlc_layer_shape* shape, const vlc_layer_weights* w,
                                          const vlc_layer_plan* p, const void* h_in, void* h_out, void* k_cache,
                                          void* v_cache, void* workspace, int64_t workspace_bytes, void* stream,
-                                         int input_norm_ready, const void* next_w_ln1, void* const* stage_events) {
+                                         int input_norm_ready, const void* next_w_ln1, const int32_t* next_row,
+                                         void* const* stage_events) {
   if (input_norm_ready != 0 && input_norm_ready != 1)
     return fail(VLC_ERR_SHAPE, "vlc_layer_forward_chained: input_norm_ready=%d (0 or 1)", input_norm_ready);
   return layer_forward_impl(shape, w, p, h_in, h_out, k_cache, v_cache, workspace, workspace_bytes, stream,
-                            stage_events, input_norm_ready, next_w_ln1);
+                            stage_events, input_norm_ready, next_w_ln1, next_w_ln1 ? next_row : nullptr);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -337,16 +337,19 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// RMSNorm with optional row gather: y[i] = x[map[i]] * rsqrt(mean(x^2) + eps) * w
+// RMSNorm with optional row gather: y[i] = x[map[i]] * rsqrt(mean(x^2) + eps) * w.  With a destination list
+// the result of row i goes to y[ymap[i]], and a row whose entry is negative is skipped.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int MAXC>
 __global__ __launch_bounds__(kThreads) void rmsnorm_kernel(const uint4* __restrict__ x,
                                                            const int32_t* __restrict__ map,
                                                            const uint4* __restrict__ w,
                                                            uint4* __restrict__ y, int chunks, float inv_h,
-                                                           float eps) {
+                                                           float eps, const int32_t* __restrict__ ymap) {
   constexpr int VEC = Chunk<T>::VEC;
   const int64_t row = blockIdx.x;
+  const int64_t yrow = ymap ? (int64_t)ymap[row] : row;
+  if (yrow < 0) return;                    // the same for the whole workgroup
   const int64_t srow = map ? (int64_t)map[row] : row;
   const uint4* xr = x + srow * chunks;
   float v[MAXC][VEC];
@@ -377,7 +380,7 @@ __global__ __launch_bounds__(kThreads) void rmsnorm_kernel(const uint4* __restri
       Chunk<T>::unpack(w[c], wv);
 #pragma unroll
       for (int i = 0; i < VEC; ++i) o[i] = v[j][i] * r * wv[i];
-      y[row * chunks + c] = Chunk<T>::pack(o);
+      y[yrow * chunks + c] = Chunk<T>::pack(o);
     }
   }
 }
@@ -389,10 +392,11 @@ template <int MAXC>
 __global__ __launch_bounds__(kThreads) void sum_residual_rmsnorm_kernel(
     const float* __restrict__ part, int splits, int64_t split_stride, const uint4* __restrict__ resid,
     const int32_t* __restrict__ rmap, const uint4* __restrict__ w, uint4* __restrict__ h,
-    uint4* __restrict__ y, int chunks, float inv_h, float eps) {
+    uint4* __restrict__ y, int chunks, float inv_h, float eps, const int32_t* __restrict__ ymap) {
   using CB = Chunk<uint16_t>;
   const int64_t row = blockIdx.x;
   const int64_t rrow = rmap ? (int64_t)rmap[row] : row;
+  const int64_t yrow = ymap ? (int64_t)ymap[row] : row;    // < 0: h is written, the norm is not wanted
   float v[MAXC][8];
   float ss = 0.f;
 #pragma unroll
@@ -425,6 +429,7 @@ __global__ __launch_bounds__(kThreads) void sum_residual_rmsnorm_kernel(
       for (int i = 0; i < 8; ++i) ss += v[j][i] * v[j][i];
     }
   }
+  if (yrow < 0) return;                    // the same for the whole workgroup
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
   __shared__ float red[kThreads / 64];
@@ -442,7 +447,7 @@ __global__ __launch_bounds__(kThreads) void sum_residual_rmsnorm_kernel(
       CB::unpack(w[c], wv);
 #pragma unroll
       for (int i = 0; i < 8; ++i) o[i] = v[j][i] * r * wv[i];
-      y[row * chunks + c] = CB::pack(o);
+      y[yrow * chunks + c] = CB::pack(o);
     }
   }
 }
@@ -665,7 +670,7 @@ int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t
 }
 
 int launch_rmsnorm(const void* x, const int32_t* map, const void* w, void* y, int64_t n, int H,
-                   float eps, int dtype, hipStream_t st) {
+                   float eps, int dtype, hipStream_t st, const int32_t* ymap) {
   if (n <= 0) return VLC_OK;
   const int vec = dtype == VLC_BF16 ? 8 : 4;
   if (H % vec) return fail(VLC_ERR_SHAPE, "rmsnorm: H=%d not a multiple of %d", H, vec);
@@ -674,7 +679,7 @@ int launch_rmsnorm(const void* x, const int32_t* map, const void* w, void* y, in
   const float inv_h = 1.0f / (float)H;
 #define VLC_LAUNCH_RMS(T, MAXC)                                                                       \
   hipLaunchKernelGGL((rmsnorm_kernel<T, MAXC>), grid, dim3(kThreads), 0, st, (const uint4*)x, map,    \
-                     (const uint4*)w, (uint4*)y, chunks, inv_h, eps)
+                     (const uint4*)w, (uint4*)y, chunks, inv_h, eps, ymap)
   if (chunks <= kThreads * 2) {
     if (dtype == VLC_BF16) VLC_LAUNCH_RMS(uint16_t, 2); else VLC_LAUNCH_RMS(float, 2);
   } else if (chunks <= kThreads * 4) {
@@ -691,7 +696,7 @@ int launch_rmsnorm(const void* x, const int32_t* map, const void* w, void* y, in
 
 int launch_sum_residual_rmsnorm(const float* partials, int splits, const void* resid, const int32_t* rmap,
                                 const void* w, void* h, void* y, int64_t n, int H, float eps,
-                                hipStream_t st) {
+                                hipStream_t st, const int32_t* ymap) {
   if (n <= 0) return VLC_OK;
   if (H % 8) return fail(VLC_ERR_SHAPE, "sum+residual+rmsnorm: H=%d not a multiple of 8", H);
   if (splits < 1 || splits > kMaxSplits) return fail(VLC_ERR_SHAPE, "sum+residual+rmsnorm: %d splits", splits);
@@ -702,7 +707,7 @@ int launch_sum_residual_rmsnorm(const float* partials, int splits, const void* r
 #define VLC_LAUNCH_SRN(MAXC)                                                                          \
   hipLaunchKernelGGL((sum_residual_rmsnorm_kernel<MAXC>), grid, dim3(kThreads), 0, st, partials,      \
                      splits, split_stride, (const uint4*)resid, rmap, (const uint4*)w, (uint4*)h,     \
-                     (uint4*)y, chunks, inv_h, eps)
+                     (uint4*)y, chunks, inv_h, eps, ymap)
   if (chunks <= kThreads * 2) VLC_LAUNCH_SRN(2);
   else if (chunks <= kThreads * 4) VLC_LAUNCH_SRN(4);
   else if (chunks <= kThreads * 8) VLC_LAUNCH_SRN(8);

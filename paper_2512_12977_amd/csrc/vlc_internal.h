@@ -43,15 +43,16 @@ RopeFreq make_rope_freq(double base, int D, int mrope_h = 0, int mrope_w = 0);
 int launch_gather_rows(const void* src, int64_t row_bytes, const int32_t* idx, int64_t n, void* dst,
                        hipStream_t st);
 
-// y[i,:] = rmsnorm(x[map ? map[i] : i, :]) * w
+// y[ymap ? ymap[i] : i, :] = rmsnorm(x[map ? map[i] : i, :]) * w; rows with ymap[i] < 0 are skipped
 int launch_rmsnorm(const void* x, const int32_t* map, const void* w, void* y, int64_t n, int H,
-                   float eps, int dtype, hipStream_t st);
+                   float eps, int dtype, hipStream_t st, const int32_t* ymap = nullptr);
 
 // bf16 path, after a GEMM that left `splits` float partial matrices [splits][n][H]:
-// h = round(sum of partials + resid[rmap ? rmap[i] : i]) (stored), y = RMSNorm(h) * w.
+// h = round(sum of partials + resid[rmap ? rmap[i] : i]) (stored), y[ymap ? ymap[i] : i] = RMSNorm(h) * w
+// (no norm for rows with ymap[i] < 0).
 int launch_sum_residual_rmsnorm(const float* partials, int splits, const void* resid, const int32_t* rmap,
                                 const void* w, void* h, void* y, int64_t n, int H, float eps,
-                                hipStream_t st);
+                                hipStream_t st, const int32_t* ymap = nullptr);
 
 // out[r, v] = x[r, :] . W[v, :] for m <= 8 rows (bf16 x [m, H] and W [V, H], float out [m, V]); reads W once
 int launch_rows_times_matrix_bf16(const void* x, const void* W, float* out, int64_t m, int64_t V, int H,

@@ -153,26 +153,46 @@ def run_layer(shape_rec, weights: DeviceWeights, plan_rec, h_in, h_out, k_cache,
 
 def keeps_every_row(plans: DevicePlans, l: int) -> bool:
     """True if layer l + 1 recomputes exactly the rows layer l did (its map is then 0..n-1: the planner's maps
-    are strictly increasing), so that layer l may leave the input norm of layer l + 1 behind."""
-    if l + 1 >= plans.L or plans.n_rows[l] == 0 or plans.n_rows[l + 1] != plans.n_rows[l]:
+    are strictly increasing)."""
+    if l + 1 >= plans.L or plans.n_rows[l + 1] != plans.n_rows[l]:
         return False
     n = plans.n_rows[l]
     return bool(np.array_equal(plans.host["map"][l + 1, :n], np.arange(n, dtype=plans.host["map"].dtype)))
 
 
+def chain_link(plans: DevicePlans, l: int):
+    """How layer l can hand the input norm to layer l + 1: (False, None) if it cannot (last layer, or one of the
+    two has no rows), else (True, next_row) with next_row None if layer l + 1 keeps every row, else the int32
+    device list that gives each row of layer l its index among the rows of layer l + 1 (-1: dropped) - the
+    inverse of layer l + 1's map.  Built once per plan and kept."""
+    links = plans.__dict__.setdefault("_links", {})
+    if l not in links:
+        if l + 1 >= plans.L or plans.n_rows[l] == 0 or plans.n_rows[l + 1] == 0:
+            links[l] = (False, None)
+        elif keeps_every_row(plans, l):
+            links[l] = (True, None)
+        else:
+            n, m = plans.n_rows[l], plans.n_rows[l + 1]
+            inv = np.full(n, -1, dtype=np.int32)
+            inv[plans.host["map"][l + 1, :m]] = np.arange(m, dtype=np.int32)
+            links[l] = (True, torch.from_numpy(inv).to(plans.dev[l]["slot"].device))
+    return links[l]
+
+
 def run_layers(shape_rec, weights: Sequence[DeviceWeights], plans: DevicePlans, records: Sequence, h0, hbuf,
                k_cache, v_cache, ws: Workspace, stream=None, events=None, chain: bool = True):
-    """All layers in order through vlc_layer_forward_chained: a layer whose successor keeps every row hands it
-    the input norm (chain=False: every layer norms its own input).  h0 [n_in, H] is the first layer's input,
-    hbuf two [n_max, H] buffers the layers alternate between; events: per-layer stage-event arrays or None.
+    """All layers in order through vlc_layer_forward_chained: every layer hands its successor the input norm
+    (chain=False: every layer norms its own input).  h0 [n_in, H] is the first layer's input, hbuf two
+    [n_max, H] buffers the layers alternate between; events: per-layer stage-event arrays or None.
     Returns the buffer that holds the last layer's output rows."""
     h_in, ready = h0, False
     for l in range(plans.L):
         h_out = hbuf[l & 1]
-        nxt = weights[l + 1].t["w_ln1"] if chain and keeps_every_row(plans, l) else None
+        linked, next_row = chain_link(plans, l) if chain else (False, None)
         B.vlc_layer_forward_chained(shape_rec, weights[l].rec, records[l], h_in, h_out, k_cache[l], v_cache[l], ws.t,
-                                    ready, nxt, None if events is None else events[l], stream)
-        h_in, ready = h_out, nxt is not None
+                                    ready, weights[l + 1].t["w_ln1"] if linked else None, next_row,
+                                    None if events is None else events[l], stream)
+        h_in, ready = h_out, linked
     return h_in
 
 

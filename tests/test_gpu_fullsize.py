@@ -176,13 +176,15 @@ def test_layer_rows_that_leave_a_partial_round_of_gemm_tiles(shape, n_text, n_im
     assert_close(back(h_out[sel_t]), r["h2"], sh.dtype, "h_out (down-proj + residual)")
 
 
-def test_chained_layers_at_the_7b_shape():
-    """Three layers of the 7B-shaped single-image workload (596 recomputed rows in each: the down projection splits
-    its k range) through vlc_layer_forward_chained.  (1) Every layer's h_out and K/V equal, bit for bit, what
-    vlc_layer_forward gives layer by layer.  (2) After a layer that was given its successor's norm weight, every 13th
-    row of h_out and of the normed rows left in the workspace is compared with the oracle evaluated on the GPU's own
-    h1 and SwiGLU product of that layer."""
-    wl = syn.make_workload("c2")
+@pytest.mark.parametrize("name", ["c2", "c3"])
+def test_chained_layers_at_the_7b_shape(name):
+    """Three layers of a 7B-shaped workload through vlc_layer_forward_chained (the down projection splits its k
+    range, so the fused sum + residual + norm kernel runs).  c2: 596 recomputed rows in every layer.  c3: 1020, 1012
+    and 1000 rows - each layer drops rows of the one above, and the norm is written through the row list.
+    (1) Every layer's h_out and K/V equal, bit for bit, what vlc_layer_forward gives layer by layer.  (2) After a
+    layer that was given its successor's norm weight, every 13th row of h_out and every 13th of the normed rows left
+    in the workspace are compared with the oracle evaluated on the GPU's own h1 and SwiGLU product of that layer."""
+    wl = syn.make_workload(name)
     sh = wl.shape
     st = orc.STORE[sh.dtype]
     dt = R.torch_dtype(sh.dtype)
@@ -190,15 +192,20 @@ def test_chained_layers_at_the_7b_shape():
     L = 3
     k, _ = plan_steps(wl)
     plans = R.DevicePlans(wl.requests, L, k=k[:L])
-    n, total = plans.n_rows[0], wl.total_slots
-    assert plans.n_rows == [n] * L and R.keeps_every_row(plans, 0) and R.keeps_every_row(plans, 1)
-    assert not R.keeps_every_row(plans, 2)
+    ns, total = plans.n_rows, wl.total_slots
+    links = [R.chain_link(plans, l) for l in range(L)]
+    assert [a for a, _ in links] == [True, True, False]
+    if name == "c2":
+        assert ns == [596] * 3 and links[0][1] is None and links[1][1] is None
+    else:
+        assert ns[0] > ns[1] > ns[2] and links[0][1] is not None and links[1][1] is not None
+        assert int((links[1][1] >= 0).sum().item()) == ns[2]
     Ws = [syn.layer_weights(sh, wl.seed, l) for l in range(L)]
     dWs = [R.DeviceWeights(W, dt) for W in Ws]
     pools = [[torch.from_numpy(a).to(DEV).to(dt) for a in syn.cached_kv(wl, l)] for l in range(L)]
     emb = torch.from_numpy(syn.embedding_rows(wl)).to(DEV).to(dt)
-    ws = R.Workspace(rec, n)
-    recs = [plans.record(l, total if l == 0 else n, total, pools[l][0], pools[l][1]) for l in range(L)]
+    ws = R.Workspace(rec, max(ns))
+    recs = [plans.record(l, total if l == 0 else ns[l - 1], total, pools[l][0], pools[l][1]) for l in range(L)]
 
     def caches():
         return ([torch.zeros((total, sh.Hkv, sh.D), device=DEV, dtype=dt) for _ in range(L)],
@@ -208,7 +215,7 @@ def test_chained_layers_at_the_7b_shape():
     kc0, vc0 = caches()
     hs0, h_in = [], emb
     for l in range(L):
-        h_out = torch.empty((n, sh.H), device=DEV, dtype=dt)
+        h_out = torch.empty((ns[l], sh.H), device=DEV, dtype=dt)
         R.run_layer(rec, dWs[l], recs[l], h_in, h_out, kc0[l], vc0[l], ws)
         hs0.append(h_out)
         h_in = h_out
@@ -216,23 +223,29 @@ def test_chained_layers_at_the_7b_shape():
 
     # chained, stopping after layer 1 to look at what it left behind
     kc1, vc1 = caches()
-    hs1 = [torch.empty((n, sh.H), device=DEV, dtype=dt) for _ in range(L)]
+    hs1 = [torch.empty((ns[l], sh.H), device=DEV, dtype=dt) for l in range(L)]
     print("chained layer 0", flush=True)
-    vlc.vlc_layer_forward_chained(rec, dWs[0].rec, recs[0], emb, hs1[0], kc1[0], vc1[0], ws.t, False, dWs[1].t["w_ln1"])
+    vlc.vlc_layer_forward_chained(rec, dWs[0].rec, recs[0], emb, hs1[0], kc1[0], vc1[0], ws.t, False,
+                                  dWs[1].t["w_ln1"], links[0][1])
     print("chained layer 1", flush=True)
-    vlc.vlc_layer_forward_chained(rec, dWs[1].rec, recs[1], hs1[0], hs1[1], kc1[1], vc1[1], ws.t, True, dWs[2].t["w_ln1"])
+    vlc.vlc_layer_forward_chained(rec, dWs[1].rec, recs[1], hs1[0], hs1[1], kc1[1], vc1[1], ws.t, True,
+                                  dWs[2].t["w_ln1"], links[1][1])
     torch.cuda.synchronize()
+    n, m = ns[1], ns[2]
     off = vlc.vlc_layer_workspace_layout(rec, n)
     sel = np.unique(np.concatenate([np.arange(0, n, 13), [n - 1]]))
-    sel_t = torch.from_numpy(sel).to(DEV)
 
-    def ws_rows(name, cols):
-        return back(ws.t[off[name]:off[name] + n * cols * 2].view(dt).reshape(n, cols)[sel_t])
+    def ws_rows(field, rows, idx, cols):
+        return back(ws.t[off[field]:off[field] + rows * cols * 2].view(dt).reshape(rows, cols)[torch.from_numpy(idx).to(DEV)])
 
-    h1, act, xn_next = ws_rows("h1", sh.H), ws_rows("act", sh.I), ws_rows("xn", sh.H)
-    g_h = back(hs1[1][sel_t])
-    assert_close(g_h, st(h1 + orc.linear(act, st(Ws[1]["w_down"]))), sh.dtype, "h_out of a chained layer")
-    assert_close(xn_next, st(orc.rmsnorm(g_h, st(Ws[2]["w_ln1"]), sh.eps)), sh.dtype, "input norm left for the next layer")
+    h1, act = ws_rows("h1", n, sel, sh.H), ws_rows("act", n, sel, sh.I)
+    assert_close(back(hs1[1][torch.from_numpy(sel).to(DEV)]), st(h1 + orc.linear(act, st(Ws[1]["w_down"]))), sh.dtype,
+                 "h_out of a chained layer")
+    sel2 = np.unique(np.concatenate([np.arange(0, m, 13), [m - 1]]))
+    src = plans.host["map"][2, :m].astype(np.int64)[sel2]          # the rows of layer 1 they come from
+    xn_next = ws_rows("xn", m, sel2, sh.H)
+    assert_close(xn_next, st(orc.rmsnorm(back(hs1[1][torch.from_numpy(src).to(DEV)]), st(Ws[2]["w_ln1"]), sh.eps)),
+                 sh.dtype, "input norm left for the next layer")
     print("chained layer 2", flush=True)
     vlc.vlc_layer_forward_chained(rec, dWs[2].rec, recs[2], hs1[1], hs1[2], kc1[2], vc1[2], ws.t, True, None)
     torch.cuda.synchronize()
@@ -242,10 +255,10 @@ def test_chained_layers_at_the_7b_shape():
 
     # the runner's loop over all layers, chained and not
     kc2, vc2 = caches()
-    hbuf = [torch.empty((n, sh.H), device=DEV, dtype=dt) for _ in range(2)]
+    hbuf = [torch.empty((max(ns), sh.H), device=DEV, dtype=dt) for _ in range(2)]
     out = R.run_layers(rec, dWs, plans, recs, emb, hbuf, kc2, vc2, ws)
     torch.cuda.synchronize()
-    assert torch.equal(out[:n], hs0[L - 1]) and all(torch.equal(kc2[l], kc0[l]) for l in range(L))
+    assert torch.equal(out[:ns[-1]], hs0[L - 1]) and all(torch.equal(kc2[l], kc0[l]) for l in range(L))
     out = R.run_layers(rec, dWs, plans, recs, emb, hbuf, kc2, vc2, ws, chain=False)
     torch.cuda.synchronize()
-    assert torch.equal(out[:n], hs0[L - 1])
+    assert torch.equal(out[:ns[-1]], hs0[L - 1])

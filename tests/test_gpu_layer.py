@@ -44,8 +44,8 @@ def run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher=None, a
     """Runs `layers` layers on the GPU.  teacher: optional per-layer input rows (oracle outputs of the
     previous layer) to feed instead of the GPU's own previous output.  shift_ahead: the reused keys/values of all
     layers are placed by one vlc_rope_shift_kv_layers call before the first layer and the layers get no reuse
-    list.  chain: layers go through vlc_layer_forward_chained, and a layer whose successor keeps every row leaves
-    that layer's input norm in the workspace.  Returns per-layer (h, K, V[, ws])."""
+    list.  chain: layers go through vlc_layer_forward_chained, every layer leaving its successor's input norm in
+    the workspace (plans.chained counts 1 per link and 10 more per link that drops rows).  Returns per-layer (h, K, V[, ws])."""
     sh = wl.shape
     dt = R.torch_dtype(sh.dtype)
     rec = R.make_shape(sh)
@@ -80,10 +80,11 @@ def run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, teacher=None, a
         prec = plans.record(l, n_prev, total, None if all_rows else kp, None if all_rows else vp)
         assert not shift_ahead or prec.n_reuse == 0
         if chain:
-            nxt = dws[l + 1].t["w_ln1"] if R.keeps_every_row(plans, l) else None
-            vlc.vlc_layer_forward_chained(rec, W.rec, prec, h_prev, h_out, kc, vc, ws.t, ready, nxt)
-            ready = nxt is not None
-            chained += int(ready)
+            linked, next_row = R.chain_link(plans, l)
+            vlc.vlc_layer_forward_chained(rec, W.rec, prec, h_prev, h_out, kc, vc, ws.t, ready,
+                                          dws[l + 1].t["w_ln1"] if linked else None, next_row)
+            ready = linked
+            chained += int(linked) + 10 * int(next_row is not None)
         else:
             R.run_layer(rec, W, prec, h_prev, h_out, kc, vc, ws)
         torch.cuda.synchronize()
@@ -261,8 +262,8 @@ def test_reused_keys_of_all_layers_placed_ahead_of_the_layer_loop():
 
 def test_chained_layers_small_shapes():
     """vlc_layer_forward_chained over whole stacks against the oracle: the fp32 and bf16 tiny stacks and the packed
-    pair with a uniform rate (every layer hands its successor the input norm), full recompute, and rates that fall
-    with depth (only runs of equal rates chain; a layer whose successor drops rows norms for itself)."""
+    pair with a uniform rate (the successor keeps every row), full recompute, and rates that fall with depth (the
+    successor drops rows: the norm is written through the row list)."""
     for name in ("c1", "c1_bf16", "c1_q3"):
         check_against_oracle(syn.make_workload(name), layers=2, teacher_forced=False, chain=True)
         assert check_against_oracle.chained == 1
@@ -279,7 +280,10 @@ def test_chained_layers_small_shapes():
     k, _ = plan_steps(wl)
     assert k[0] != k[1]
     check_against_oracle(wl, layers=sh.L, teacher_forced=False, chain=True)
-    assert check_against_oracle.chained == 0
+    assert check_against_oracle.chained == 11
+    wl = syn.Workload("falling_bf16", syn.SHAPES["tiny_bf16"], [r0, r1], 200, "dynamic", budget_bp=2000, seed=14)
+    check_against_oracle(wl, layers=2, teacher_forced=False, chain=True)
+    assert check_against_oracle.chained == 11
 
 
 def test_7b_shape_layer_stage_by_stage():

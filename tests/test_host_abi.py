@@ -259,10 +259,10 @@ def test_layer_forward_chained_argument_checks():
     f = vlc.lib().vlc_layer_forward_chained
     sh = vlc.LayerShape(256, 4, 2, 128, 512, vlc.VLC_BF16, 1e-6, 1e4, 0, 0, 0, 0, 0)
     a = ctypes.addressof(sh)
-    assert f(a, None, None, None, None, None, None, None, 0, None, 2, None, None) == 2
+    assert f(a, None, None, None, None, None, None, None, 0, None, 2, None, None, None) == 2
     assert "input_norm_ready" in vlc.last_error()
-    assert f(None, None, None, None, None, None, None, None, 0, None, 0, None, None) == 1
-    assert f(a, None, None, None, None, None, None, None, 0, None, 1, None, None) == 1      # weights / plan
+    assert f(None, None, None, None, None, None, None, None, 0, None, 0, None, None, None) == 1
+    assert f(a, None, None, None, None, None, None, None, 0, None, 1, None, None, None) == 1      # weights / plan
 
 
 def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
