@@ -242,12 +242,12 @@ static int layer_forward_impl(const vlc_layer_shape* shape, const vlc_layer_weig
     rc = vlc::launch_gemm_grouped(act, I, nullptr, w->w_down, H * I, y, H, pairs, E, H, I, vlc::EPI_BIAS, ms.tiles,
                                   ms.n_tiles, tile_rows, s.dtype, st, pairs);
     if (rc) return rc;
-    rc = vlc::launch_moe_combine(h1, y, ms.wts, ms.pair_pos, n, K, s.H, h_out, s.dtype, st);
+    if (next_w_ln1)   // chained: the weighted sum and the input norm of the layer below in one kernel
+      rc = vlc::launch_moe_combine_norm(h1, y, ms.wts, ms.pair_pos, n, K, s.H, h_out, next_w_ln1, xn, next_row,
+                                        s.eps, s.dtype, st);
+    else
+      rc = vlc::launch_moe_combine(h1, y, ms.wts, ms.pair_pos, n, K, s.H, h_out, s.dtype, st);
     if (rc) return rc;
-    if (next_w_ln1) {
-      rc = vlc::launch_rmsnorm(h_out, nullptr, next_w_ln1, xn, n, s.H, s.eps, s.dtype, st, next_row);
-      if (rc) return rc;
-    }
     VLC_MARK(9);
     return VLC_OK;
   }

@@ -242,6 +242,81 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const T* __restrict__ 
   }
 }
 
+// moe_combine_kernel followed by the RMSNorm of the row it has just written (the input norm of the layer below,
+// weight nw): thread t owns chunks t, t + 256, ... as the stand-alone norm kernel does, and the sums are taken
+// in the same order on the stored (rounded) values, so both routes give the same bits.  The normed row goes to
+// yn[ymap ? ymap[row] : row]; a negative entry: no norm for this row.
+template <typename T, int MAXC>
+__global__ __launch_bounds__(256) void moe_combine_norm_kernel(const T* __restrict__ h1, const T* __restrict__ y,
+                                                               const float* __restrict__ wts,
+                                                               const int32_t* __restrict__ pair_pos, int K, int H,
+                                                               T* __restrict__ out, const T* __restrict__ nw,
+                                                               T* __restrict__ yn, const int32_t* __restrict__ ymap,
+                                                               float inv_h, float eps) {
+  constexpr int VEC = 16 / sizeof(T);
+  const int64_t row = blockIdx.x;
+  __shared__ float w[kMaxTopK];
+  __shared__ int pos[kMaxTopK];
+  __shared__ float red[4];
+  if (threadIdx.x < K) {
+    w[threadIdx.x] = wts[row * K + threadIdx.x];
+    pos[threadIdx.x] = pair_pos[row * K + threadIdx.x];
+  }
+  __syncthreads();
+  float v[MAXC][VEC];
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = (threadIdx.x + j * 256) * VEC;
+    if (c < H) {
+      float acc[VEC];
+      uint4 raw = *reinterpret_cast<const uint4*>(h1 + row * H + c);
+      const T* hp = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+      for (int k = 0; k < K; ++k) {
+        const uint4 yr = *reinterpret_cast<const uint4*>(y + (int64_t)pos[k] * H + c);
+        const T* yp = reinterpret_cast<const T*>(&yr);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w[k], ld_elem(yp + i), acc[i]);
+      }
+      uint4 o;
+      T* op = reinterpret_cast<T*>(&o);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) st_elem(op + i, ld_elem(hp + i) + acc[i]);
+      *reinterpret_cast<uint4*>(out + row * H + c) = o;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        v[j][i] = ld_elem(op + i);
+        ss += v[j][i] * v[j][i];
+      }
+    }
+  }
+  const int64_t yrow = ymap ? (int64_t)ymap[row] : row;
+  if (yrow < 0) return;                    // the same for the whole workgroup
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) tot += red[i];
+  const float r = 1.0f / sqrtf(tot * inv_h + eps);
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = (threadIdx.x + j * 256) * VEC;
+    if (c < H) {
+      const uint4 wr = *reinterpret_cast<const uint4*>(nw + c);
+      const T* wp = reinterpret_cast<const T*>(&wr);
+      uint4 o;
+      T* op = reinterpret_cast<T*>(&o);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) st_elem(op + i, v[j][i] * r * ld_elem(wp + i));
+      *reinterpret_cast<uint4*>(yn + yrow * H + c) = o;
+    }
+  }
+}
+
 }  // namespace
 
 int launch_moe_route(const float* logits, int splits, int64_t split_stride, float* sum_out, int64_t n,
@@ -294,6 +369,32 @@ int launch_moe_combine(const void* h1, const void* y, const float* wts, const in
     return fail(VLC_ERR_DTYPE, "moe combine: dtype=%d", dtype);
   }
   VLC_CHECK_LAUNCH("moe_combine");
+  return VLC_OK;
+}
+
+int launch_moe_combine_norm(const void* h1, const void* y, const float* wts, const int32_t* pair_pos, int64_t n,
+                            int top_k, int H, void* out, const void* norm_w, void* normed, const int32_t* ymap,
+                            float eps, int dtype, hipStream_t st) {
+  if (n <= 0) return VLC_OK;
+  if (top_k < 1 || top_k > kMaxTopK) return fail(VLC_ERR_SHAPE, "moe combine: top_k=%d", top_k);
+  if (dtype != VLC_BF16 && dtype != VLC_F32) return fail(VLC_ERR_DTYPE, "moe combine: dtype=%d", dtype);
+  const int vec = dtype == VLC_BF16 ? 8 : 4;
+  if (H % vec) return fail(VLC_ERR_SHAPE, "moe combine: H=%d must be a multiple of %d", H, vec);
+  const int chunks = H / vec;
+  const float inv_h = 1.0f / (float)H;
+#define VLC_LAUNCH_MCN(T, MAXC)                                                                              \
+  hipLaunchKernelGGL((moe_combine_norm_kernel<T, MAXC>), dim3((unsigned)n), dim3(256), 0, st, (const T*)h1,  \
+                     (const T*)y, wts, pair_pos, top_k, H, (T*)out, (const T*)norm_w, (T*)normed, ymap, inv_h, eps)
+  if (chunks <= 256 * 2) {
+    if (dtype == VLC_BF16) VLC_LAUNCH_MCN(uint16_t, 2); else VLC_LAUNCH_MCN(float, 2);
+  } else if (chunks <= 256 * 8) {
+    if (dtype == VLC_BF16) VLC_LAUNCH_MCN(uint16_t, 8); else VLC_LAUNCH_MCN(float, 8);
+  } else {   // very wide rows: the two kernels one after the other
+    const int rc = launch_moe_combine(h1, y, wts, pair_pos, n, top_k, H, out, dtype, st);
+    return rc ? rc : launch_rmsnorm(out, nullptr, norm_w, normed, n, H, eps, dtype, st, ymap);
+  }
+#undef VLC_LAUNCH_MCN
+  VLC_CHECK_LAUNCH("moe_combine_norm");
   return VLC_OK;
 }
 

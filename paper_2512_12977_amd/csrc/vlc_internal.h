@@ -151,6 +151,11 @@ int launch_moe_route(const float* logits, int splits, int64_t split_stride, floa
                      int n_experts, int top_k, int tile_rows, const MoeScratch& s, hipStream_t st);
 int launch_moe_combine(const void* h1, const void* y, const float* wts, const int32_t* pair_pos, int64_t n,
                        int top_k, int H, void* out, int dtype, hipStream_t st);
+// launch_moe_combine, then normed[ymap ? ymap[i] : i] = RMSNorm(out[i]) * norm_w in the same kernel
+// (rows with ymap[i] < 0 get no norm); the same bits as launch_moe_combine + launch_rmsnorm
+int launch_moe_combine_norm(const void* h1, const void* y, const float* wts, const int32_t* pair_pos, int64_t n,
+                            int top_k, int H, void* out, const void* norm_w, void* normed, const int32_t* ymap,
+                            float eps, int dtype, hipStream_t st);
 
 }  // namespace vlc
 #endif

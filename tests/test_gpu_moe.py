@@ -98,6 +98,39 @@ def test_moe_tiny_fp32_stack_end_to_end():
     assert check_against_oracle.chained == 1
 
 
+def stack_both_ways(wl, layers):
+    """The first `layers` layers free-running on the GPU, layer by layer and chained; returns both results."""
+    sh = wl.shape
+    k, explicit = plan_steps(wl)
+    weights = [syn.layer_weights(sh, wl.seed, l) for l in range(layers)]
+    emb = syn.embedding_rows(wl)
+    caches = [syn.cached_kv(wl, l) for l in range(layers)]
+    plain, _ = run_gpu_stack(wl, weights, emb, caches, k, explicit, layers)
+    chained, plans = run_gpu_stack(wl, weights, emb, caches, k, explicit, layers, chain=True)
+    return plain, chained, plans
+
+
+@pytest.mark.parametrize("name", ["c1_moe", "c1_moe_bf16", "falling", "c2_moe"])
+def test_moe_chained_layers_equal_layer_by_layer(name):
+    """With experts the chained call takes the next layer's input norm in the kernel that forms the weighted sum of
+    the experts' outputs: h_out and K/V of every layer equal, bit for bit, those of vlc_layer_forward layer by layer
+    (which the other tests compare with the oracle) - tiny fp32 and bf16 stacks, a bf16 stack whose second layer
+    drops rows, and two layers at the 30B-A3B shape."""
+    if name == "falling":
+        from vlc_synth.workloads import _grid_request
+        req = _grid_request([("text", 20), ("image", 10, 10, 3, 0), ("text", 9), ("image", 6, 10, 40, 100), ("text", 5)])
+        wl = syn.Workload("falling_moe", syn.SHAPES["tiny_moe_bf16"], [req], 160, "dynamic", budget_bp=2000, seed=16)
+    else:
+        wl = syn.make_workload(name)
+    plain, chained, plans = stack_both_ways(wl, 2)
+    assert plans.chained == (11 if name == "falling" else 1)
+    for l in range(2):
+        for a, b, what in zip(plain[l], chained[l], ("h_out", "K", "V")):
+            assert np.array_equal(a, b), "%s of layer %d" % (what, l)
+    if name != "c2_moe":
+        check_against_oracle(wl, layers=2, teacher_forced=False, chain=True)
+
+
 @pytest.mark.parametrize("name", ["c1_moe", "c1_moe_bf16"])
 def test_moe_tiny_layer_stage_by_stage(name):
     wl = syn.make_workload(name)
