@@ -15,8 +15,9 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-@pytest.mark.parametrize("name", ["c1_bf16", "c1_moe_bf16", "c1"])
-def test_captured_prefill_replays_like_eager(name):
+@pytest.mark.parametrize("name,chain", [("c1_bf16", False), ("c1_moe_bf16", False), ("c1", False),
+                                        ("c1_bf16", True), ("c1_moe_bf16", True)])
+def test_captured_prefill_replays_like_eager(name, chain):
     wl = syn.make_workload(name)
     sh = wl.shape
     L = sh.L
@@ -44,6 +45,9 @@ def test_captured_prefill_replays_like_eager(name):
 
     def step():
         shift.run(sh.rope_base)
+        if chain:     # vlc_layer_forward_chained: each layer leaves the next one's input norm in the workspace
+            R.run_layers(rec, weights, plans, recs, h_in, hbuf, kc, vc, ws)
+            return
         x = h_in
         for l in range(L):
             R.run_layer(rec, weights[l], recs[l], x, hbuf[l & 1], kc[l], vc[l], ws)
