@@ -145,24 +145,14 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
     my_len[rt] = vr_ok[rt] ? s_len[r_local[rt]] : 0;
   }
 
-  // Q fragments: Q[vr][16*ks + 8*x .. +8)
+  // Q fragments: Q[vr][16*ks + 8*x .. +8).  They are fetched together with the first K and V tiles of the first
+  // run of rows (one memory latency instead of two, which counts when a workgroup has only a few key blocks).
   bf16x8 qf[RT][ATT_D / 16];
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const u32x4* qp = reinterpret_cast<const u32x4*>(q + (int64_t)(row0 + (vr_ok[rt] ? r_local[rt] : 0)) * q_stride +
-                                                     (int64_t)head[rt] * ATT_D);
+  for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-    for (int ks = 0; ks < ATT_D / 16; ++ks) {
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (vr_ok[rt]) v = qp[2 * ks + x];
-      qf[rt][ks] = __builtin_bit_cast(bf16x8, v);
-    }
-  }
-
-  // The Q loads are the only vector-memory reads the compiler knows of; completing them here keeps it
-  // from placing a vmcnt(0) wait (which would also wait for freshly issued K/V copies) at their
-  // first use inside the key loop.
-  VLC_ATT_WAIT_VM0();
+    for (int ks = 0; ks < ATT_D / 16; ++ks) qf[rt][ks] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+  bool q_loaded = false;
 
   f32x16 o_acc[RT][ATT_D / 32];
   float m_run[RT], l_run[RT];
@@ -399,8 +389,22 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
       VLC_ATT_ISSUE_K(kb_first, 0)
       VLC_ATT_ISSUE_V(kb_first, 0)
       if (n_blocks > 1) VLC_ATT_ISSUE_K(kb_first + 1, 1)
-      VLC_ATT_WAIT_VM0();
     }
+    if (!q_loaded) {
+      q_loaded = true;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const u32x4* qp = reinterpret_cast<const u32x4*>(q + (int64_t)(row0 + (vr_ok[rt] ? r_local[rt] : 0)) * q_stride +
+                                                         (int64_t)head[rt] * ATT_D);
+#pragma unroll
+        for (int ks = 0; ks < ATT_D / 16; ++ks)
+          if (vr_ok[rt]) qf[rt][ks] = __builtin_bit_cast(bf16x8, qp[2 * ks + x]);
+      }
+    }
+    // The Q loads are the only vector-memory reads the compiler knows of; completing them here, together with
+    // this wavefront's shares of the tiles fetched above, keeps it from placing a vmcnt(0) wait (which would
+    // also wait for freshly issued K/V copies) at their first use inside the key loop.
+    VLC_ATT_WAIT_VM0();
     __syncthreads();
     if (n_blocks > 0 && kb_first * KB < w_max) VLC_ATT_QK(st_a, 0)
     __syncthreads();                 // K stage 0 may be refilled from here on
