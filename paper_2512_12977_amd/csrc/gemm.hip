@@ -665,19 +665,22 @@ int dispatch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ld
   // 256 x 256 tiles (one workgroup per CU) against the small tiles (two per CU).
   bool big;
   if constexpr (EPI == EPI_SWIGLU) {
-    // Both in rounds of resident workgroups, the last round shortened by the tail split as launch_bf16 does it;
-    // a round of 256 x 256 tiles takes 1.09 rounds of 128 x 192 tiles (measured rates 1.26 and 1.03 PFLOP/s).
-    auto rounds = [KT](int64_t tiles, int slots) {
+    // Both in rounds of resident workgroups, the last round shortened by the tail split as launch_bf16 does it.
+    // A round of 256 x 256 tiles takes 1.09 rounds of 128 x 192 tiles (measured rates 1.26 and 1.03 PFLOP/s with
+    // thousands of tiles); its workgroups have nobody beside them on the CU to cover their start, their end and the
+    // float blocks of a split tile, which with few rounds costs about a quarter round per launch and a fifth per
+    // split tail (fitted on 596 ... 1600 rows at three shapes: the small tile wins up to about 1000 rows).
+    auto rounds = [KT](int64_t tiles, int slots, float split_cost) {
       const int64_t full = tiles / slots, tail = tiles % slots;
       float r = (float)full;
       if (tail > 0) {
         const int64_t tsp = full > 0 ? (slots / tail < KT / 8 ? slots / tail : KT / 8) : 1;
-        r += tsp >= 2 ? 1.0f / (float)tsp + 0.1f : 1.0f;
+        r += tsp >= 2 ? 1.0f / (float)tsp + split_cost : 1.0f;
       }
       return r;
     };
     const int64_t tiles_big = ((M + 255) / 256) * ((N + 127) / 128), tiles_small = ((M + 127) / 128) * ((N + 95) / 96);
-    big = 1.09f * rounds(tiles_big, 256) < rounds(tiles_small, 512);
+    big = 1.09f * rounds(tiles_big, 256, 0.2f) + 0.25f < rounds(tiles_small, 512, 0.1f);
   } else {
     // with few output columns (the o, down and qkv products) there are not enough 256 x 256 tiles for the 256 CUs
     // until several thousand rows: the small tiles with a split k range stay ahead
