@@ -109,15 +109,18 @@ def test_full_size_layer_sampled_rows(name, layer, req_ids, n_rows):
 
 @pytest.mark.parametrize("shape,n_text,n_image,all_rows", [("7b", 200, 5000, True), ("7b", 720, 2000, False),
                                                            ("7b", 1184, 0, True), ("7b", 1600, 0, True),
-                                                           ("72b", 1000, 0, True)])
+                                                           ("72b", 1000, 0, True), ("7b", 300, 0, True),
+                                                           ("72b", 600, 0, True)])
 def test_layer_rows_that_leave_a_partial_round_of_gemm_tiles(shape, n_text, n_image, all_rows):
     """Row counts at which the output tiles of the GEMMs do not fill the chip a whole number of times
-    (5200 rows: all four GEMMs on 256-row tiles; 720 rows: the gate|up GEMM on 128 x 192 tiles, whose last column
-    tile is ragged; 1184 and 1600 rows: gate|up on 256-row tiles next to o, down and qkv on 128-row tiles with a
-    split k range): the tiles of the last round are then split along k and summed by a second kernel.  Every 13th row
-    (so every tile of every GEMM is sampled) is compared stage by stage with the oracle.  72B shape, 1000 rows: the
-    q|k|v projection (10240 columns) takes 128 x 192 tiles without a split k range and with the float-output epilogue
-    (432 tiles fit the chip at once, 640 tiles of 128 columns would not)."""
+    (5200 rows: all four GEMMs on 256-row tiles; 720, 1184 and 1600 rows: gate|up on 256-row tiles - three row tiles, the
+    last ragged, at 720 - next to o, down and qkv on 128-row tiles with a split k range; 300 rows at the 7B shape and 600
+    at the 72B shape: gate|up on 128 x 192 tiles with the mixed gate/up accumulator tile, 594 = 512 + 82 and 1540 =
+    3 x 512 + 4 of them, whose last column tile is ragged): the tiles of the last round are then split along k (6 and
+    16 ways for the last two) and summed by a second kernel.  Every 13th row (so every tile of every GEMM is sampled)
+    is compared stage by stage with the oracle.  72B shape, 1000 rows: the q|k|v projection (10240 columns) takes
+    128 x 192 tiles without a split k range and with the float-output epilogue (432 tiles fit the chip at once, 640
+    tiles of 128 columns would not)."""
     sh = syn.SHAPES[shape]
     st = orc.STORE[sh.dtype]
     dt = R.torch_dtype(sh.dtype)
