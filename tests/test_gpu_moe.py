@@ -156,6 +156,17 @@ def test_moe_many_pairs_grouped_with_atomic_ranks():
     assert g["moe_idx"].shape == (330 * 124, 2)
 
 
+@pytest.mark.parametrize("rows", [250, 420, 700])
+def test_moe_mid_sized_groups_on_128_row_tiles(rows):
+    """62, 105 and 175 rows per expert on average (8 experts, 2 per token): the grouped GEMMs run on 128 x 128 tiles
+    (56 to 191 rows per expert), with groups of one and of two row tiles, the last ragged."""
+    sh = syn.SHAPES["tiny_moe_bf16"]
+    req = syn.Request([syn.Segment(0, rows, False)], 0, 0, syn.grid_positions([("text", rows)]))
+    wl = syn.Workload("moe_mid_%d" % rows, sh, [req], 1, "static", static_k=0, seed=18)
+    g = check_moe_layer(wl, 0)
+    assert g["moe_idx"].shape == (rows, 2)
+
+
 def test_moe_more_pairs_than_2_gib_of_input_rows():
     """66000 rows at the 30B-A3B shape: 528000 (row, expert) pairs, so pairs x row bytes (2.2 GB) passes the 2 GiB
     that the grouped GEMM's 32-bit row offsets cover while the rows themselves (270 MB) do not - the bound that
