@@ -132,24 +132,100 @@ def stage_bytes_of_gemm(sh, name, n):
     return float(N * K * e + n * K * e + n * n_out * eo)
 
 
+def hbm_kernels(hev, stream, iters=20):
+    """The three stand-alone HBM-bound entry points at the sizes of the long-context batch (7B-shaped K/V rows of
+    1 KB, 8 requests x 18432 slots), timed with HIP events on `stream`.  Algorithmic bytes: gather 2*H*e per row;
+    scatter 4*Hkv*D*e per row (K and V, read + write); RoPE shift 4*Hkv*D*e per reused token (K and V, read + write).
+    The index lists have the structure of that workload: per request the text runs plus the 20 leading tokens of
+    each of 16 images are recomputed rows, every other image token is reused."""
+    import torch
+    import paper_2512_12977_amd as vlc
+    dev, dt = "cuda", torch.bfloat16
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    Hkv, D, H = 4, 128, 3584
+    n_req, S, n_img, T, lead = 8, 18432, 16, 1024, 20
+    slots, pool = n_req * S, n_req * n_img * T
+    rec_rows, reuse_dst, reuse_src, delta = [], [], [], []
+    for b in range(n_req):
+        a = 100 + 97 * b                                   # text before the images (distinct per request)
+        base = b * S
+        rec_rows.append(np.arange(base, base + a))
+        for j in range(n_img):
+            s0 = base + a + j * T
+            rec_rows.append(np.arange(s0, s0 + lead))
+            reuse_dst.append(np.arange(s0 + lead, s0 + T))
+            reuse_src.append((b * n_img + j) * T + np.arange(lead, T))
+            delta.append(np.full(T - lead, a, dtype=np.int64))
+        rec_rows.append(np.arange(base + a + n_img * T, base + S))
+    rec = torch.from_numpy(np.concatenate(rec_rows).astype(np.int32)).to(dev)
+    dst = torch.from_numpy(np.concatenate(reuse_dst).astype(np.int32)).to(dev)
+    src = torch.from_numpy(np.concatenate(reuse_src).astype(np.int32)).to(dev)
+    dl = torch.from_numpy(np.concatenate(delta).astype(np.int32)).to(dev)
+    n, n_tok = rec.numel(), dst.numel()
+    kp = torch.randn((pool, Hkv, D), device=dev, generator=g).to(dt)
+    vp = torch.randn((pool, Hkv, D), device=dev, generator=g).to(dt)
+    kc = torch.zeros((slots, Hkv, D), device=dev, dtype=dt)
+    vc = torch.zeros((slots, Hkv, D), device=dev, dtype=dt)
+    h = torch.randn((slots, H), device=dev, generator=g).to(dt)
+    x = torch.empty((n, H), device=dev, dtype=dt)
+    kn = torch.randn((n, Hkv, D), device=dev, generator=g).to(dt)
+    vn = torch.randn((n, Hkv, D), device=dev, generator=g).to(dt)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ev = hev.create(2)
+        hev.record(ev[0], stream)
+        for _ in range(iters):
+            fn()
+        hev.record(ev[1], stream)
+        torch.cuda.synchronize()
+        t = hev.elapsed_ms(ev[0], ev[1]) / iters * 1e-3
+        hev.destroy(ev)
+        return t
+
+    out = {}
+    for name, fn, units, by in (
+            ("vlc_rope_shift_kv", lambda: vlc.vlc_rope_shift_kv(kp, vp, kc, vc, src, dst, dl, 1e6), n_tok,
+             n_tok * 4.0 * Hkv * D * 2),
+            ("vlc_gather_rows", lambda: vlc.vlc_gather_rows(h, rec, x), n, n * 2.0 * H * 2),
+            ("vlc_scatter_kv", lambda: vlc.vlc_scatter_kv(kn, vn, rec, kc, vc), n, n * 4.0 * Hkv * D * 2)):
+        t = timed(fn)
+        out[name] = {"rows": int(units), "avg_us": round(t * 1e6, 2), "bytes_per_launch": by, "bound": "hbm",
+                     "achieved": round(by / t / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(by / t / 1e9 / PEAK_HBM_GBS, 4)}
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c2", choices=sorted(DESCR))
+    ap.add_argument("--workload", default="c4", choices=sorted(DESCR),
+                    help="default: c4, the long-context batch (the largest 7B-shaped configuration; the regime the "
+                         "method targets)")
     ap.add_argument("--parity-layers", type=int, default=1,
                     help="layers whose weights/caches come from the seeded host generator (rest: device RNG)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full", action="store_true", help="skip the full-recompute comparison")
     ap.add_argument("--no-first-token", action="store_true", help="skip the first-token head timing")
     ap.add_argument("--cpu-layers", type=int, default=None, help="layers of the oracle sample")
+    ap.add_argument("--cpu-images", type=int, default=None,
+                    help="oracle sample: only the leading part of request 0 up to and including this many images")
     ap.add_argument("--per-layer-shift", action="store_true",
                     help="re-rotate the reused keys inside every layer call instead of in one launch for all "
                          "layers ahead of the layer loop")
     ap.add_argument("--no-chain", action="store_true",
                     help="every layer takes its own input norm (default: each layer leaves the norm of the rows its "
                          "successor recomputes behind, vlc_layer_forward_chained)")
+    ap.add_argument("--no-hbm-kernels", action="store_true",
+                    help="skip the stand-alone timing of vlc_gather_rows / vlc_scatter_kv / vlc_rope_shift_kv")
+    ap.add_argument("--hbm-kernels-only", action="store_true",
+                    help="time only the three stand-alone HBM-bound entry points at the long-context batch sizes and "
+                         "print their JSON (the command the kernel-trace / counter summaries of these kernels use)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain row copy of 1 GiB through vlc_gather_rows "
                          "(identity index) so a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -168,12 +244,15 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     dev = "cuda"
+    if args.hbm_kernels_only:
+        print(json.dumps({"hbm_kernels": hbm_kernels(HipEvents(), torch.cuda.current_stream().cuda_stream or None)}))
+        return 0
     wl = syn.make_workload(args.workload)
     sh = wl.shape
     L = sh.L
     dt = R.torch_dtype(sh.dtype)
     rec = R.make_shape(sh)
-    steps = args.steps if args.steps is not None else {"c1": 50, "c2": 20, "c3": 10, "c4": 5, "c4_5": 5, "c5": 5, "c2_q3": 20, "c3_q3": 10, "c2_moe": 20, "c4_moe": 5}[wl.name]
+    steps = args.steps if args.steps is not None else {"c1": 50, "c2": 20, "c3": 10, "c4": 10, "c4_5": 10, "c5": 5, "c2_q3": 20, "c3_q3": 10, "c2_moe": 20, "c4_moe": 5}[wl.name]
 
     # ---- plans (library planner) ---------------------------------------------------------------
     k, explicit = R.plan_for(wl)
@@ -337,28 +416,49 @@ def main() -> int:
         stages["rope_shift_all_layers"] = {"avg_us": round(shift_all_us, 2), "per_step": True,
                                            "gbs": round(by / (shift_all_us * 1e-6) / 1e9, 1)}
     dom_name = vlc.LAYER_STAGES[dom]
-    fl = np.mean([stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])[dom_name][0] for l in range(L)])
-    by = np.mean([stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])[dom_name][1] for l in range(L)])
-    dur = dom_us * 1e-6          # average over every launch of the timed region
     peak = PEAK_BF16_TFLOPS if sh.dtype == "bf16" else PEAK_F32_TFLOPS
-    gemm_bytes = stage_bytes_of_gemm(sh, dom_name, float(np.mean(rows))) if fl > 0 else None
-    if fl > 0 and gemm_bytes and gemm_bytes / (PEAK_HBM_GBS * 1e9) > fl / (peak * 1e12):
-        # a GEMM whose matrices take longer to stream than its products take to form (few rows per expert)
-        ach = gemm_bytes / dur / 1e9
-        roofline = {"kernel": dom_name, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
+
+    def roof(name, fl, by, dur):
+        """Roofline record of one stage: fl / by = algorithmic flops / bytes per launch, dur = seconds per launch."""
+        gemm_bytes = stage_bytes_of_gemm(sh, name, float(np.mean(rows))) if fl > 0 else None
+        if fl > 0 and gemm_bytes and gemm_bytes / (PEAK_HBM_GBS * 1e9) > fl / (peak * 1e12):
+            # a GEMM whose matrices take longer to stream than its products take to form (few rows per expert)
+            ach = gemm_bytes / dur / 1e9
+            return {"kernel": name, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
                     "avg_launch_us": round(dur * 1e6, 2), "bytes_per_launch": gemm_bytes, "flops_per_launch": fl}
-    elif fl > 0:
-        ach = fl / dur / 1e12
-        roofline = {"kernel": dom_name, "bound": "mfma" if sh.dtype == "bf16" else "alu", "achieved": round(ach, 2),
+        if fl > 0:
+            ach = fl / dur / 1e12
+            return {"kernel": name, "bound": "mfma" if sh.dtype == "bf16" else "alu", "achieved": round(ach, 2),
                     "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4), "traffic": None,
                     "avg_launch_us": round(dur * 1e6, 2), "flops_per_launch": fl,
                     "algorithmic_bytes_per_launch": gemm_bytes}
-    else:
         ach = by / dur / 1e9
-        roofline = {"kernel": dom_name, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
-                    "avg_launch_us": round(dur * 1e6, 2), "bytes_per_launch": by}
+        return {"kernel": name, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
+                "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
+                "avg_launch_us": round(dur * 1e6, 2), "bytes_per_launch": by}
+
+    def mean_work(name):
+        w = [stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])[name] for l in range(L)]
+        return float(np.mean([a for a, _ in w])), float(np.mean([b for _, b in w]))
+
+    # the dominant stage: average over every launch of the timed region
+    roofline = roof(dom_name, *mean_work(dom_name), dom_us * 1e-6)
+    # every stage against its own roofline, from the all-event pass (same kernels, same inputs, outside `value`)
+    kernels = {}
+    for i, name in enumerate(vlc.LAYER_STAGES):
+        fl, by = mean_work(name)
+        us = float(stage_avg_us[i])
+        if (fl <= 0 and by <= 0) or "note" in stages[name]:
+            continue
+        r = roof(name, fl, by, us * 1e-6)
+        kernels[name] = {k2: r[k2] for k2 in ("bound", "achieved", "peak", "unit", "frac", "avg_launch_us")}
+    if shift_all_us is not None:
+        by = float(sum(stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])["rope_shift"][1] for l in range(L)))
+        ach = by / (shift_all_us * 1e-6) / 1e9
+        kernels["rope_shift_all_layers"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
+                                            "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4),
+                                            "avg_launch_us": round(shift_all_us, 2), "launches_per_step": 1}
 
     # HBM traffic of the dominant kernel, if a counter run of this workload has been summarised
     try:
@@ -422,6 +522,12 @@ def main() -> int:
         full_ms = hev.elapsed_ms(e2[0], e2[1]) / fsteps
         hev.destroy(e2)
 
+    # ---- the three stand-alone HBM-bound entry points at the long-context batch sizes -----------------
+    hbm = None
+    if not args.no_hbm_kernels:
+        torch.cuda.empty_cache()
+        hbm = hbm_kernels(hev, stream)
+
     if args.calibrate_copy:
         rows_c, elems_c = 1 << 17, 4096                      # 2^17 rows x 8 KiB = 1 GiB read + 1 GiB written
         src_c = torch.ones((rows_c, elems_c), device=dev, dtype=torch.bfloat16)
@@ -441,6 +547,16 @@ def main() -> int:
         except Exception:
             cores = os.cpu_count()
         req = wl.requests[0]
+        sample_note = "request 0 of %d" % len(wl.requests)
+        if args.cpu_images is not None:
+            # the request's leading part (its first text run and that many of its images).  Attention is causal in
+            # slot order, so these rows come out exactly as they do inside the whole request.
+            import dataclasses
+            lead = tuple(req.segments[:1 + args.cpu_images])
+            n_lead = sum(sg.length for sg in lead)
+            req = dataclasses.replace(req, segments=lead, pos3=None if req.pos3 is None else req.pos3[:n_lead])
+            sample_note = "leading %d slots (first text run + %d images) of request 0 of %d" % (
+                req.S, args.cpu_images, len(wl.requests))
         # about 10-30 s of oracle work: ~1.3 s per 7B-shaped layer at 596 rows on the box's 16 host threads
         n_layers = args.cpu_layers or {"c1": 2, "c2": 10, "c3": 3, "c2_q3": 10, "c3_q3": 3, "c2_moe": 4}.get(wl.name, 1)
         n_layers = min(n_layers, L)
@@ -456,8 +572,8 @@ def main() -> int:
         cpu_s = time.perf_counter() - t0
         cpu_rows = sum(len(r["slots"]) for r in res)
         cpu = {"value": round(cpu_rows / cpu_s, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-               "sample": "request 0 of %d, layers 0..%d of %d (%d recomputed rows), numpy float64, %.1f s"
-                         % (len(wl.requests), n_layers - 1, L, cpu_rows, cpu_s)}
+               "sample": "%s, layers 0..%d of %d (%d recomputed rows), numpy float64, %.1f s"
+                         % (sample_note, n_layers - 1, L, cpu_rows, cpu_s)}
 
     n_req = len(wl.requests)
     out = {
@@ -487,6 +603,10 @@ def main() -> int:
         "first_token": first_tok,
         "ttft_like_ms": None if first_tok is None else round(ms_per_step + first_tok["avg_us"] * 1e-3, 4),
         "roofline": roofline,
+        "kernels": kernels,
+        "kernels_source": "HIP-event stage durations of a separate pass with all stage events (3 steps, same inputs); "
+                          "fractions are achieved algorithmic rate / published peak (2.5 PFLOP/s dense bf16 MFMA, 8 TB/s HBM)",
+        "hbm_kernels": hbm,
         "stages": stages,
         "stages_source": "separate untimed pass with all stage events (3 steps); the timed steps record only the two events around the dominant stage of each layer",
         "cpu_baseline": cpu,
