@@ -64,6 +64,9 @@ int vlc_version(void);
  * among layers that stay <= G and keep the sequence non-increasing; the drop must be > 0;
  * equal drops go to the lowest layer index; stops when the budget is spent or no layer
  * qualifies.  The result is unique.
+ * Limitation: from all zeros only layer 0 can move under Eq. 8, so a table whose first layer's scores do not
+ * fall (measured tables: layer 0's cached keys/values do not depend on the prompt, Sec. 3.2) yields the
+ * all-zero plan with VLC_OK and the budget unspent; use vlc_plan_layer_rates_blocks for such tables.
  *   sens   host, [L][G+1] doubles, column c = score of that layer at rate c/500
  *   k_out  host, [L] int32, written
  * Errors: NULL pointers, L <= 0, G <= 0 or G > VLC_RATE_GRID, budget_steps < 0.
@@ -123,6 +126,24 @@ int vlc_plan_token_indices(int n_seg, const vlc_segment* seg, int L, const int32
                            const int32_t* count_override, int64_t cap, int32_t* n_rows,
                            int32_t* slot, int32_t* map, int32_t* pos, int32_t* kv_start,
                            int32_t* kv_len);
+
+/*
+ * Where each row of a layer goes in the layer below (Sec. 4.1, last paragraph / Eq. 8: rates do not increase
+ * with depth, so the rows of layer l+1 are a subset of those of layer l): next_row[l][i] = index of row i of
+ * layer l among the rows of layer l+1, or -1 if layer l+1 drops it - the inverse of that layer's `map`
+ * (next_row[l][map[l+1][j]] == j).  The last layer's entries are all -1.  This is the list
+ * vlc_layer_forward_chained takes.  Output host int32 [L][cap], the first n_rows[l] entries of each layer
+ * written; k / count_override / cap rules and errors as vlc_plan_token_indices.
+ */
+int vlc_plan_next_rows(int n_seg, const vlc_segment* seg, int L, const int32_t* k,
+                       const int32_t* count_override, int64_t cap, int32_t* next_row);
+
+/*
+ * Budget of the allocator from a mean recomputation rate (Eq. 7 bounds the sum of the layers' rates; Sec. 5.1
+ * quotes mean rates): a mean of mean_rate_bp / 10000 over L layers is mean_rate_bp * L / 20 steps of the
+ * 0.002 grid, rounded down.  steps: host, written.  Errors: NULL, mean_rate_bp outside 0..10000, L <= 0.
+ */
+int vlc_plan_budget_steps(int mean_rate_bp, int L, int64_t* steps);
 
 /*
  * The complementary list: image tokens that are reused (not recomputed) in each layer, with the
@@ -329,8 +350,8 @@ int vlc_layer_forward_timed(const vlc_layer_shape* shape, const vlc_layer_weight
                             void* const* stage_events);
 
 /*
- * vlc_layer_forward for consecutive layers of one prefill (Algorithm 1's allocation makes the rows of a
- * layer a subset of those of the layer above): the input RMSNorm of the layer below is produced by this
+ * vlc_layer_forward for consecutive layers of one prefill (Sec. 4.1, last paragraph / Eq. 8: rates do not
+ * increase with depth, which makes the rows of a layer a subset of those of the layer above): the input RMSNorm of the layer below is produced by this
  * layer's last kernel - the one that sums the down projection's partial products when its k range is
  * split - instead of a kernel of its own at the head of the next call.  Results equal vlc_layer_forward's
  * bit for bit.

@@ -67,6 +67,8 @@ def lib():
         L.vlc_plan_layer_rates.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
         L.vlc_plan_layer_rates_blocks.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
         L.vlc_plan_token_indices.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int64] + [C.c_void_p] * 6
+        L.vlc_plan_next_rows.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.vlc_plan_budget_steps.argtypes = [C.c_int, C.c_int, C.c_void_p]
         L.vlc_plan_reuse_rows.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int64] + [C.c_void_p] * 4
         L.vlc_gather_rows.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_void_p]
         L.vlc_rope_shift_kv.argtypes = [C.c_void_p] * 7 + [C.c_int64, C.c_int, C.c_int, C.c_double, C.c_int, C.c_void_p]
@@ -173,6 +175,25 @@ def vlc_plan_token_indices(segs: Sequence, L: int, k=None, count_override=None, 
                                         out["kv_start"].ctypes.data, out["kv_len"].ctypes.data))
     out["n_rows"] = n_rows
     return out
+
+
+def vlc_plan_next_rows(segs: Sequence, L: int, k=None, count_override=None, cap: Optional[int] = None) -> np.ndarray:
+    """Host int32 [L, cap]: index of each row of layer l among the rows of layer l + 1 (-1: dropped)."""
+    arr = _segments(segs)
+    if cap is None:
+        cap = sum(s.length for s in arr)
+    kk = None if k is None else _host_i32(k, "k")
+    oo = None if count_override is None else _host_i32(count_override, "count_override")
+    out = np.full((L, cap), -1, dtype=np.int32)
+    _check(lib().vlc_plan_next_rows(len(arr), C.addressof(arr), L, None if kk is None else kk.ctypes.data,
+                                    None if oo is None else oo.ctypes.data, cap, out.ctypes.data))
+    return out
+
+
+def vlc_plan_budget_steps(mean_rate_bp: int, L: int) -> int:
+    steps = C.c_int64()
+    _check(lib().vlc_plan_budget_steps(int(mean_rate_bp), int(L), C.addressof(steps)))
+    return int(steps.value)
 
 
 def vlc_plan_reuse_rows(segs: Sequence, L: int, k=None, count_override=None, cap: Optional[int] = None):

@@ -2,6 +2,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 #include "vlc_internal.h"
 
@@ -15,6 +16,24 @@ int fail(int code, const char* fmt, ...) {
   vsnprintf(g_err, sizeof(g_err), fmt, ap);
   va_end(ap);
   return code;
+}
+
+int ensure_dynamic_lds(const void* kernel, int bytes) {
+  // a fixed table, so that no call on the launch path touches the heap: the library has a few dozen kernel
+  // instantiations with dynamic LDS, times the devices of one node
+  struct Entry { int dev; const void* kernel; };
+  constexpr int kMax = 1024;
+  static std::mutex mu;
+  static Entry done[kMax];
+  static int n_done = 0;
+  int dev = 0;
+  VLC_CHECK_HIP(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lock(mu);
+  for (int i = 0; i < n_done; ++i)
+    if (done[i].dev == dev && done[i].kernel == kernel) return VLC_OK;
+  VLC_CHECK_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+  if (n_done < kMax) done[n_done++] = Entry{dev, kernel};   // a full table only costs the repeated call
+  return VLC_OK;
 }
 
 RopeFreq make_rope_freq(double base, int D, int mrope_h, int mrope_w) {

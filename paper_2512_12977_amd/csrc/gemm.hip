@@ -609,12 +609,7 @@ int launch_bf16(const void* A, int64_t lda, const void* W, void* C, int64_t ldc,
   const int tiles = tiles_m * tiles_n;
   const size_t lds = (size_t)STAGES * (BM + BN) * BK * 2;
   auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, STAGES, OCC, EPI>;
-  static bool attr_set = false;    // raising the dynamic LDS limit is per kernel, once per process
-  if (!attr_set) {
-    VLC_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds)) return rc;
   // Tail split: the chip holds `slots` workgroups at once; the tiles of the last, partly filled round are
   // shared out over as many k-ranges as fit into the idle slots (at least 8 k-tiles each).
   constexpr int slots = 256 * OCC;
@@ -779,12 +774,7 @@ int launch_bf16_grouped(const void* A, int64_t lda, const int32_t* amap, const v
   const int tiles_n = (int)((N + CN - 1) / CN);
   const size_t lds = (size_t)STAGES * (BM + BN) * BK * 2;
   auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, STAGES, OCC, EPI, true>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    VLC_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds)) return rc;
   const int grid = max_tiles_m * tiles_n;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), lds, st, (const uint16_t*)A, lda, (const uint16_t*)W,
                      (uint16_t*)C, ldc, 0, (int)N, (int)K, (const uint16_t*)nullptr, (const uint16_t*)nullptr,

@@ -162,6 +162,42 @@ extern "C" int vlc_plan_token_indices(int n_seg, const vlc_segment* seg, int L, 
   return VLC_OK;
 }
 
+extern "C" int vlc_plan_next_rows(int n_seg, const vlc_segment* seg, int L, const int32_t* k,
+                                  const int32_t* count_override, int64_t cap, int32_t* next_row) {
+  const char* who = "vlc_plan_next_rows";
+  if (!seg || !next_row) return fail(VLC_ERR_NULL, "%s: NULL pointer", who);
+  if (L <= 0 || cap < 0) return fail(VLC_ERR_SHAPE, "%s: L=%d cap=%lld", who, L, (long long)cap);
+  int rc = check_segments(n_seg, seg, who);
+  if (rc) return rc;
+  rc = check_rates(L, k, count_override, who);
+  if (rc) return rc;
+  // A layer keeps the leading take(l) tokens of a segment, the layer below the leading take(l+1) <= take(l) of
+  // them: row (rows of layer l before the segment) + t goes to (rows of layer l+1 before it) + t if t < take(l+1).
+  for (int l = 0; l < L; ++l) {
+    int64_t n = 0, n_below = 0;
+    for (int s = 0; s < n_seg; ++s) {
+      const vlc_segment& g = seg[s];
+      const int64_t take = g.is_image ? leading(k, count_override, l, g.length) : g.length;
+      const int64_t below = l + 1 >= L ? 0 : (g.is_image ? leading(k, count_override, l + 1, g.length) : g.length);
+      if (n + take > cap) return fail(VLC_ERR_SHAPE, "%s: cap=%lld too small at layer %d", who, (long long)cap, l);
+      for (int64_t t = 0; t < take; ++t)
+        next_row[(int64_t)l * cap + n + t] = t < below ? (int32_t)(n_below + t) : -1;
+      n += take;
+      n_below += below;
+    }
+  }
+  return VLC_OK;
+}
+
+extern "C" int vlc_plan_budget_steps(int mean_rate_bp, int L, int64_t* steps) {
+  if (!steps) return fail(VLC_ERR_NULL, "vlc_plan_budget_steps: steps is NULL");
+  if (mean_rate_bp < 0 || mean_rate_bp > 10000 || L <= 0)
+    return fail(VLC_ERR_SHAPE, "vlc_plan_budget_steps: mean_rate_bp=%d (0..10000) L=%d", mean_rate_bp, L);
+  // a mean rate of bp / 10000 over L layers is a rate sum of bp * L / 10000 (Eq. 7), i.e. bp * L / 20 grid steps
+  *steps = ((int64_t)mean_rate_bp * L) / (10000 / VLC_RATE_GRID);
+  return VLC_OK;
+}
+
 extern "C" int vlc_plan_reuse_rows(int n_seg, const vlc_segment* seg, int L, const int32_t* k,
                                    const int32_t* count_override, int64_t cap, int32_t* n_reuse,
                                    int32_t* src_row, int32_t* dst_slot, int32_t* delta) {

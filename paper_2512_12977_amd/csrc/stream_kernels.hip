@@ -729,12 +729,8 @@ int launch_rows_times_matrix_bf16(const void* x, const void* W, float* out, int6
   int64_t blocks = 256 * per_cu;
   const int64_t max_blocks = (V + kGemvThreads / 64 - 1) / (kGemvThreads / 64);
   if (blocks > max_blocks) blocks = max_blocks;
-  static bool attr_set = false;
-  if (!attr_set) {
-    VLC_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rows_times_matrix_bf16_kernel<8>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024));
-    attr_set = true;
-  }
+  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(rows_times_matrix_bf16_kernel<8>), 160 * 1024 - 1024))
+    return rc;
   hipLaunchKernelGGL(rows_times_matrix_bf16_kernel<8>, dim3((unsigned)blocks), dim3(kGemvThreads), lds, st,
                      (const uint4*)x, (const uint4*)W, out, (int)m, chunks, V);
   VLC_CHECK_LAUNCH("rows_times_matrix_bf16");

@@ -29,6 +29,10 @@ inline int elem_size(int dtype) { return dtype == VLC_BF16 ? 2 : 4; }
                          hipGetErrorString(e_));                                         \
   } while (0)
 
+// Raises a kernel's dynamic-LDS limit to `bytes`, once per (device, kernel): thread-safe, keyed by the current
+// device (the attribute belongs to the kernel's code object on that device).  Returns VLC_OK or VLC_ERR_HIP.
+int ensure_dynamic_lds(const void* kernel, int bytes);
+
 // RoPE inverse frequencies theta_i = base^(-2i/D), i < D/2, in double; passed to kernels by value.
 // axis[i]: which position id (0 temporal, 1 height, 2 width) drives frequency i (all 0: 1-D RoPE).
 struct RopeFreq {

@@ -88,6 +88,7 @@ class DevicePlans:
             k, count_override = np.full(L, 500, dtype=np.int32), None
         self.host = B.vlc_plan_token_indices(segs, L, k=k, count_override=count_override)
         self.reuse = B.vlc_plan_reuse_rows(segs, L, k=k, count_override=count_override)
+        self.next_row = B.vlc_plan_next_rows(segs, L, k=k, count_override=count_override)
         self.L = L
         self.total_slots = sum(s.length for s in segs)
         self.n_rows = [int(v) for v in self.host["n_rows"]]
@@ -151,31 +152,18 @@ def run_layer(shape_rec, weights: DeviceWeights, plan_rec, h_in, h_out, k_cache,
     B.vlc_layer_forward(shape_rec, weights.rec, plan_rec, h_in, h_out, k_cache, v_cache, ws.t, stream)
 
 
-def keeps_every_row(plans: DevicePlans, l: int) -> bool:
-    """True if layer l + 1 recomputes exactly the rows layer l did (its map is then 0..n-1: the planner's maps
-    are strictly increasing)."""
-    if l + 1 >= plans.L or plans.n_rows[l + 1] != plans.n_rows[l]:
-        return False
-    n = plans.n_rows[l]
-    return bool(np.array_equal(plans.host["map"][l + 1, :n], np.arange(n, dtype=plans.host["map"].dtype)))
-
-
 def chain_link(plans: DevicePlans, l: int):
     """How layer l can hand the input norm to layer l + 1: (False, None) if it cannot (last layer, or one of the
-    two has no rows), else (True, next_row) with next_row None if layer l + 1 keeps every row, else the int32
-    device list that gives each row of layer l its index among the rows of layer l + 1 (-1: dropped) - the
-    inverse of layer l + 1's map.  Built once per plan and kept."""
+    two has no rows), else (True, next_row) with next_row None if layer l + 1 keeps every row (same row count: its
+    rows are a subset), else the planner's int32 list (vlc_plan_next_rows) on the device.  Uploaded once per plan."""
     links = plans.__dict__.setdefault("_links", {})
     if l not in links:
         if l + 1 >= plans.L or plans.n_rows[l] == 0 or plans.n_rows[l + 1] == 0:
             links[l] = (False, None)
-        elif keeps_every_row(plans, l):
+        elif plans.n_rows[l + 1] == plans.n_rows[l]:
             links[l] = (True, None)
         else:
-            n, m = plans.n_rows[l], plans.n_rows[l + 1]
-            inv = np.full(n, -1, dtype=np.int32)
-            inv[plans.host["map"][l + 1, :m]] = np.arange(m, dtype=np.int32)
-            links[l] = (True, torch.from_numpy(inv).to(plans.dev[l]["slot"].device))
+            links[l] = (True, torch.from_numpy(plans.next_row[l, :plans.n_rows[l]].copy()).to(plans.dev[l]["slot"].device))
     return links[l]
 
 
@@ -198,8 +186,7 @@ def run_layers(shape_rec, weights: Sequence[DeviceWeights], plans: DevicePlans, 
 
 def plan_for(wl):
     """(k per layer | None, explicit leading-token count per layer | None) of a workload description,
-    through the library's planner.  A mean-rate budget of bp basis points over L layers is
-    bp * L / 20 grid steps of 0.002 (integer floor)."""
+    through the library's planner (the budget conversion included)."""
     L = wl.shape.L
     if wl.plan == "static":
         return np.full(L, wl.static_k, dtype=np.int32), None
@@ -207,4 +194,4 @@ def plan_for(wl):
         return None, np.full(L, wl.explicit_counts, dtype=np.int32)
     import vlc_synth as syn
     sens = syn.sensitivity_table(L, 150, 1)
-    return B.vlc_plan_layer_rates(sens, (int(wl.budget_bp) * L) // 20), None
+    return B.vlc_plan_layer_rates(sens, B.vlc_plan_budget_steps(int(wl.budget_bp), L)), None

@@ -108,6 +108,48 @@ def test_token_indices_bit_exact_vs_oracle(name):
         prev = slots
 
 
+@pytest.mark.parametrize("name", ["c1", "c3", "c4", "c5"])
+def test_next_rows_vs_oracle_selection(name):
+    """vlc_plan_next_rows: the index of every row of a layer among the rows of the layer below, from the ORACLE's
+    selection of both layers (position of a slot in the next layer's sorted slot list, -1 if it is not there)."""
+    wl = syn.make_workload(name)
+    L = wl.shape.L
+    k, explicit = plan_steps(wl)
+    segs = segments_of(wl.requests)
+    nxt = vlc.vlc_plan_next_rows(segs, L, k=k, count_override=explicit)
+    out = vlc.vlc_plan_token_indices(segs, L, k=k, count_override=explicit)
+
+    def slots_of(l):
+        return np.concatenate([req.kv_start + orc.select_slots(req.segments, counts_for(req, k, explicit, l))
+                               for req in wl.requests])
+    dropped = 0
+    for l in range(L):
+        cur = slots_of(l)
+        n = len(cur)
+        if l + 1 == L:
+            assert (nxt[l, :n] == -1).all()
+            continue
+        below = slots_of(l + 1)
+        at = np.searchsorted(below, cur)
+        hit = (at < len(below)) & (below[np.minimum(at, len(below) - 1)] == cur)
+        want = np.where(hit, at, -1)
+        np.testing.assert_array_equal(nxt[l, :n], want)
+        m = int(out["n_rows"][l + 1])
+        np.testing.assert_array_equal(nxt[l, out["map"][l + 1, :m]], np.arange(m))     # inverse of the map
+        dropped += int((want < 0).sum())
+    if name in ("c3", "c5"):
+        assert dropped > 0          # layer-aware rates: rows do fall away with depth
+
+
+def test_budget_steps_vs_oracle():
+    for bp, L in ((500, 28), (300, 80), (0, 5), (10000, 3), (37, 7), (1, 19), (9999, 80)):
+        assert vlc.vlc_plan_budget_steps(bp, L) == orc.budget_steps_from_mean_rate(bp, L)
+    assert vlc.vlc_plan_budget_steps(500, 28) == 700 and vlc.vlc_plan_budget_steps(300, 80) == 1200
+    for bad in ((-1, 5), (10001, 5), (100, 0)):
+        with pytest.raises(vlc.VlcError):
+            vlc.vlc_plan_budget_steps(*bad)
+
+
 @pytest.mark.parametrize("name", ["c1_q3", "c2_q3", "c3_q3"])
 def test_reuse_deltas_with_grid_position_ids(name):
     """3-axis ids: the runner hands the planner each run's first temporal id, so a reused image's shift is
