@@ -398,6 +398,22 @@ int vlc_first_token(const void* h, const int32_t* rows, int64_t n_req, int H, in
                     int64_t workspace_bytes, int dtype, void* stream);
 
 /*
+ * vlc_first_token for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as vlc_first_token without the
+ * workspace pair: the scratch (normed rows + partial choices) is a device array built into the library,
+ * vlc_first_token_noalloc_max_bytes() = 1 MiB per GPU, which every GPU the entry point is called on holds until
+ * the process ends.  The call allocates and frees nothing and enqueues the same four kernels on `stream`.
+ * Limit: vlc_first_token_workspace_bytes(H, n_req, dtype) must not exceed that size (bf16: 128 requests at
+ * H = 3584, 60 at H = 8192), else VLC_ERR_WORKSPACE and nothing is enqueued.  All calls on one GPU share the
+ * array: calls that may overlap on one GPU (different streams, several threads) race on it and must be ordered
+ * by the caller; nothing in it needs clearing between calls.
+ */
+int64_t vlc_first_token_noalloc_max_bytes(void);
+int vlc_first_token_noalloc(const void* h, const int32_t* rows, int64_t n_req, int H, int64_t vocab, float eps,
+                            const void* w_norm, const void* w_out, float* logits, int32_t* token, int dtype,
+                            void* stream);
+
+/*
  * Mean squared difference of two float arrays, the error measure of the layer-wise sensitivity
  * score S_i(r) = E MSE(z_orig, z_reuse) (Sec. 4.1, Eq. 5): out[0] = sum_i (a[i] - b[i])^2 / n,
  * accumulated in double.  a, b: device float [n]; out: device double [1]; workspace: device, at

@@ -88,6 +88,9 @@ def lib():
         L.vlc_first_token_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int]
         L.vlc_first_token.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int64, C.c_float] + \
                                      [C.c_void_p] * 5 + [C.c_int64, C.c_int, C.c_void_p]
+        L.vlc_first_token_noalloc_max_bytes.restype = C.c_int64
+        L.vlc_first_token_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int64, C.c_float] + \
+                                             [C.c_void_p] * 4 + [C.c_int, C.c_void_p]
         _LIB = L
     return _LIB
 
@@ -334,6 +337,17 @@ def vlc_first_token(h, rows, eps: float, w_norm, w_out, logits, token, workspace
     _check(lib().vlc_first_token(_dev(h), _dev(rows), n_req, H, vocab, float(eps), _dev(w_norm), _dev(w_out),
                                  _dev(logits), _dev(token), _dev(workspace),
                                  workspace.numel() * workspace.element_size(), _dtype_code(h), _stream(stream)))
+
+
+def vlc_first_token_noalloc_max_bytes() -> int:
+    return int(lib().vlc_first_token_noalloc_max_bytes())
+
+
+def vlc_first_token_noalloc(h, rows, eps: float, w_norm, w_out, logits, token, stream=None) -> None:
+    """vlc_first_token with the library's built-in scratch array instead of a workspace tensor."""
+    _check(lib().vlc_first_token_noalloc(_dev(h), _dev(rows), rows.numel(), h.shape[-1], w_out.shape[0], float(eps),
+                                         _dev(w_norm), _dev(w_out), _dev(logits), _dev(token), _dtype_code(h),
+                                         _stream(stream)))
 
 
 def vlc_mean_squared_error(a, b, out, workspace, stream=None) -> None:

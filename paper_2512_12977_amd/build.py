@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvlcache.so")
-SOURCES = ["api.cpp", "planner.cpp", "layer.cpp", "stream_kernels.hip", "gemm.hip", "attention.hip", "moe.hip"]
+SOURCES = ["api.cpp", "planner.cpp", "layer.cpp", "stream_kernels.hip", "gemm.hip", "attention.hip", "moe.hip", "noalloc.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -150,6 +150,22 @@ def test_budget_steps_vs_oracle():
             vlc.vlc_plan_budget_steps(*bad)
 
 
+def test_first_token_noalloc_argument_checks():
+    """The variant for callers that cannot allocate refuses what does not fit its built-in scratch before any
+    GPU work (no GPU needed): sizes beyond the array, bad dtype / shape; zero requests are a no-op."""
+    L = vlc.lib()
+    f = L.vlc_first_token_noalloc
+    cap = L.vlc_first_token_noalloc_max_bytes()
+    assert cap == 1 << 20
+    assert f(None, None, 0, 3584, 152064, 1e-6, None, None, None, None, vlc.VLC_BF16, None) == 0
+    assert f(None, None, 2, 3584, 152064, 1e-6, None, None, None, None, 9, None) == 3
+    assert f(None, None, -1, 3584, 152064, 1e-6, None, None, None, None, vlc.VLC_BF16, None) == 2
+    assert L.vlc_first_token_workspace_bytes(3584, 128, vlc.VLC_BF16) <= cap < L.vlc_first_token_workspace_bytes(3584, 129, vlc.VLC_BF16)
+    assert f(None, None, 129, 3584, 152064, 1e-6, None, None, None, None, vlc.VLC_BF16, None) == 5
+    assert "scratch" in vlc.last_error()
+    assert f(None, None, 61, 8192, 152064, 1e-6, None, None, None, None, vlc.VLC_BF16, None) == 5
+
+
 @pytest.mark.parametrize("name", ["c1_q3", "c2_q3", "c3_q3"])
 def test_reuse_deltas_with_grid_position_ids(name):
     """3-axis ids: the runner hands the planner each run's first temporal id, so a reused image's shift is
