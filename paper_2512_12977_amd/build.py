@@ -51,5 +51,36 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_host_check(verbose: bool = False) -> str:
+    """The library's sources and tests/sanitize/host_check.cpp as one executable whose HOST code is instrumented with
+    AddressSanitizer and UndefinedBehaviorSanitizer (device code is compiled as always and never runs: the program
+    only calls the planner and the argument checks).  Returns the path of the executable."""
+    hipcc = _hipcc()
+    objdir = os.path.join(HERE, "_build", "asan")
+    os.makedirs(objdir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1", "-g"] + san
+    srcs = [os.path.join(CSRC, s) for s in SOURCES] + [os.path.join(ROOT, "tests", "sanitize", "host_check.cpp")]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        r = subprocess.run([hipcc, *flags, "-c", src, "-o", obj], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc (sanitizers) failed on %s:\n%s" % (src, r.stderr))
+        return obj
+
+    with ThreadPoolExecutor(max_workers=6) as ex:
+        objs = list(ex.map(compile_one, srcs))
+    exe = os.path.join(objdir, "host_check")
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+                        "-o", exe, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link (sanitizers) failed:\n" + r.stderr)
+    if verbose:
+        print("built", exe)
+    return exe
+
+
 if __name__ == "__main__":
     build()
