@@ -250,6 +250,9 @@ def test_attention_long_context_bf16():
     (64, 64, [(700, [-1, 0, 0] + list(range(0, 700, 1)) + [5, 699, 3]), (300, list(range(300))), (1000, list(range(1000)))]),
     # two query heads per kv head, 128 rows per tile, ragged tail
     (32, 16, [(2500, list(range(2500))), (1723, list(range(0, 1723)))]),
+    # seven query heads per kv head (7B layout): 36 rows and 252 of 256 lanes per tile of the many-row kernel,
+    # rows of one request out of order, a zero-length row and single-key rows among them
+    (28, 4, [(1500, list(range(1500))), (1800, [-1, 0, 0, 1799, 2] + list(range(1800))), (1400, list(range(1399, -1, -1)))]),
 ])
 def test_attention_many_rows(Hq, Hkv, reqs):
     """Thousands of rows, several requests, more than 512 workgroups."""
