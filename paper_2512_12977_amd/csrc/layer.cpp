@@ -332,13 +332,11 @@ extern "C" int vlc_first_token(const void* h, const int32_t* rows, int64_t n_req
   hipStream_t st = (hipStream_t)stream;
   int rc = vlc::launch_rmsnorm(h, rows, w_norm, workspace, n_req, H, eps, dtype, st);
   if (rc) return rc;
-  // The output matrix is streamed once (vocab * H elements).  Up to 8 requests (bf16): a kernel that
-  // does exactly that, one matrix row per wavefront pass.  Otherwise the GEMM (128-row MFMA tiles).
-  if (dtype == VLC_BF16 && n_req <= 8 && (int64_t)n_req * H * 2 <= 159 * 1024)
-    rc = vlc::launch_rows_times_matrix_bf16(workspace, w_out, logits, n_req, vocab, H, st);
-  else
-    rc = vlc::launch_gemm(workspace, H, w_out, logits, vocab, n_req, vocab, H, vlc::EPI_BIAS_F32, nullptr, nullptr, 0,
-                          nullptr, dtype, nullptr, 0, st);
+  // The output matrix is streamed once (vocab * H elements) by the GEMM: 128-row MFMA tiles whose few real rows are
+  // the requests - HBM-bound whatever the count (a kernel that kept the rows in LDS and formed the products with
+  // dot instructions was slower from two requests on: every 16 bytes of the matrix cost a 16-byte LDS read per row).
+  rc = vlc::launch_gemm(workspace, H, w_out, logits, vocab, n_req, vocab, H, vlc::EPI_BIAS_F32, nullptr, nullptr, 0,
+                        nullptr, dtype, nullptr, 0, st);
   if (rc) return rc;
   char* part = static_cast<char*>(workspace) + align256(n_req * (int64_t)H * (dtype == VLC_BF16 ? 2 : 4));
   return vlc::launch_argmax_rows(logits, n_req, vocab, token, part, st);

@@ -453,59 +453,6 @@ __global__ __launch_bounds__(kThreads) void sum_residual_rmsnorm_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Scores of a few rows against a large matrix: out[r, v] = x[r, :] . W[v, :], bf16 inputs, float
-// accumulation (v_dot2c_f32_bf16: two products per instruction, no unpacking).  The matrix is read
-// exactly once, a wavefront streaming one whole row at a time (16 bytes per lane, consecutive
-// lanes consecutive chunks); the m <= MAXM rows of x sit in LDS.  HBM-bound: 2 bytes per matrix
-// element against 2 * m flops.
-// ---------------------------------------------------------------------------------------------
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-
-__device__ __forceinline__ float dot8_bf16(const uint4& a, const uint4& b, float acc) {
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), acc, false);
-  return acc;
-}
-
-constexpr int kGemvThreads = 512;
-
-template <int MAXM>
-__global__ __launch_bounds__(kGemvThreads) void rows_times_matrix_bf16_kernel(
-    const uint4* __restrict__ x, const uint4* __restrict__ W, float* __restrict__ out, int m, int chunks,
-    int64_t V) {
-  extern __shared__ uint4 xs[];                          // [m][chunks]
-  for (int i = threadIdx.x; i < m * chunks; i += kGemvThreads) xs[i] = x[i];
-  __syncthreads();
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = (int64_t)blockIdx.x * (kGemvThreads / 64) + (threadIdx.x >> 6);
-  const int64_t n_waves = (int64_t)gridDim.x * (kGemvThreads / 64);
-  for (int64_t v = wave; v < V; v += n_waves) {
-    const uint4* wr = W + v * chunks;
-    float acc[MAXM];
-#pragma unroll
-    for (int r = 0; r < MAXM; ++r) acc[r] = 0.f;
-#pragma unroll 4
-    for (int c = lane; c < chunks; c += 64) {
-      const uint4 w = wr[c];
-#pragma unroll
-      for (int r = 0; r < MAXM; ++r)
-        if (r < m) acc[r] = dot8_bf16(w, xs[r * chunks + c], acc[r]);
-    }
-#pragma unroll
-    for (int r = 0; r < MAXM; ++r) {
-      if (r < m) {                                       // m is uniform: every lane takes part in the exchange
-        float s = acc[r];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-        if (lane == 0) out[(int64_t)r * V + v] = s;
-      }
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
 // Greedy choice: index of the largest score of a row, the lowest index among equal scores; NaNs
 // never win.  Two passes: kArgmaxSlices workgroups per row each scan a slice of the columns (16
 // bytes per lane) and leave their best (value, index); one workgroup per row then picks among those.
@@ -714,26 +661,6 @@ int launch_sum_residual_rmsnorm(const float* partials, int splits, const void* r
   else return fail(VLC_ERR_SHAPE, "sum+residual+rmsnorm: H=%d too large", H);
 #undef VLC_LAUNCH_SRN
   VLC_CHECK_LAUNCH("sum_residual_rmsnorm");
-  return VLC_OK;
-}
-
-int launch_rows_times_matrix_bf16(const void* x, const void* W, float* out, int64_t m, int64_t V, int H,
-                                  hipStream_t st) {
-  if (m <= 0 || V <= 0) return VLC_OK;
-  if (m > 8 || H % 8) return fail(VLC_ERR_SHAPE, "rows x matrix: m=%lld (at most 8), H=%d", (long long)m, H);
-  const int chunks = H / 8;
-  const size_t lds = (size_t)m * chunks * 16;
-  if (lds > 160 * 1024 - 1024) return fail(VLC_ERR_SHAPE, "rows x matrix: %lld rows of %d do not fit LDS", (long long)m, H);
-  // two workgroups per CU where LDS allows, one otherwise; every wavefront loops over its rows
-  const int per_cu = lds <= 79 * 1024 ? 2 : 1;
-  int64_t blocks = 256 * per_cu;
-  const int64_t max_blocks = (V + kGemvThreads / 64 - 1) / (kGemvThreads / 64);
-  if (blocks > max_blocks) blocks = max_blocks;
-  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(rows_times_matrix_bf16_kernel<8>), 160 * 1024 - 1024))
-    return rc;
-  hipLaunchKernelGGL(rows_times_matrix_bf16_kernel<8>, dim3((unsigned)blocks), dim3(kGemvThreads), lds, st,
-                     (const uint4*)x, (const uint4*)W, out, (int)m, chunks, V);
-  VLC_CHECK_LAUNCH("rows_times_matrix_bf16");
   return VLC_OK;
 }
 

@@ -58,9 +58,6 @@ int launch_sum_residual_rmsnorm(const float* partials, int splits, const void* r
                                 const void* w, void* h, void* y, int64_t n, int H, float eps,
                                 hipStream_t st, const int32_t* ymap = nullptr);
 
-// out[r, v] = x[r, :] . W[v, :] for m <= 8 rows (bf16 x [m, H] and W [V, H], float out [m, V]); reads W once
-int launch_rows_times_matrix_bf16(const void* x, const void* W, float* out, int64_t m, int64_t V, int H,
-                                  hipStream_t st);
 // out[r] = index of the largest x[r, :] (lowest index among equals); x float [rows, cols], cols % 4 == 0;
 // ws: argmax_ws_bytes(rows) bytes of scratch (8-byte aligned)
 int launch_argmax_rows(const float* x, int64_t rows, int64_t cols, int32_t* out, void* ws, hipStream_t st);
