@@ -10,7 +10,8 @@ Procedure per sample (the three phases of Sec. 3.2):
      the leading floor(k T / 500) tokens of each image in layer i, which keep their fresh k, v
      (rows with a negative slot entry are computed but not stored); mean squared error of the
      answer rows' scores against the reference.
-The table this returns is what vlc_plan_layer_rates consumes.
+The table this returns is what vlc_plan_layer_rates_blocks consumes (a measured table has a flat first layer, from
+which the one-step greedy vlc_plan_layer_rates cannot start: it returns the all-zero plan).
 """
 from __future__ import annotations
 
@@ -165,13 +166,14 @@ def main() -> int:
     # the planner wants every grid column 0..G; columns between the measured steps are interpolated
     G = max(steps)
     table = np.stack([np.interp(np.arange(G + 1), steps, S[i]) for i in range(args.layers)])
-    budget = (args.budget_bp * args.layers) // 20
+    budget = B.vlc_plan_budget_steps(args.budget_bp, args.layers)
     plan = B.vlc_plan_layer_rates(table, budget)
     plan_runs = B.vlc_plan_layer_rates_blocks(table, budget)   # the first layer's scores are flat: it has to be carried
     print(json.dumps({"shape": args.shape, "layers": args.layers, "slots": smp["request"].S, "steps": steps,
                       "S": [[float("%.6g" % v) for v in row] for row in S], "passes": passes,
                       "ms_per_pass": round(dt_s * 1e3 / passes, 3), "budget_steps": budget,
-                      "plan_one_step_greedy": [int(v) for v in plan], "plan_runs_greedy": [int(v) for v in plan_runs]}))
+                      "plan": [int(v) for v in plan_runs], "planner": "vlc_plan_layer_rates_blocks",
+                      "plan_one_step_greedy_for_comparison": [int(v) for v in plan]}))
     return 0
 
 
