@@ -206,6 +206,50 @@ def hbm_kernels(hev, stream, iters=20):
     return out
 
 
+def machine_probes(hev, stream):
+    """What this machine delivers with nothing in the way: the register-only MFMA loop of vlc_probe_mfma_bf16 (operands of
+    random bits draw the power of a real GEMM, constant ones do not: the clock differs) and a 1 GiB row copy through
+    vlc_gather_rows (1 GiB read + 1 GiB written)."""
+    import torch
+    import paper_2512_12977_amd as vlc
+    dev = "cuda"
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    rnd = torch.randn((65536,), device=dev, generator=g).to(torch.bfloat16)          # 131072 bytes of bf16 values
+    const = torch.full((65536,), 1.0, device=dev, dtype=torch.bfloat16)
+    out = torch.empty((1024 * 512,), device=dev, dtype=torch.float32)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        ev = hev.create(2)
+        hev.record(ev[0], stream)
+        for _ in range(reps):
+            fn()
+        hev.record(ev[1], stream)
+        torch.cuda.synchronize()
+        t = hev.elapsed_ms(ev[0], ev[1]) / reps * 1e-3
+        hev.destroy(ev)
+        return t
+
+    res = {}
+    for name, ops in (("random_operands", rnd), ("constant_operands", const)):
+        for waves in (1, 2):
+            fl = [0.0]
+
+            def run():
+                fl[0] = vlc.vlc_probe_mfma_bf16(ops, out, 60000, waves)
+            t = timed(run, 3)
+            res["mfma_bf16_%s_%d_wave%s_per_simd_tflops" % (name, waves, "" if waves == 1 else "s")] = round(fl[0] / t / 1e12, 1)
+    rows_c, elems_c = 1 << 17, 4096                                                  # 2^17 rows x 8 KiB = 1 GiB
+    src_c = torch.ones((rows_c, elems_c), device=dev, dtype=torch.bfloat16)
+    dst_c = torch.empty_like(src_c)
+    idx_c = torch.arange(rows_c, device=dev, dtype=torch.int32)
+    t = timed(lambda: vlc.vlc_gather_rows(src_c, idx_c, dst_c), 5)
+    res["row_copy_1gib_gbs"] = round(2.0 * rows_c * elems_c * 2 / t / 1e9, 1)
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -233,6 +277,11 @@ def main() -> int:
     ap.add_argument("--hbm-kernels-only", action="store_true",
                     help="time only the three stand-alone HBM-bound entry points at the long-context batch sizes and "
                          "print their JSON (the command the kernel-trace / counter summaries of these kernels use)")
+    ap.add_argument("--probes-only", action="store_true",
+                    help="print only the machine probes (register-only MFMA loop, 1 GiB row copy)")
+    ap.add_argument("--no-probes", action="store_true", help="skip the machine probes")
+    ap.add_argument("--attention-only", action="store_true",
+                    help="time vlc_sparse_q_attention alone on the first layer's rows of the workload and print its JSON")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain row copy of 1 GiB through vlc_gather_rows "
                          "(identity index) so a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -254,8 +303,46 @@ def main() -> int:
     if args.hbm_kernels_only:
         print(json.dumps({"hbm_kernels": hbm_kernels(HipEvents(), torch.cuda.current_stream().cuda_stream or None)}))
         return 0
+    if args.probes_only:
+        print(json.dumps({"machine_probes": machine_probes(HipEvents(), torch.cuda.current_stream().cuda_stream or None)}))
+        return 0
     wl = syn.make_workload(args.workload)
     sh = wl.shape
+    if args.attention_only:
+        # the attention entry point alone, on the query rows and key ranges of the workload's first layer
+        hev0 = HipEvents()
+        st0 = torch.cuda.current_stream().cuda_stream or None
+        k0, ex0 = R.plan_for(wl)
+        p0 = R.DevicePlans(wl.requests, 1, k=None if k0 is None else k0[:1], count_override=None if ex0 is None else ex0[:1])
+        n0, d0 = p0.n_rows[0], p0.dev[0]
+        g0 = torch.Generator(device=dev)
+        g0.manual_seed(0)
+        tdt = R.torch_dtype(sh.dtype)
+        q0 = torch.randn((n0, sh.Hq, sh.D), device=dev, generator=g0).to(tdt)
+        kc0 = torch.randn((wl.total_slots, sh.Hkv, sh.D), device=dev, generator=g0).to(tdt)
+        vc0 = torch.randn((wl.total_slots, sh.Hkv, sh.D), device=dev, generator=g0).to(tdt)
+        o0 = torch.empty_like(q0)
+        pairs0 = float(p0.host["kv_len"][0, :n0].astype(np.float64).sum())
+
+        def att():
+            vlc.vlc_sparse_q_attention(q0, kc0, vc0, d0["kv_start"], d0["kv_len"], 1.0 / sh.D ** 0.5, o0)
+        for _ in range(2):
+            att()
+        torch.cuda.synchronize()
+        ev0 = hev0.create(2)
+        reps0 = args.steps or 10
+        hev0.record(ev0[0], st0)
+        for _ in range(reps0):
+            att()
+        hev0.record(ev0[1], st0)
+        torch.cuda.synchronize()
+        ms0 = hev0.elapsed_ms(ev0[0], ev0[1]) / reps0
+        fl0 = 4.0 * sh.Hq * sh.D * pairs0
+        print(json.dumps({"kernel": "vlc_sparse_q_attention", "workload": wl.name, "rows": n0, "row_key_pairs": pairs0,
+                          "avg_ms": round(ms0, 4), "tflops": round(fl0 / ms0 / 1e9, 1),
+                          "frac_of_bf16_mfma_peak": round(fl0 / ms0 / 1e9 / PEAK_BF16_TFLOPS, 4),
+                          "library": vlc.lib_path()}))
+        return 0
     L = sh.L
     dt = R.torch_dtype(sh.dtype)
     rec = R.make_shape(sh)
@@ -535,6 +622,11 @@ def main() -> int:
         torch.cuda.empty_cache()
         hbm = hbm_kernels(hev, stream)
 
+    probes = None
+    if not args.no_probes and sh.dtype == "bf16":
+        torch.cuda.empty_cache()
+        probes = machine_probes(hev, stream)
+
     if args.calibrate_copy:
         rows_c, elems_c = 1 << 17, 4096                      # 2^17 rows x 8 KiB = 1 GiB read + 1 GiB written
         src_c = torch.ones((rows_c, elems_c), device=dev, dtype=torch.bfloat16)
@@ -614,6 +706,7 @@ def main() -> int:
         "kernels_source": "HIP-event stage durations of a separate pass with all stage events (3 steps, same inputs); "
                           "fractions are achieved algorithmic rate / published peak (2.5 PFLOP/s dense bf16 MFMA, 8 TB/s HBM)",
         "hbm_kernels": hbm,
+        "machine_probes": probes,
         "stages": stages,
         "stages_source": "separate untimed pass with all stage events (3 steps); the timed steps record only the two events around the dominant stage of each layer",
         "cpu_baseline": cpu,

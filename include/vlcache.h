@@ -424,6 +424,18 @@ int64_t vlc_mean_squared_error_workspace_bytes(void);
 int vlc_mean_squared_error(const float* a, const float* b, int64_t n, double* out, void* workspace,
                            int64_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid, no part of the method: one launch of a register-only loop of v_mfma_f32_32x32x16_bf16 on every
+ * CU (one workgroup per CU, waves_per_simd wavefronts per SIMD, iters x 8 MFMAs per wavefront on operands read once
+ * from `operands`), against which bench.py sets the rates of the GEMM and attention kernels: with operands of random
+ * bits it shows what the matrix pipe delivers at the clock the chip sustains under a real kernel's power draw.
+ *   operands: device, >= 131072 bytes of bf16 data, 16-byte aligned; out: device float [>= CUs * 256 * waves_per_simd]
+ *   (written, content meaningless); flops: host, receives the flops of the launch.  Enqueues one kernel.
+ * Errors: VLC_ERR_NULL, VLC_ERR_SHAPE (iters <= 0, waves_per_simd not 1 or 2, buffers too small), VLC_ERR_HIP.
+ */
+int vlc_probe_mfma_bf16(const void* operands, int64_t operand_bytes, float* out, int64_t out_elems, int iters,
+                        int waves_per_simd, double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

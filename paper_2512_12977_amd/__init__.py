@@ -11,7 +11,7 @@ from .binding import (VlcError, lib, lib_path, last_error, VLC_F32, VLC_BF16,
                       vlc_layer_workspace_bytes, vlc_layer_workspace_layout, vlc_layer_forward,
                       vlc_layer_forward_timed, vlc_layer_forward_chained, LAYER_STAGES, vlc_first_token_workspace_bytes, vlc_first_token,
                       vlc_first_token_noalloc, vlc_first_token_noalloc_max_bytes,
-                      vlc_mean_squared_error, vlc_mean_squared_error_workspace_bytes,
+                      vlc_mean_squared_error, vlc_mean_squared_error_workspace_bytes, vlc_probe_mfma_bf16,
                       Segment, LayerShape, LayerWeights, LayerPlan, ShiftJob)
 
 __all__ = ["VlcError", "lib", "lib_path", "last_error", "VLC_F32", "VLC_BF16",
@@ -20,5 +20,5 @@ __all__ = ["VlcError", "lib", "lib_path", "last_error", "VLC_F32", "VLC_BF16",
            "vlc_layer_workspace_bytes", "vlc_layer_workspace_layout", "vlc_layer_forward", "vlc_layer_forward_timed", "vlc_layer_forward_chained", "LAYER_STAGES",
            "vlc_first_token_workspace_bytes", "vlc_first_token", "vlc_first_token_noalloc",
            "vlc_first_token_noalloc_max_bytes", "vlc_mean_squared_error",
-           "vlc_mean_squared_error_workspace_bytes",
+           "vlc_mean_squared_error_workspace_bytes", "vlc_probe_mfma_bf16",
            "Segment", "LayerShape", "LayerWeights", "LayerPlan", "ShiftJob"]

@@ -49,7 +49,9 @@ class LayerPlan(C.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libvlcache.so")
+    """libvlcache.so beside this file; VLC_LIB names another build of the same library (e.g. one made with
+    `python -m paper_2512_12977_amd.build --tag T --define D` for an ablation measurement)."""
+    return os.environ.get("VLC_LIB") or os.path.join(_HERE, "libvlcache.so")
 
 
 def lib():
@@ -88,6 +90,8 @@ def lib():
         L.vlc_first_token_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int]
         L.vlc_first_token.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int64, C.c_float] + \
                                      [C.c_void_p] * 5 + [C.c_int64, C.c_int, C.c_void_p]
+        L.vlc_probe_mfma_bf16.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p,
+                                          C.c_void_p]
         L.vlc_first_token_noalloc_max_bytes.restype = C.c_int64
         L.vlc_first_token_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int64, C.c_float] + \
                                              [C.c_void_p] * 4 + [C.c_int, C.c_void_p]
@@ -355,6 +359,14 @@ def vlc_mean_squared_error(a, b, out, workspace, stream=None) -> None:
     assert a.numel() == b.numel()
     _check(lib().vlc_mean_squared_error(_dev(a), _dev(b), a.numel(), _dev(out), _dev(workspace),
                                         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def vlc_probe_mfma_bf16(operands, out, iters: int, waves_per_simd: int, stream=None) -> float:
+    """Enqueues the register-only MFMA loop; returns the flops of the launch (time it with events)."""
+    flops = C.c_double()
+    _check(lib().vlc_probe_mfma_bf16(_dev(operands), operands.numel() * operands.element_size(), _dev(out), out.numel(),
+                                     int(iters), int(waves_per_simd), C.addressof(flops), _stream(stream)))
+    return float(flops.value)
 
 
 def vlc_mean_squared_error_workspace_bytes() -> int:

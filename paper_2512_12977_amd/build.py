@@ -5,12 +5,13 @@ import os
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
+from typing import Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvlcache.so")
-SOURCES = ["api.cpp", "planner.cpp", "layer.cpp", "stream_kernels.hip", "gemm.hip", "attention.hip", "moe.hip", "noalloc.hip"]
+SOURCES = ["api.cpp", "planner.cpp", "layer.cpp", "stream_kernels.hip", "gemm.hip", "attention.hip", "moe.hip", "noalloc.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -23,15 +24,21 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = True) -> str:
-    """Compile every source and link the shared library; returns its path."""
+def build(verbose: bool = True, tag: str = "", defines: Sequence[str] = ()) -> str:
+    """Compile every source and link the shared library; returns its path.  With a tag the result is
+    libvlcache_<tag>.so (beside the product library, which is left alone) built with the given -D macros:
+    the measurement variants of the kernels (see the VLC_ABLATE_* macros in csrc/attention.hip)."""
     hipcc = _hipcc()
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, "_build", tag) if tag else os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
+    lib = os.path.join(HERE, "libvlcache_%s.so" % tag) if tag else LIB
+    if defines and not tag:
+        raise ValueError("macros change what the kernels compute: give the variant a tag")
+    extra = ["-D" + d for d in defines]
 
     def compile_one(src: str) -> str:
         obj = os.path.join(objdir, src + ".o")
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
@@ -42,13 +49,13 @@ def build(verbose: bool = True) -> str:
 
     with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 def build_host_check(verbose: bool = False) -> str:
@@ -83,4 +90,9 @@ def build_host_check(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    build()
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--tag", default="", help="build libvlcache_<tag>.so instead of the product library")
+    ap.add_argument("--define", action="append", default=[], help="-D macro for a tagged measurement variant")
+    a = ap.parse_args()
+    build(tag=a.tag, defines=a.define)

@@ -89,6 +89,41 @@ __device__ __forceinline__ float pair_sum(float v) {
 
 #define VLC_ATT_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8) | (0 << 14))
 
+// Measurement variants (python -m paper_2512_12977_amd.build --tag T --define VLC_ABLATE_...): each takes one
+// ingredient of the key loop out - the results are wrong, only the timing is of interest - to show what that
+// ingredient costs: the K or V^T fragment reads from LDS, the exponentials, the S^T or the PV MFMAs.
+#ifdef VLC_ABLATE_K_READS
+#define VLC_ATT_KFRAG(expr_) (u32x4{(uint32_t)lane, 0x3c003c00u, (uint32_t)wave, 0x3c003c00u})
+#else
+#define VLC_ATT_KFRAG(expr_) (expr_)
+#endif
+#ifdef VLC_ABLATE_V_READS
+#define VLC_ATT_VFRAG(expr_) (s16x4{(short)lane, (short)0x3c00, (short)wave, (short)0x3c00})
+#else
+#define VLC_ATT_VFRAG(expr_) (expr_)
+#endif
+#ifdef VLC_ABLATE_EXP
+#define VLC_ATT_EXP2(x_) (x_)
+#else
+#define VLC_ATT_EXP2(x_) __builtin_amdgcn_exp2f(x_)
+#endif
+#if defined(VLC_ABLATE_QK_MFMA) || defined(VLC_ABLATE_PV_MFMA)
+__device__ __forceinline__ f32x16 ablated_mfma(bf16x8 a, bf16x8 b, f32x16 c) {   // one vector op that keeps the data flow
+  c[0] += (float)a[0] * (float)b[0];
+  return c;
+}
+#endif
+#ifdef VLC_ABLATE_QK_MFMA
+#define VLC_ATT_MFMA_QK(a_, b_, c_) ablated_mfma(a_, b_, c_)
+#else
+#define VLC_ATT_MFMA_QK(a_, b_, c_) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b_, c_, 0, 0, 0)
+#endif
+#ifdef VLC_ABLATE_PV_MFMA
+#define VLC_ATT_MFMA_PV(a_, b_, c_) ablated_mfma(a_, b_, c_)
+#else
+#define VLC_ATT_MFMA_PV(a_, b_, c_) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b_, c_, 0, 0, 0)
+#endif
+
 // SPLIT: blockIdx.z handles the z-th share of split_blocks key blocks of each run (the last share also what
 // lies beyond) and leaves an un-normalised partial (O as float, running max, running sum) for
 // attention_merge_kernel; a workgroup whose share starts beyond the tile's longest row leaves at once and writes
@@ -262,15 +297,14 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
       _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                         \
         _Pragma("unroll") for (int e = 0; e < 16; ++e) ST[rt][mt][e] = 0.f;                                    \
     u32x4 kf_[2];   /* fragment i+1 is read while fragment i is multiplied */                                  \
-    kf_[0] = *reinterpret_cast<const u32x4*>(sk_ + k_rd[0]);                                                   \
+    kf_[0] = VLC_ATT_KFRAG(*reinterpret_cast<const u32x4*>(sk_ + k_rd[0]));                                    \
     _Pragma("unroll") for (int i = 0; i < 2 * (ATT_D / 16); ++i) {                                             \
       const int mt = i / (ATT_D / 16), ks = i % (ATT_D / 16);                                                  \
       if (i + 1 < 2 * (ATT_D / 16))                                                                            \
-        kf_[(i + 1) & 1] = *reinterpret_cast<const u32x4*>(sk_ + k_rd[(i + 1) % (ATT_D / 16)] +                \
-                                                           ((i + 1) / (ATT_D / 16)) * (32 * 256));             \
+        kf_[(i + 1) & 1] = VLC_ATT_KFRAG(*reinterpret_cast<const u32x4*>(sk_ + k_rd[(i + 1) % (ATT_D / 16)] +  \
+                                                                         ((i + 1) / (ATT_D / 16)) * (32 * 256))); \
       _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                        \
-        ST[rt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf_[i & 1]), qf[rt][ks], \
-                                                             ST[rt][mt], 0, 0, 0);                             \
+        ST[rt][mt] = VLC_ATT_MFMA_QK(__builtin_bit_cast(bf16x8, kf_[i & 1]), qf[rt][ks], ST[rt][mt]);          \
     }                                                                                                          \
   }
     // keys of the block beyond a lane's visible range are masked (only where the block crosses it)
@@ -303,7 +337,7 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
       float psum_ = 0.f;                                                                                       \
       _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                         \
         _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                       \
-          const float p_ = __builtin_amdgcn_exp2f(fmaf(ST[rt][mt][j], scale_log2, -m_use_));                   \
+          const float p_ = VLC_ATT_EXP2(fmaf(ST[rt][mt][j], scale_log2, -m_use_));                             \
           ST[rt][mt][j] = p_;                                                                                  \
           psum_ += p_;                                                                                         \
         }                                                                                                      \
@@ -333,15 +367,15 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
     bf16x8 pf_[RT];                                                                                            \
     s16x4 vh_[2][2];   /* V^T fragment i+1 is read while fragment i is multiplied */                           \
     _Pragma("unroll") for (int r = 0; r < 2; ++r)                                                              \
-      vh_[0][r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(          \
-          const_cast<unsigned char*>(sv_) + v_rd[0] + (8 * r) * 256));                                         \
+      vh_[0][r] = VLC_ATT_VFRAG(__builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)( \
+          const_cast<unsigned char*>(sv_) + v_rd[0] + (8 * r) * 256)));                                        \
     _Pragma("unroll") for (int i = 0; i < 4 * (ATT_D / 32); ++i) {                                             \
       const int t = i / (ATT_D / 32), md = i % (ATT_D / 32);                                                   \
       if (i + 1 < 4 * (ATT_D / 32)) {                                                                          \
         const int t1 = (i + 1) / (ATT_D / 32), md1 = (i + 1) % (ATT_D / 32);                                   \
         _Pragma("unroll") for (int r = 0; r < 2; ++r)                                                          \
-          vh_[(i + 1) & 1][r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)( \
-              const_cast<unsigned char*>(sv_) + v_rd[md1] + (16 * t1 + 8 * r) * 256));                         \
+          vh_[(i + 1) & 1][r] = VLC_ATT_VFRAG(__builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)( \
+              const_cast<unsigned char*>(sv_) + v_rd[md1] + (16 * t1 + 8 * r) * 256)));                        \
       }                                                                                                        \
       if (md == 0) {                                                                                           \
         _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                      \
@@ -354,8 +388,7 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
       }                                                                                                        \
       const s16x8 vv_ = __builtin_shufflevector(vh_[i & 1][0], vh_[i & 1][1], 0, 1, 2, 3, 4, 5, 6, 7);         \
       _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                        \
-        o_acc[rt][md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv_), pf_[rt],      \
-                                                                o_acc[rt][md], 0, 0, 0);                       \
+        o_acc[rt][md] = VLC_ATT_MFMA_PV(__builtin_bit_cast(bf16x8, vv_), pf_[rt], o_acc[rt][md]);              \
     }                                                                                                          \
   }
     // One key block j (S^T already in CUR): fetch ahead, start the next block's S^T into NXT (its MFMAs

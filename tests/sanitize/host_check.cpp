@@ -153,6 +153,9 @@ static int errors() {
   rc.push_back(vlc_first_token_noalloc(p, i32, 0, 3584, 152064, 1e-6f, p, p, (float*)p, i32, VLC_BF16, nullptr));
   rc.push_back(vlc_mean_squared_error((const float*)p, (const float*)p, 0, (double*)p, p, 8192, nullptr));
   rc.push_back(vlc_mean_squared_error((const float*)p, (const float*)p, 5, (double*)p, p, 8, nullptr));
+  double fl = 0;
+  rc.push_back(vlc_probe_mfma_bf16(nullptr, 0, nullptr, 0, 10, 1, &fl, nullptr));
+  rc.push_back(vlc_probe_mfma_bf16(p, 4096, (float*)p, 1024, 10, 3, &fl, nullptr));
   printf("errors");
   for (int v : rc) printf(" %d", v);
   printf("\n%s\n", vlc_last_error());

@@ -43,7 +43,8 @@ def test_refused_calls_under_sanitizers(host_check):
             1, 1, 1, 0, N,                    # workspace queries (as booleans), layout ok, layout NULL
             F, N, N, S, W, N, S,              # layer: n > n_in, NULL lists, NULL weights, alias, workspace, events, flag
             S, W, W, 0,                       # first token: H, workspace; no-alloc: beyond the array, no requests
-            S, W]                             # mean squared error: n = 0, workspace
+            S, W,                             # mean squared error: n = 0, workspace
+            N, S]                             # MFMA probe: NULL, waves per SIMD
     assert codes == want
 
 
