@@ -91,7 +91,8 @@ __device__ __forceinline__ float pair_sum(float v) {
 
 // Measurement variants (python -m paper_2512_12977_amd.build --tag T --define VLC_ABLATE_...): each takes one
 // ingredient of the key loop out - the results are wrong, only the timing is of interest - to show what that
-// ingredient costs: the K or V^T fragment reads from LDS, the exponentials, the S^T or the PV MFMAs.
+// ingredient costs: the K or V^T fragment reads from LDS (all or every other one), the exponentials, the scale-and-subtract
+// in front of them, the S^T or the PV MFMAs, the workgroup barrier of a key block.
 #ifdef VLC_ABLATE_K_READS
 #define VLC_ATT_KFRAG(expr_) (u32x4{(uint32_t)lane, 0x3c003c00u, (uint32_t)wave, 0x3c003c00u})
 #else
@@ -106,6 +107,23 @@ __device__ __forceinline__ float pair_sum(float v) {
 #define VLC_ATT_EXP2(x_) (x_)
 #else
 #define VLC_ATT_EXP2(x_) __builtin_amdgcn_exp2f(x_)
+#endif
+#ifdef VLC_ABLATE_SOFTMAX_FMA   // the exponent's argument without the scale-and-subtract (one vector op per score less)
+#define VLC_ATT_EXP_ARG(s_, scale_, m_) (s_)
+#else
+#define VLC_ATT_EXP_ARG(s_, scale_, m_) fmaf(s_, scale_, -(m_))
+#endif
+#ifdef VLC_ABLATE_HALF_READS    // every other K / V^T fragment read left out: each fragment read feeds two MFMAs
+#define VLC_ATT_READ_NOW(i_) (((i_) & 1) == 0)
+#define VLC_ATT_FRAG_BUF(i_) (((i_) >> 1) & 1)
+#else
+#define VLC_ATT_READ_NOW(i_) true
+#define VLC_ATT_FRAG_BUF(i_) ((i_) & 1)
+#endif
+#ifdef VLC_ABLATE_BLOCK_BARRIER // no workgroup barrier per key block (LDS addresses do not depend on what is read)
+#define VLC_ATT_BLOCK_BARRIER()
+#else
+#define VLC_ATT_BLOCK_BARRIER() __syncthreads()
 #endif
 #if defined(VLC_ABLATE_QK_MFMA) || defined(VLC_ABLATE_PV_MFMA)
 __device__ __forceinline__ f32x16 ablated_mfma(bf16x8 a, bf16x8 b, f32x16 c) {   // one vector op that keeps the data flow
@@ -300,11 +318,11 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
     kf_[0] = VLC_ATT_KFRAG(*reinterpret_cast<const u32x4*>(sk_ + k_rd[0]));                                    \
     _Pragma("unroll") for (int i = 0; i < 2 * (ATT_D / 16); ++i) {                                             \
       const int mt = i / (ATT_D / 16), ks = i % (ATT_D / 16);                                                  \
-      if (i + 1 < 2 * (ATT_D / 16))                                                                            \
-        kf_[(i + 1) & 1] = VLC_ATT_KFRAG(*reinterpret_cast<const u32x4*>(sk_ + k_rd[(i + 1) % (ATT_D / 16)] +  \
+      if (i + 1 < 2 * (ATT_D / 16) && VLC_ATT_READ_NOW(i + 1))                                                 \
+        kf_[VLC_ATT_FRAG_BUF(i + 1)] = VLC_ATT_KFRAG(*reinterpret_cast<const u32x4*>(sk_ + k_rd[(i + 1) % (ATT_D / 16)] +  \
                                                                          ((i + 1) / (ATT_D / 16)) * (32 * 256))); \
       _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                        \
-        ST[rt][mt] = VLC_ATT_MFMA_QK(__builtin_bit_cast(bf16x8, kf_[i & 1]), qf[rt][ks], ST[rt][mt]);          \
+        ST[rt][mt] = VLC_ATT_MFMA_QK(__builtin_bit_cast(bf16x8, kf_[VLC_ATT_FRAG_BUF(i)]), qf[rt][ks], ST[rt][mt]); \
     }                                                                                                          \
   }
     // keys of the block beyond a lane's visible range are masked (only where the block crosses it)
@@ -337,7 +355,7 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
       float psum_ = 0.f;                                                                                       \
       _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                                         \
         _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                       \
-          const float p_ = VLC_ATT_EXP2(fmaf(ST[rt][mt][j], scale_log2, -m_use_));                             \
+          const float p_ = VLC_ATT_EXP2(VLC_ATT_EXP_ARG(ST[rt][mt][j], scale_log2, m_use_));                             \
           ST[rt][mt][j] = p_;                                                                                  \
           psum_ += p_;                                                                                         \
         }                                                                                                      \
@@ -371,10 +389,10 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
           const_cast<unsigned char*>(sv_) + v_rd[0] + (8 * r) * 256)));                                        \
     _Pragma("unroll") for (int i = 0; i < 4 * (ATT_D / 32); ++i) {                                             \
       const int t = i / (ATT_D / 32), md = i % (ATT_D / 32);                                                   \
-      if (i + 1 < 4 * (ATT_D / 32)) {                                                                          \
+      if (i + 1 < 4 * (ATT_D / 32) && VLC_ATT_READ_NOW(i + 1)) {                                               \
         const int t1 = (i + 1) / (ATT_D / 32), md1 = (i + 1) % (ATT_D / 32);                                   \
         _Pragma("unroll") for (int r = 0; r < 2; ++r)                                                          \
-          vh_[(i + 1) & 1][r] = VLC_ATT_VFRAG(__builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)( \
+          vh_[VLC_ATT_FRAG_BUF(i + 1)][r] = VLC_ATT_VFRAG(__builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)( \
               const_cast<unsigned char*>(sv_) + v_rd[md1] + (16 * t1 + 8 * r) * 256)));                        \
       }                                                                                                        \
       if (md == 0) {                                                                                           \
@@ -386,7 +404,7 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
             pf_[rt][2 * e + 1] = pb_[1];                                                                       \
           }                                                                                                    \
       }                                                                                                        \
-      const s16x8 vv_ = __builtin_shufflevector(vh_[i & 1][0], vh_[i & 1][1], 0, 1, 2, 3, 4, 5, 6, 7);         \
+      const s16x8 vv_ = __builtin_shufflevector(vh_[VLC_ATT_FRAG_BUF(i)][0], vh_[VLC_ATT_FRAG_BUF(i)][1], 0, 1, 2, 3, 4, 5, 6, 7); \
       _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                        \
         o_acc[rt][md] = VLC_ATT_MFMA_PV(__builtin_bit_cast(bf16x8, vv_), pf_[rt], o_acc[rt][md]);              \
     }                                                                                                          \
@@ -413,7 +431,7 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
       __builtin_amdgcn_s_setprio(0);                                                                           \
     }                                                                                                          \
     VLC_ATT_WAIT_VM0();   /* this wavefront's shares of the tiles fetched above have landed */                 \
-    __syncthreads();                                                                                           \
+    VLC_ATT_BLOCK_BARRIER();                                                                                   \
   }
 
     __syncthreads();                 // the rings are free (previous run finished reading them)
