@@ -29,7 +29,8 @@ rope_shift(d) o rope_shift(-d) = id and composition with direct RoPE; brute-forc
 dense attention on tiny inputs; planner closed forms and exhaustive optimum; the first-token
 head against a Hugging Face Qwen2 causal LM with the same weights, and closed forms.
 Parity unpinned: agreement with the authors' own rate lists / prototype numerics
-(their code and tables are not available).
+(their code and tables are not available); the sensitivity measurement (profile_prefill,
+sensitivity_profile) is pinned by invariants only - the paper prints no value of S_i(r).
 """
 from __future__ import annotations
 
