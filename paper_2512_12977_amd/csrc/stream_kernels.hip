@@ -74,48 +74,38 @@ __device__ __forceinline__ void rope_sincos(double inv_freq, int delta, float* s
 // gather / scatter of whole rows in 16-byte chunks
 // ---------------------------------------------------------------------------------------------
 // dst chunk (i, c) = src chunk (src_idx ? src_idx[i] : i, c) written at row (dst_idx ? dst_idx[i] : i).
-// Row strides are given in chunks.  Each thread moves UNROLL chunks, all loads issued first
-// (plain cached accesses: non-temporal ones measured half the rate here).  blockIdx.y selects one of up to two
+// Row strides are given in chunks.  Plain cached accesses (non-temporal ones measured half the rate
+// here).  blockIdx.y selects one of up to two
 // (src, dst) pairs that share the index arrays (K and V of a scatter go in one launch).
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-template <int UNROLL>
-__global__ __launch_bounds__(kThreads) void copy_rows_kernel(const u32x4* __restrict__ src0,
-                                                             const u32x4* __restrict__ src1,
-                                                             u32x4* __restrict__ dst0, u32x4* __restrict__ dst1,
-                                                             int64_t src_stride,
-                                                             const int32_t* __restrict__ src_idx,
-                                                             int64_t dst_stride,
-                                                             const int32_t* __restrict__ dst_idx, uint32_t total,
-                                                             uint32_t chunks_per_row) {
+constexpr int kCopyThreads = 256;
+
+// One 16-byte chunk per thread.  (Several chunks per thread are slower: a 1 GiB copy runs at 5.8 TB/s with four,
+// at 6.35 TB/s with one, at half that with eight - short-lived threads keep more loads in flight.)
+__global__ __launch_bounds__(kCopyThreads) void copy_rows_kernel(const u32x4* __restrict__ src0,
+                                                                 const u32x4* __restrict__ src1,
+                                                                 u32x4* __restrict__ dst0, u32x4* __restrict__ dst1,
+                                                                 int64_t src_stride,
+                                                                 const int32_t* __restrict__ src_idx,
+                                                                 int64_t dst_stride,
+                                                                 const int32_t* __restrict__ dst_idx, uint32_t total,
+                                                                 uint32_t chunks_per_row) {
   const u32x4* __restrict__ src = blockIdx.y ? src1 : src0;
   u32x4* __restrict__ dst = blockIdx.y ? dst1 : dst0;
-  const uint32_t base = blockIdx.x * (uint32_t)(kThreads * UNROLL) + threadIdx.x;
-  u32x4 v[UNROLL];
-  int64_t off[UNROLL];
-#pragma unroll
-  for (int u = 0; u < UNROLL; ++u) {
-    const uint32_t id = base + u * kThreads;
-    off[u] = -1;
-    if (id < total) {
-      const uint32_t row = id / chunks_per_row;
-      const uint32_t c = id - row * chunks_per_row;
-      const int64_t srow = src_idx ? (int64_t)src_idx[row] : (int64_t)row;
-      const int64_t drow = dst_idx ? (int64_t)dst_idx[row] : (int64_t)row;
-      v[u] = src[srow * src_stride + c];
-      off[u] = drow * dst_stride + c;
-    }
-  }
-#pragma unroll
-  for (int u = 0; u < UNROLL; ++u)
-    if (off[u] >= 0) dst[off[u]] = v[u];
+  const uint32_t id = blockIdx.x * (uint32_t)kCopyThreads + threadIdx.x;
+  if (id >= total) return;
+  const uint32_t row = id / chunks_per_row;
+  const uint32_t c = id - row * chunks_per_row;
+  const int64_t srow = src_idx ? (int64_t)src_idx[row] : (int64_t)row;
+  const int64_t drow = dst_idx ? (int64_t)dst_idx[row] : (int64_t)row;
+  dst[drow * dst_stride + c] = src[srow * src_stride + c];
 }
 
 // One or two row copies (same row count, strides and index arrays) in a single launch.
 int copy_rows(const void* src0, const void* src1, int64_t src_stride_bytes, const int32_t* src_idx, void* dst0,
               void* dst1, int64_t dst_stride_bytes, const int32_t* dst_idx, int64_t n, int64_t row_bytes,
               hipStream_t st, const char* name) {
-  constexpr int UNROLL = 4;
   const int64_t cpr = row_bytes / 16;
   if (n <= 0 || cpr <= 0) return VLC_OK;
   // keep flat chunk ids within 31 bits: slice the row range if needed
@@ -123,13 +113,13 @@ int copy_rows(const void* src0, const void* src1, int64_t src_stride_bytes, cons
   for (int64_t r0 = 0; r0 < n; r0 += rows_per_launch) {
     const int64_t rows = (n - r0 < rows_per_launch) ? n - r0 : rows_per_launch;
     const uint32_t total = (uint32_t)(rows * cpr);
-    const uint32_t blocks = (total + kThreads * UNROLL - 1) / (kThreads * UNROLL);
+    const uint32_t blocks = (total + kCopyThreads - 1) / kCopyThreads;
     const int64_t so = src_idx ? 0 : r0 * src_stride_bytes, dof = dst_idx ? 0 : r0 * dst_stride_bytes;
     const u32x4* s0 = reinterpret_cast<const u32x4*>(static_cast<const char*>(src0) + so);
     u32x4* d0 = reinterpret_cast<u32x4*>(static_cast<char*>(dst0) + dof);
     const u32x4* s1 = src1 ? reinterpret_cast<const u32x4*>(static_cast<const char*>(src1) + so) : nullptr;
     u32x4* d1 = dst1 ? reinterpret_cast<u32x4*>(static_cast<char*>(dst1) + dof) : nullptr;
-    hipLaunchKernelGGL(copy_rows_kernel<UNROLL>, dim3(blocks, src1 ? 2 : 1), dim3(kThreads), 0, st, s0, s1, d0, d1,
+    hipLaunchKernelGGL(copy_rows_kernel, dim3(blocks, src1 ? 2 : 1), dim3(kCopyThreads), 0, st, s0, s1, d0, d1,
                        src_stride_bytes / 16, src_idx ? src_idx + r0 : nullptr, dst_stride_bytes / 16,
                        dst_idx ? dst_idx + r0 : nullptr, total, (uint32_t)cpr);
     VLC_CHECK_LAUNCH(name);
@@ -140,57 +130,52 @@ int copy_rows(const void* src0, const void* src1, int64_t src_stride_bytes, cons
 // ---------------------------------------------------------------------------------------------
 // RoPE shift of reused keys + copy of reused values (Sec. 4.2)
 // ---------------------------------------------------------------------------------------------
-// One thread owns, for one token, VEC rotation pairs (a 16-byte chunk of the low half and the
-// matching chunk of the high half) and walks over the Hkv heads, so each sine/cosine is computed
-// once per token and reused for every head.  Consecutive lanes cover consecutive chunks of a row.
+// One thread owns VEC rotation pairs of one head of one token: a 16-byte chunk of the low half and the matching
+// chunk of the high half of the key, and the same two chunks of the value.  Consecutive lanes cover consecutive
+// chunks, then the heads of a token, then tokens, so a wavefront touches whole 128-byte lines.  (Threads that walk
+// over all heads of a token, to compute each sine/cosine once, are 3-5 % slower: the kernel is bound by memory
+// parallelism, and four short-lived threads keep more loads in flight than one long one.)
 template <typename T, int D>
 __device__ __forceinline__ void rope_shift_thread(
     int64_t gid, const uint4* k_src, const uint4* v_src, uint4* k_dst, uint4* v_dst,   // may alias (in-place use)
     const int32_t* __restrict__ src_row, const int32_t* __restrict__ dst_row,
-    const int32_t* __restrict__ delta, int64_t n_tok, int Hkv, int head_parts, const RopeFreq& freq) {
+    const int32_t* __restrict__ delta, int64_t n_tok, int Hkv, const RopeFreq& freq) {
   constexpr int VEC = Chunk<T>::VEC;
   constexpr int CH = (D / 2) / VEC;                  // chunks per half head
   constexpr int HEAD_CHUNKS = 2 * CH;                // chunks per head
   const int64_t t = gid / CH;
   const int c = (int)(gid - t * CH);
-  const int64_t tok = t / head_parts;                // head_parts > 1: the heads of a token are shared out
-  const int hpt = Hkv / head_parts;                  // heads per thread (head_parts divides Hkv)
-  const int h0 = (int)(t - tok * head_parts) * hpt;
+  const int64_t tok = t / Hkv;
+  const int h = (int)(t - tok * Hkv);
   if (tok >= n_tok) return;
   const int64_t srow = src_row[tok], drow = dst_row[tok];
   const int d = delta[tok];
+  const int64_t row_chunks = (int64_t)Hkv * HEAD_CHUNKS;
+  const int64_t so = srow * row_chunks + h * HEAD_CHUNKS + c, dof = drow * row_chunks + h * HEAD_CHUNKS + c;
+  const bool do_v = v_src != nullptr && v_dst != nullptr;
+  const uint4 lo_r = k_src[so];
+  const uint4 hi_r = k_src[so + CH];
+  uint4 v_lo, v_hi;
+  if (do_v) {
+    v_lo = v_src[so];
+    v_hi = v_src[so + CH];
+  }
   float sn[VEC], cs[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) rope_sincos<sizeof(T) == 2>(freq.inv_freq[c * VEC + i], d, &sn[i], &cs[i]);
-  const int64_t row_chunks = (int64_t)Hkv * HEAD_CHUNKS;
-  const uint4* ks = k_src + srow * row_chunks + c;
-  uint4* kd = k_dst + drow * row_chunks + c;
-  const bool do_v = v_src != nullptr && v_dst != nullptr;
-  const uint4* vs = do_v ? v_src + srow * row_chunks + c : nullptr;
-  uint4* vd = do_v ? v_dst + drow * row_chunks + c : nullptr;
-#pragma unroll 4
-  for (int h = h0; h < h0 + hpt; ++h) {
-    const uint4 lo_r = ks[h * HEAD_CHUNKS];
-    const uint4 hi_r = ks[h * HEAD_CHUNKS + CH];
-    uint4 v_lo, v_hi;
-    if (do_v) {
-      v_lo = vs[h * HEAD_CHUNKS];
-      v_hi = vs[h * HEAD_CHUNKS + CH];
-    }
-    float lo[VEC], hi[VEC], olo[VEC], ohi[VEC];
-    Chunk<T>::unpack(lo_r, lo);
-    Chunk<T>::unpack(hi_r, hi);
+  float lo[VEC], hi[VEC], olo[VEC], ohi[VEC];
+  Chunk<T>::unpack(lo_r, lo);
+  Chunk<T>::unpack(hi_r, hi);
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) {
-      olo[i] = lo[i] * cs[i] - hi[i] * sn[i];
-      ohi[i] = hi[i] * cs[i] + lo[i] * sn[i];
-    }
-    kd[h * HEAD_CHUNKS] = Chunk<T>::pack(olo);
-    kd[h * HEAD_CHUNKS + CH] = Chunk<T>::pack(ohi);
-    if (do_v) {
-      vd[h * HEAD_CHUNKS] = v_lo;
-      vd[h * HEAD_CHUNKS + CH] = v_hi;
-    }
+  for (int i = 0; i < VEC; ++i) {
+    olo[i] = lo[i] * cs[i] - hi[i] * sn[i];
+    ohi[i] = hi[i] * cs[i] + lo[i] * sn[i];
+  }
+  k_dst[dof] = Chunk<T>::pack(olo);
+  k_dst[dof + CH] = Chunk<T>::pack(ohi);
+  if (do_v) {
+    v_dst[dof] = v_lo;
+    v_dst[dof + CH] = v_hi;
   }
 }
 
@@ -198,25 +183,25 @@ template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void rope_shift_kernel(
     const uint4* k_src, const uint4* v_src, uint4* k_dst, uint4* v_dst,
     const int32_t* __restrict__ src_row, const int32_t* __restrict__ dst_row,
-    const int32_t* __restrict__ delta, int64_t n_tok, int Hkv, int head_parts, RopeFreq freq) {
+    const int32_t* __restrict__ delta, int64_t n_tok, int Hkv, RopeFreq freq) {
   rope_shift_thread<T, D>((int64_t)blockIdx.x * kThreads + threadIdx.x, k_src, v_src, k_dst, v_dst, src_row, dst_row,
-                          delta, n_tok, Hkv, head_parts, freq);
+                          delta, n_tok, Hkv, freq);
 }
 
 // The same for a table of jobs (one per layer): blockIdx.y picks the job, blocks beyond its token count leave.
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void rope_shift_jobs_kernel(const vlc_shift_job* __restrict__ jobs, int Hkv,
-                                                                   int head_parts, RopeFreq freq) {
+                                                                   RopeFreq freq) {
   const vlc_shift_job j = jobs[blockIdx.y];
   rope_shift_thread<T, D>((int64_t)blockIdx.x * kThreads + threadIdx.x, (const uint4*)j.k_src, (const uint4*)j.v_src,
-                          (uint4*)j.k_dst, (uint4*)j.v_dst, j.src_row, j.dst_row, j.delta, j.n_tok, Hkv, head_parts,
-                          freq);
+                          (uint4*)j.k_dst, (uint4*)j.v_dst, j.src_row, j.dst_row, j.delta, j.n_tok, Hkv, freq);
 }
 
 constexpr int kMaxSplits = 8;   // the GEMM never splits the k range into more parts
 
-// One thread owns VEC rotation pairs of up to HB consecutive heads of one row of the fused q|k|v
-// matrix (unrounded float).  Head index < Hq: query, rotated, written to q_out.  < Hq+Hkv: key,
+// One thread owns VEC rotation pairs of one head of one row of the fused q|k|v matrix (unrounded float; several
+// heads per thread, to reuse each sine/cosine, measured 9 % slower at 18944 rows: memory parallelism counts, the
+// arithmetic does not).  Head index < Hq: query, rotated, written to q_out.  < Hq+Hkv: key,
 // rotated and written to its cache slot (the blend).  Otherwise: value, written to its cache slot.
 // Outputs are rounded to the storage type once, after the rotation.
 // SUM: the projection was left as `splits` float partial matrices (split_stride elements apart,
@@ -225,12 +210,12 @@ constexpr int kMaxSplits = 8;   // the GEMM never splits the k range into more p
 // pos3 (optional): per-axis position ids [n, 3]; frequency i then takes the id of axis freq.axis[i].
 // w_qn / w_kn (optional, [D]): RMSNorm over every q / k head before the rotation (a head's D values
 // are spread over CH consecutive lanes, which exchange their partial sums of squares).
-template <typename T, int D, int HB, bool SUM>
+template <typename T, int D, bool SUM>
 __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
     const float* __restrict__ qkv, int splits, int64_t split_stride, const uint16_t* __restrict__ bias,
     float* __restrict__ qkv_sum, const int32_t* __restrict__ pos, const int32_t* __restrict__ pos3,
     const T* __restrict__ w_qn, const T* __restrict__ w_kn, float eps, const int32_t* __restrict__ slot,
-    int64_t n, int Hq, int Hkv, int head_blocks, RopeFreq freq, uint4* __restrict__ q_out,
+    int64_t n, int Hq, int Hkv, RopeFreq freq, uint4* __restrict__ q_out,
     uint4* __restrict__ k_cache, uint4* __restrict__ v_cache) {
   constexpr int VEC = Chunk<T>::VEC;
   constexpr int CH = (D / 2) / VEC;
@@ -238,10 +223,10 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
   const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const int c = (int)(gid % CH);
   const int64_t t = gid / CH;
-  const int hb = (int)(t % head_blocks);
-  const int64_t row = t / head_blocks;
-  if (row >= n) return;
   const int heads = Hq + 2 * Hkv;
+  const int h = (int)(t % heads);
+  const int64_t row = t / heads;
+  if (row >= n) return;
   float sn[VEC], cs[VEC];
   if (pos3) {
     const int p3[3] = {pos3[3 * row], pos3[3 * row + 1], pos3[3 * row + 2]};
@@ -258,10 +243,7 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
   const int row_slot = slot[row];
   const bool keep_kv = row_slot >= 0;      // a negative slot: the row is computed, its k and v are not stored
   const int64_t dst = (int64_t)(keep_kv ? row_slot : 0) * ((int64_t)Hkv * HEAD_CHUNKS) + c;
-#pragma unroll
-  for (int j = 0; j < HB; ++j) {
-    const int h = hb * HB + j;
-    if (h >= heads) break;
+  {
     float lo[VEC], hi[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; i += 4) {
@@ -301,7 +283,7 @@ __global__ __launch_bounds__(kThreads) void rope_qk_scatter_kernel(
         v_cache[dst + (h - Hq - Hkv) * HEAD_CHUNKS] = Chunk<T>::pack(lo);
         v_cache[dst + (h - Hq - Hkv) * HEAD_CHUNKS + CH] = Chunk<T>::pack(hi);
       }
-      continue;
+      return;
     }
     if (w_qn) {   // RMSNorm over the head, float; every lane of the head's CH-lane group is here
       float ss = 0.f;
@@ -538,14 +520,12 @@ int launch_rope_shift(const void* k_src, const void* v_src, void* k_dst, void* v
                       int64_t n_tok, int Hkv, int D, const RopeFreq& f, int dtype, hipStream_t st) {
   if (n_tok <= 0) return VLC_OK;
   const int vec = dtype == VLC_BF16 ? 8 : 4;
-  // few tokens: one head per thread, so that the grid still covers the chip
-  const int head_parts = n_tok * ((D / 2) / vec) < (int64_t)kThreads * 1024 ? Hkv : 1;
-  const int64_t threads = n_tok * head_parts * ((D / 2) / vec);
+  const int64_t threads = n_tok * Hkv * ((D / 2) / vec);
   const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads));
 #define VLC_LAUNCH_SHIFT(T, DD)                                                                       \
   hipLaunchKernelGGL((rope_shift_kernel<T, DD>), grid, dim3(kThreads), 0, st, (const uint4*)k_src,    \
                      (const uint4*)v_src, (uint4*)k_dst, (uint4*)v_dst, src_row, dst_row, delta,      \
-                     n_tok, Hkv, head_parts, f)
+                     n_tok, Hkv, f)
   if (dtype == VLC_BF16 && D == 128) VLC_LAUNCH_SHIFT(uint16_t, 128);
   else if (dtype == VLC_BF16 && D == 64) VLC_LAUNCH_SHIFT(uint16_t, 64);
   else if (dtype == VLC_F32 && D == 128) VLC_LAUNCH_SHIFT(float, 128);
@@ -560,11 +540,10 @@ int launch_rope_shift_jobs(const vlc_shift_job* jobs, int n_jobs, int64_t max_n_
                            const RopeFreq& f, int dtype, hipStream_t st) {
   if (n_jobs <= 0 || max_n_tok <= 0) return VLC_OK;
   const int vec = dtype == VLC_BF16 ? 8 : 4;
-  const int head_parts = max_n_tok * n_jobs * ((D / 2) / vec) < (int64_t)kThreads * 1024 ? Hkv : 1;
-  const int64_t threads = max_n_tok * head_parts * ((D / 2) / vec);
+  const int64_t threads = max_n_tok * Hkv * ((D / 2) / vec);
   const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads), (unsigned)n_jobs);
 #define VLC_LAUNCH_SHIFT(T, DD) \
-  hipLaunchKernelGGL((rope_shift_jobs_kernel<T, DD>), grid, dim3(kThreads), 0, st, jobs, Hkv, head_parts, f)
+  hipLaunchKernelGGL((rope_shift_jobs_kernel<T, DD>), grid, dim3(kThreads), 0, st, jobs, Hkv, f)
   if (dtype == VLC_BF16 && D == 128) VLC_LAUNCH_SHIFT(uint16_t, 128);
   else if (dtype == VLC_BF16 && D == 64) VLC_LAUNCH_SHIFT(uint16_t, 64);
   else if (dtype == VLC_F32 && D == 128) VLC_LAUNCH_SHIFT(float, 128);
@@ -587,22 +566,13 @@ int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t
   const int64_t split_stride = n * (int64_t)(Hq + 2 * Hkv) * D;
   const int vec = dtype == VLC_BF16 ? 8 : 4;
   const int heads = Hq + 2 * Hkv;
-  // Four heads per thread reuse each sine/cosine; with few rows one head per thread keeps the
-  // grid large enough to cover the chip.
-  const bool wide = n * ((heads + 3) / 4) * ((D / 2) / vec) >= (int64_t)kThreads * 2048;
-  const int hb = wide ? 4 : 1;
-  const int head_blocks = (heads + hb - 1) / hb;
-  const int64_t threads = n * head_blocks * ((D / 2) / vec);
+  const int64_t threads = n * heads * ((D / 2) / vec);
   const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads));
-#define VLC_LAUNCH_RQS2(T, DD, SUM, HB)                                                               \
-  hipLaunchKernelGGL((rope_qk_scatter_kernel<T, DD, HB, SUM>), grid, dim3(kThreads), 0, st,           \
+#define VLC_LAUNCH_RQS(T, DD, SUM)                                                                    \
+  hipLaunchKernelGGL((rope_qk_scatter_kernel<T, DD, SUM>), grid, dim3(kThreads), 0, st,               \
                      SUM ? partials : qkv32, splits, split_stride, (const uint16_t*)bias,             \
                      const_cast<float*>(qkv32), pos, pos3, (const T*)w_qnorm, (const T*)w_knorm, eps, \
-                     slot, n, Hq, Hkv, head_blocks, f, (uint4*)q_out, (uint4*)k_cache, (uint4*)v_cache)
-#define VLC_LAUNCH_RQS(T, DD, SUM)                                                                    \
-  do {                                                                                                \
-    if (wide) VLC_LAUNCH_RQS2(T, DD, SUM, 4); else VLC_LAUNCH_RQS2(T, DD, SUM, 1);                    \
-  } while (0)
+                     slot, n, Hq, Hkv, f, (uint4*)q_out, (uint4*)k_cache, (uint4*)v_cache)
   if (splits > 1 && D == 128) VLC_LAUNCH_RQS(uint16_t, 128, true);
   else if (splits > 1 && D == 64) VLC_LAUNCH_RQS(uint16_t, 64, true);
   else if (dtype == VLC_BF16 && D == 128) VLC_LAUNCH_RQS(uint16_t, 128, false);
@@ -610,7 +580,6 @@ int launch_rope_qk_scatter(const float* qkv32, const int32_t* pos, const int32_t
   else if (dtype == VLC_F32 && D == 128) VLC_LAUNCH_RQS(float, 128, false);
   else if (dtype == VLC_F32 && D == 64) VLC_LAUNCH_RQS(float, 64, false);
   else return fail(VLC_ERR_SHAPE, "rope+scatter: unsupported D=%d", D);
-#undef VLC_LAUNCH_RQS2
 #undef VLC_LAUNCH_RQS
   VLC_CHECK_LAUNCH("rope_qk_scatter");
   return VLC_OK;
