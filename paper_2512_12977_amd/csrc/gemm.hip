@@ -95,6 +95,14 @@ __device__ __forceinline__ int fswz(int row) { return (row & 7) ^ ((row >> 3) & 
 // offsets never change, the base moves along k with scalar adds, so the k-loop holds no vector address arithmetic
 // (a vector instruction of a wavefront does not overlap with its own MFMAs).
 __device__ __forceinline__ void dma16(const void* uniform_base, uint32_t lane_byte_off, uint32_t lds_byte_addr) {
+#ifdef VLC_ABLATE_GEMM_COPIES   // measurement build: no operand ever reaches LDS (results wrong, timing only)
+  return;
+#endif
+#ifdef VLC_ABLATE_GEMM_LDS_WRITES   // measurement build: the same loads, into a register nobody reads instead of LDS
+  u32x4 sink;
+  asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(sink) : "v"(lane_byte_off), "s"(uniform_base) : "memory");
+  return;
+#endif
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_byte_addr), "v"(lane_byte_off), "s"(uniform_base)
@@ -226,8 +234,13 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   (lds_base + (uint32_t)(((stage_) * STAGE_CHUNKS +                                                           \
                           ((i_) < A_INSTR ? wave * A_INSTR * 64 + (i_) * 64                                  \
                                           : BM * 8 + wave * W_INSTR * 64 + ((i_) - A_INSTR) * 64)) * 16))
+#ifdef VLC_ABLATE_GEMM_COPY_MISSES   // measurement build: every copy re-reads the tile's first two k-tiles (cache hits)
+#define VLC_DMA_KT(kt_) ((kt_) & 1)
+#else
+#define VLC_DMA_KT(kt_) (kt_)
+#endif
 #define VLC_DMA(kt_, i_, stage_)                                                                              \
-  dma16(((i_) < A_INSTR ? a_base : w_base) + (kt_) * BK,                                                \
+  dma16(((i_) < A_INSTR ? a_base : w_base) + VLC_DMA_KT(kt_) * BK,                                                \
         (i_) < A_INSTR ? a_lane[(i_) < A_INSTR ? (i_) : 0] : w_lane[(i_) >= A_INSTR ? (i_) - A_INSTR : 0],     \
         VLC_LDS_DST(stage_, i_))
 #define VLC_ISSUE(kt_, stage_) _Pragma("unroll") for (int i = 0; i < LOADS; ++i) VLC_DMA(kt_, i, stage_);
@@ -270,8 +283,8 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
   {                                                                                                           \
     const u32x4* st_ = lds + (cst_) * STAGE_CHUNKS;                                                           \
     bf16x8 wf[2][NT], af[2][MT];                                                                              \
-    _Pragma("unroll") for (int nt = 0; nt < NT; ++nt) wf[0][nt] = __builtin_bit_cast(bf16x8, st_[w_off[nt][0]]); \
-    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) af[0][mt] = __builtin_bit_cast(bf16x8, st_[a_off[mt][0]]); \
+    _Pragma("unroll") for (int nt = 0; nt < NT; ++nt) wf[0][nt] = __builtin_bit_cast(bf16x8, VLC_GEMM_FRAG(st_[w_off[nt][0]])); \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) af[0][mt] = __builtin_bit_cast(bf16x8, VLC_GEMM_FRAG(st_[a_off[mt][0]])); \
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                       \
       _Pragma("unroll") for (int g = 0; g < G; ++g) {                                                         \
         if (WITH_LOADS) {                                                                                     \
@@ -281,8 +294,8 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
         if (ks + 1 < KS) {                                                                                    \
           _Pragma("unroll") for (int f = 0; f < NF; ++f) {                                                    \
             if (f * G / NF == g) {                                                                            \
-              if (f < NT) wf[(ks + 1) & 1][f < NT ? f : 0] = __builtin_bit_cast(bf16x8, st_[w_off[f < NT ? f : 0][ks + 1]]); \
-              else af[(ks + 1) & 1][f >= NT ? f - NT : 0] = __builtin_bit_cast(bf16x8, st_[a_off[f >= NT ? f - NT : 0][ks + 1]]); \
+              if (f < NT) wf[(ks + 1) & 1][f < NT ? f : 0] = __builtin_bit_cast(bf16x8, VLC_GEMM_FRAG(st_[w_off[f < NT ? f : 0][ks + 1]])); \
+              else af[(ks + 1) & 1][f >= NT ? f - NT : 0] = __builtin_bit_cast(bf16x8, VLC_GEMM_FRAG(st_[a_off[f >= NT ? f - NT : 0][ks + 1]])); \
             }                                                                                                 \
           }                                                                                                   \
         }                                                                                                     \
@@ -297,6 +310,34 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
     }                                                                                                         \
   }
 
+#if defined(VLC_ABLATE_GEMM_COPIES) || defined(VLC_ABLATE_GEMM_LDS_WRITES)
+  // measurement build: the ring is filled once with pseudo-random finite bf16 values (so that the MFMAs draw the power
+  // of a real product) and no copy is ever issued
+  for (int i = tid; i < STAGES * STAGE_CHUNKS; i += NW * 64) {
+    uint32_t h = (uint32_t)i * 2654435761u + blockIdx.x * 40503u;
+    u32x4 v;
+    for (int e = 0; e < 4; ++e) {
+      h ^= h >> 13; h *= 0x5bd1e995u; h ^= h >> 15;
+      v[e] = (h & 0x807f807fu) | 0x3f003f00u;
+    }
+    lds[i] = v;
+  }
+  __syncthreads();
+#endif
+#ifdef VLC_ABLATE_GEMM_FRAG_READS
+  // measurement build: every MFMA operand is one register-resident pseudo-random fragment, nothing is read from LDS
+  u32x4 frag_rand;
+  {
+    uint32_t h = (uint32_t)tid * 2654435761u + 12345u;
+    for (int e = 0; e < 4; ++e) {
+      h ^= h >> 13; h *= 0x5bd1e995u; h ^= h >> 15;
+      frag_rand[e] = (h & 0x807f807fu) | 0x3f003f00u;
+    }
+  }
+#define VLC_GEMM_FRAG(x_) frag_rand
+#else
+#define VLC_GEMM_FRAG(x_) (x_)
+#endif
   // prologue: fill STAGES-1 stages
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
@@ -329,6 +370,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
 #undef VLC_DMA
 #undef VLC_LDS_DST
 #undef VLC_COMPUTE_TILE
+#undef VLC_GEMM_FRAG
 
   // ---- tail tile: raw accumulators as a float block [BN/4][BM][4] (lanes of consecutive m write 512 contiguous bytes)
   if constexpr (EPI != EPI_PARTIAL) {
@@ -404,6 +446,9 @@ __global__ __launch_bounds__(WGM * WGN * 64, OCC) void gemm_bf16_kernel(
           uint2 o;
           o.x = pack_bf16x2(v[0], v[1]);
           o.y = pack_bf16x2(v[2], v[3]);
+#ifdef VLC_ABLATE_GEMM_STORES   // measurement build: the SwiGLU epilogue computes, and stores only what can never occur
+          if (EPI == EPI_SWIGLU && o.x != 0x7fc17fc1u) continue;   // (its own inputs stay what they are; only the product after it sees stale data)
+#endif
           *reinterpret_cast<uint2*>(C + (int64_t)m * ldc + n) = o;
         }
       }
