@@ -547,6 +547,11 @@ def main() -> int:
             continue
         r = roof(name, fl, by, us * 1e-6)
         kernels[name] = {k2: r[k2] for k2 in ("bound", "achieved", "peak", "unit", "frac", "avg_launch_us")}
+        if r["bound"] == "mfma" and r.get("algorithmic_bytes_per_launch"):
+            # a contraction's other roofline: its operands and output once through HBM (what bounds it at few rows)
+            gbs = r["algorithmic_bytes_per_launch"] / (us * 1e-6) / 1e9
+            kernels[name]["hbm_gbs"] = round(gbs, 1)
+            kernels[name]["hbm_frac"] = round(gbs / PEAK_HBM_GBS, 4)
     if shift_all_us is not None:
         by = float(sum(stage_work(sh, plans.n_rows[l], plans.n_reuse[l], pairs[l])["rope_shift"][1] for l in range(L)))
         ach = by / (shift_all_us * 1e-6) / 1e9
