@@ -8,6 +8,8 @@ cases use the Qwen3-VL-shaped layer with random frequency sections and images as
 layer's h, K and V are compared with the oracle element by element at the stated tolerance (fp32: free running;
 bf16: each layer fed the oracle's previous output, as the tolerance is a per-layer statement).
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -24,7 +26,7 @@ def random_workload(seed):
     D = 128 if bf16 else int(rng.choice([64, 128]))
     Hkv = int(rng.choice([1, 2, 3]))
     g = int(rng.choice([1, 2, 3, 4, 7, 8]))
-    grid = seed >= 24       # the Qwen3-VL-shaped layer: q/k norm, three position ids per token, images as grids
+    grid = seed % 36 >= 24  # the Qwen3-VL-shaped layer: q/k norm, three position ids per token, images as grids
     extra = {}
     if grid:
         h_sec = int(rng.integers(0, D // 4 + 1))
@@ -66,7 +68,10 @@ def random_workload(seed):
     return wl, k
 
 
-@pytest.mark.parametrize("seed", range(36))
+N_SEEDS = int(os.environ.get("VLC_RANDOM_LAYOUTS", "36"))   # more seeds for a longer soak of the same check
+
+
+@pytest.mark.parametrize("seed", range(N_SEEDS))
 def test_random_shape_and_layout_against_oracle(seed):
     wl, k = random_workload(seed)
     sh, L = wl.shape, 3
@@ -85,3 +90,24 @@ def test_random_shape_and_layout_against_oracle(seed):
         assert_close(got[l][1], cat(l, "K"), sh.dtype, "%s layer %d K" % (what, l))
         assert_close(got[l][2], cat(l, "V"), sh.dtype, "%s layer %d V" % (what, l))
         assert_close(got[l][0], cat(l, "h"), sh.dtype, "%s layer %d h" % (what, l))
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_row_counts_at_mid_sized_shapes_stage_by_stage(seed):
+    """One bf16 layer at shapes between the tiny and the 7B ones (H 1024-2048, MLP width 2048-6144), with 1-2600
+    recomputed rows: the GEMM dispatcher's choices (tile, k ranges, split of the last round) and the attention's
+    key-range split change with every case.  Every stage is compared with the oracle on the GPU's own inputs."""
+    from test_gpu_layer import check_layer_stage_by_stage
+    rng = np.random.default_rng(9000 + seed)
+    Hkv = int(rng.choice([1, 2, 4]))
+    g = int(rng.choice([1, 2, 4, 7]))
+    shape = syn.Shape("mid%d" % seed, L=1, H=256 * int(rng.integers(4, 9)), Hq=Hkv * g, Hkv=Hkv, D=128,
+                      I=256 * int(rng.integers(8, 25)), rope_base=1e6, dtype="bf16", qkv_bias=bool(rng.integers(2)))
+    n_text = int(rng.integers(1, 1200))
+    T = int(rng.integers(16, 3000))
+    k = int(rng.integers(0, 501))
+    segs = syn.workloads._layout([("text", n_text // 2 + 1), ("image", T, int(rng.integers(0, 4000)), 0), ("text", n_text - n_text // 2)])
+    wl = syn.Workload("mid%d" % seed, shape, [syn.Request(segs, 0, pos_start=int(rng.integers(0, 2000)))], T, "static",
+                      static_k=k, seed=200 + seed)
+    dev, floor = check_layer_stage_by_stage(wl)
+    assert dev <= floor
