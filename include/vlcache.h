@@ -250,7 +250,7 @@ typedef struct {
   int32_t mrope_t, mrope_h, mrope_w;
   /* Mixture-of-experts MLP (the Qwen3-VL-30B-A3B model of Sec. 5.1): n_experts > 0 replaces the MLP
    * by n_experts SwiGLU experts of width I each, of which every row uses top_k (1 <= top_k <= 16,
-   * n_experts <= 256): router scores row . w_router^T, the top_k largest (equal scores: lower index
+   * n_experts <= 256, in bf16 a multiple of 4): router scores row . w_router^T, the top_k largest (equal scores: lower index
    * first), weights = softmax over all experts renormalised over the chosen ones; the experts'
    * output rows are rounded to the storage type and summed in float.  0: one dense MLP. */
   int32_t n_experts, top_k;

@@ -72,6 +72,8 @@ int check_shape(const vlc_layer_shape* s, const char* who) {
   if (s->n_experts < 0 || s->top_k < 0 || (s->n_experts > 0 && (s->n_experts > 256 || s->top_k < 1 || s->top_k > 16 ||
                                                                s->top_k > s->n_experts)))
     return fail(VLC_ERR_SHAPE, "%s: n_experts=%d (0..256), top_k=%d (1..16, <= n_experts)", who, s->n_experts, s->top_k);
+  if (s->dtype == VLC_BF16 && s->n_experts % 4)   // the router scores leave the MFMA GEMM four columns per lane
+    return fail(VLC_ERR_SHAPE, "%s: n_experts=%d must be a multiple of 4 in bf16", who, s->n_experts);
   return VLC_OK;
 }
 

@@ -223,3 +223,27 @@ def test_moe_more_pairs_than_2_gib_of_input_rows():
     assert_close(act, r["act"], sh.dtype, "SwiGLU product of the chosen experts")
     assert_close(y, r["y"], sh.dtype, "expert outputs")
     assert_close(back(h_out[sel_t]), st(h1 + r["mlp"]), sh.dtype, "weighted sum + residual")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_moe_random_expert_counts_widths_and_rows(seed):
+    """Seeded random mixture-of-experts layers: 3-48 experts, 1-6 per token, expert widths 64-512, 5-1500 rows, fp32 and
+    bf16 in turn - expert groups from empty to several row tiles, on all three tile sizes of the grouped GEMMs."""
+    rng = np.random.default_rng(11000 + seed)
+    bf16 = seed % 2 == 1
+    D = 128 if bf16 else 64
+    E = int(rng.integers(3, 49))
+    if bf16:
+        E = 4 * ((E + 3) // 4)          # bf16: the number of experts is a multiple of 4 (the library refuses others)
+    top_k = int(rng.integers(1, min(E, 6) + 1))
+    half = D // 2
+    h_sec, w_sec = int(rng.integers(0, half // 2 + 1)), int(rng.integers(0, half // 2 + 1))
+    sh = syn.Shape("moe_random%d" % seed, L=1, H=64 * int(rng.integers(2, 9)), Hq=4, Hkv=2, D=D, I=64 * int(rng.integers(1, 9)),
+                   rope_base=1e4, dtype="bf16" if bf16 else "f32", qkv_bias=False, qk_norm=True,
+                   mrope_section=(half - h_sec - w_sec, h_sec, w_sec), n_experts=E, top_k=top_k, text_scale=1.0,
+                   residual_proj_scale=0.01)
+    rows = int(rng.integers(5, 1500))
+    req = syn.Request([syn.Segment(0, rows, False)], 0, 0, syn.grid_positions([("text", rows)]))
+    wl = syn.Workload("moe_random%d" % seed, sh, [req], 1, "static", static_k=0, seed=300 + seed)
+    g = check_moe_layer(wl, 0)
+    assert g["moe_idx"].shape == (rows, top_k)

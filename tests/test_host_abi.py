@@ -279,7 +279,7 @@ def test_expert_fields_of_the_shape_and_layout():
     assert all(v >= 0 and v % 256 == 0 for v in vals) and vals == sorted(vals) and len(set(vals)) == len(vals)
     assert off["moe_idx"] - off["act"] >= 100 * 8 * 768 * 2          # the SwiGLU product holds one row per (row, expert) pair
     assert vlc.vlc_layer_workspace_bytes(moe, 100) > vlc.vlc_layer_workspace_bytes(make_shape(syn.SHAPES["q3vl_8b"]), 100) - (1 << 26)
-    for n_experts, top_k in ((257, 8), (8, 9), (8, 0), (8, 17), (-1, 0)):
+    for n_experts, top_k in ((257, 8), (8, 9), (8, 0), (8, 17), (-1, 0), (6, 2)):   # (6, 2): bf16 wants a multiple of 4
         bad = vlc.LayerShape(2048, 32, 4, 128, 768, vlc.VLC_BF16, 1e-6, 5e6, 24, 20, 20, n_experts, top_k)
         with pytest.raises(vlc.VlcError):
             vlc.vlc_layer_workspace_bytes(bad, 10)
