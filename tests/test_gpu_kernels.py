@@ -82,6 +82,49 @@ def test_rope_shift_kv_vs_oracle(dtype, Hkv, D, base):
     np.testing.assert_array_equal(back(d_k)[dst[0]], stored(ks, dtype)[src[0]])
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_streaming_entry_points_random_sizes(seed):
+    """RoPE shift, gather and scatter on seeded random sizes: 1-8 kv heads, head dimension 64 or 128, 1-6000 tokens or
+    rows, row widths that are any multiple of 8 elements, deltas up to +-2^20 positions, both storage types."""
+    rng = np.random.default_rng(15000 + seed)
+    dtype = "bf16" if seed % 2 else "f32"
+    Hkv, D = int(rng.integers(1, 9)), int(rng.choice([64, 128]))
+    base = float(rng.choice([1e4, 1e6, 5e6]))
+    n = int(rng.integers(1, 6000))
+    pool, S = n + int(rng.integers(0, 500)), n + int(rng.integers(0, 500))
+    ks = rng.standard_normal((pool, Hkv, D)).astype(np.float32)
+    vs = rng.standard_normal((pool, Hkv, D)).astype(np.float32)
+    src, dst = rng.permutation(pool)[:n], rng.permutation(S)[:n]
+    delta = rng.integers(-(1 << 20), 1 << 20, size=n)
+    d_k = torch.zeros((S, Hkv, D), device=DEV, dtype=TD[dtype])
+    d_v = torch.zeros((S, Hkv, D), device=DEV, dtype=TD[dtype])
+    vlc.vlc_rope_shift_kv(to_dev(ks, dtype), to_dev(vs, dtype), d_k, d_v, i32(src), i32(dst), i32(delta), base)
+    torch.cuda.synchronize()
+    want_k, want_v = np.zeros((S, Hkv, D)), np.zeros((S, Hkv, D))
+    want_k[dst] = orc.STORE[dtype](orc.rope_rotate(stored(ks, dtype)[src], delta, base))
+    want_v[dst] = stored(vs, dtype)[src]
+    assert_close(back(d_k), want_k, dtype, "shifted K (seed %d: %d tokens, %d heads of %d)" % (seed, n, Hkv, D))
+    np.testing.assert_array_equal(back(d_v), want_v)
+    # scatter of fresh rows into the same caches, gather of rows of a matrix of odd width: bit-exact
+    m = int(rng.integers(1, n + 1))
+    kn = rng.standard_normal((m, Hkv, D)).astype(np.float32)
+    vn = rng.standard_normal((m, Hkv, D)).astype(np.float32)
+    rows = rng.permutation(S)[:m]
+    vlc.vlc_scatter_kv(to_dev(kn, dtype), to_dev(vn, dtype), i32(rows), d_k, d_v)
+    elems = 8 * int(rng.integers(1, 700))
+    x = rng.standard_normal((pool, elems)).astype(np.float32)
+    idx = rng.integers(0, pool, size=m)
+    out = torch.empty((m, elems), device=DEV, dtype=TD[dtype])
+    vlc.vlc_gather_rows(to_dev(x, dtype), i32(idx), out)
+    torch.cuda.synchronize()
+    want_k2, want_v2 = back(d_k).copy(), back(d_v).copy()
+    np.testing.assert_array_equal(back(d_k)[rows], stored(kn, dtype))
+    np.testing.assert_array_equal(back(d_v)[rows], stored(vn, dtype))
+    keep = np.setdiff1d(np.arange(S), rows)
+    np.testing.assert_array_equal(back(d_v)[keep], want_v[keep])          # rows not scattered to are untouched
+    np.testing.assert_array_equal(back(out), stored(x, dtype)[idx])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_rope_shift_in_place_and_inverse(dtype):
     """In-place use, and shift(d) followed by shift(-d) returns the keys (to storage rounding)."""
@@ -257,6 +300,31 @@ def test_attention_long_context_bf16():
 def test_attention_many_rows(Hq, Hkv, reqs):
     """Thousands of rows, several requests, more than 512 workgroups."""
     attention_case("bf16", Hq, Hkv, 128, reqs, seed=31)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_attention_random_heads_requests_and_rows(seed):
+    """Seeded random head layouts (1-8 kv heads, 1-16 query heads per kv head), 1-5 packed requests of 1-3000 slots,
+    rows that are runs, scattered slots, duplicates and zero-length rows in any order; fp32 (D 64 or 128) and bf16."""
+    rng = np.random.default_rng(13000 + seed)
+    dtype = "bf16" if seed % 3 else "f32"
+    D = 128 if dtype == "bf16" else int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+    g = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16]))
+    reqs = []
+    for _ in range(int(rng.integers(1, 6))):
+        S = int(rng.integers(1, 3000 if dtype == "bf16" else 700))
+        kind = int(rng.integers(0, 4))
+        if kind == 0:      # a trailing run (the text behind the images)
+            slots = list(range(max(0, S - int(rng.integers(1, 200))), S))
+        elif kind == 1:    # scattered slots, unsorted, with duplicates
+            slots = [int(x) for x in rng.integers(0, S, size=int(rng.integers(1, 150)))]
+        elif kind == 2:    # leading runs of several "images" and a zero-length row
+            slots = [-1] + [s for b in range(0, S, max(1, S // 5)) for s in range(b, min(S, b + int(rng.integers(1, 40))))]
+        else:              # every slot
+            slots = list(range(S)) if S <= 1200 else list(range(0, S, 3))
+        reqs.append((S, slots))
+    attention_case(dtype, Hkv * g, Hkv, D, reqs, seed=seed)
 
 
 def test_attention_errors():
