@@ -67,6 +67,21 @@ def test_first_token_small(name):
     check(h, [5, 9, 60, 1, 2, 33, 34, 35, 8, 7, 6], Wh, shape)    # more than 8 requests: the GEMM path
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_first_token_random_widths_vocabularies_and_batches(seed):
+    """Seeded random heads: H 64-2048 (multiples of 64), vocabularies of 4-9000 entries (multiples of 4, so also fewer
+    entries than one tile and than the 64 slices of the greedy choice), 1-70 requests whose rows repeat and come in any order."""
+    import dataclasses
+    rng = np.random.default_rng(17000 + seed)
+    base = syn.SHAPES["tiny_bf16" if seed % 2 else "tiny"]
+    shape = dataclasses.replace(base, H=64 * int(rng.integers(1, 33)), vocab=4 * int(rng.integers(1, 2251)))
+    Wh = syn.head_weights(shape, 400 + seed)
+    n = int(rng.integers(1, 300))
+    h = rng.standard_normal((n, shape.H)).astype(np.float32)
+    rows = [int(r) for r in rng.integers(0, n, size=int(rng.integers(1, 71)))]
+    check(h, rows, Wh, shape)
+
+
 def test_first_token_equal_scores_take_lowest_index():
     shape = syn.SHAPES["tiny_bf16"]
     Wh = syn.head_weights(shape, 33)
