@@ -18,6 +18,10 @@
  *     of a call (weights included).  Index arrays are int32.
  *   - K/V storage is token-major: [rows, Hkv, D] per layer.  Linear weights use the
  *     [out_features, in_features] layout.
+ *   - Device functions launch kernels and nothing else (no allocation, no synchronisation, no memset
+ *     node), so their calls can be recorded into a HIP graph.  The first launch of a kernel variant
+ *     on a device sets one attribute of that kernel (its dynamic LDS size, once per device and
+ *     kernel, thread-safe): run the calls once eagerly, as a warm-up, before capturing them.
  *   - A call with zero rows is a no-op that returns VLC_OK.
  *   - Contents of device index arrays are the caller's contract (in range; scatter targets
  *     unique); the host-side builders below produce arrays that satisfy it.
