@@ -68,6 +68,9 @@ __device__ __forceinline__ int v_swz(int key, int c) { return c ^ ((key & 3) << 
 // tracked only by the explicit waits at the end of each key block (the key loop has no other
 // vector-memory instruction).  M0 holds the LDS address and is written right before each use.
 __device__ __forceinline__ void dma16(const void* gptr, u32x4* lds_dst) {
+#ifdef VLC_ABLATE_ATT_COPIES   // measurement build: no K/V tile ever reaches LDS (the rings hold pseudo-random values)
+  return;
+#endif
   const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_dst;
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                :
@@ -92,7 +95,7 @@ __device__ __forceinline__ float pair_sum(float v) {
 // Measurement variants (python -m paper_2512_12977_amd.build --tag T --define VLC_ABLATE_...): each takes one
 // ingredient of the key loop out - the results are wrong, only the timing is of interest - to show what that
 // ingredient costs: the K or V^T fragment reads from LDS (all or every other one), the exponentials, the scale-and-subtract
-// in front of them, the S^T or the PV MFMAs, the workgroup barrier of a key block.
+// in front of them, the S^T or the PV MFMAs, the workgroup barrier of a key block, the K/V copies into LDS.
 #ifdef VLC_ABLATE_K_READS
 #define VLC_ATT_KFRAG(expr_) (u32x4{(uint32_t)lane, 0x3c003c00u, (uint32_t)wave, 0x3c003c00u})
 #else
@@ -164,6 +167,18 @@ __global__ __launch_bounds__(256, RT == 1 ? 2 : 1) void attention_bf16_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, x = lane >> 5;
+#ifdef VLC_ABLATE_ATT_COPIES
+  // pseudo-random finite bf16 values, so that the MFMAs draw the power of a real product
+  for (int i = tid; i < 2 * ATT_STAGE_CHUNKS; i += 256) {
+    uint32_t h = (uint32_t)i * 2654435761u + blockIdx.x * 40503u;
+    u32x4 v;
+    for (int e = 0; e < 4; ++e) {
+      h ^= h >> 13; h *= 0x5bd1e995u; h ^= h >> 15;
+      v[e] = (h & 0x807f807fu) | 0x3f003f00u;
+    }
+    lds[i] = v;
+  }
+#endif
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The remap hands every XCD
   // one contiguous range of (kv head, row tile) pairs, so the workgroups resident on an XCD at the
   // same time are neighbouring row tiles of one request and kv head and stream the same K/V.
